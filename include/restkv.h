@@ -1,0 +1,157 @@
+/*
+ * restkv.h -- C ABI of the ReST-KV eviction path for AMD MI355X (gfx950).
+ *
+ * One call sequence compresses the KV cache of ONE transformer layer at prefill
+ * time (the paper evicts once, after prefill; App. B):
+ *
+ *     restkv_prepare_wo   (once per layer's weights, not per request)
+ *     restkv_score   ->  restkv_smooth  ->  restkv_select  ->  restkv_compact
+ *
+ * Notation (0-indexed): Hq query heads, Hkv KV heads, G = Hq/Hkv, d head_dim,
+ * L cached tokens, W observation-window queries (the last W positions),
+ * P = L - W evictable prefix tokens, B per-KV-head budget (the W window tokens
+ * are always kept and count towards B).
+ *
+ * Pointers: every pointer argument except the parameter block is a DEVICE
+ * pointer owned by the caller; the parameter block is a HOST pointer that is
+ * read before the call returns.  The library allocates nothing, frees nothing
+ * and never synchronises: each call validates its arguments on the host,
+ * enqueues kernels on `stream` (a hipStream_t; NULL = the default stream) and
+ * returns.  Scratch memory comes from the caller as `workspace` of at least
+ * restkv_workspace_bytes() bytes, 256-byte aligned; its contents are undefined
+ * between calls and calls that share a workspace must be ordered on one stream.
+ *
+ * Errors: every entry point returns RESTKV_OK (0) or a negative code; nothing is
+ * enqueued when an error is returned, except RESTKV_EHIP, which reports a launch
+ * failure of the HIP runtime and may leave earlier kernels of that call queued.
+ * No entry point throws, aborts or prints.
+ *
+ * Design readings that the paper leaves open and no independent check can pin
+ * ("parity unpinned"): the mean over the G query heads of a KV head (score), and
+ * the way the fixed kernel size k widens under the adaptive window (smooth).
+ */
+#ifndef RESTKV_H_
+#define RESTKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RESTKV_OK            0
+#define RESTKV_EINVAL       (-1)  /* null pointer, inconsistent shape, budget outside (W, L], ... */
+#define RESTKV_EUNSUPPORTED (-2)  /* head_dim not in {64,128}, unknown dtype, G*W too large ...   */
+#define RESTKV_EWORKSPACE   (-3)  /* workspace missing, misaligned or too small                   */
+#define RESTKV_EHIP         (-4)  /* the HIP runtime refused a launch                             */
+
+#define RESTKV_F32  0   /* q, k, v and the compacted cache are IEEE binary32 */
+#define RESTKV_BF16 1   /* ... are bfloat16                                   */
+
+typedef void* restkv_stream_t;    /* a hipStream_t */
+
+/*
+ * Problem statement of one layer (Sec. 3.2, Definition 3.1: the layer's cache
+ * <K_T, V_T>, the recent queries, the head's output projection and the budget B).
+ */
+typedef struct restkv_params {
+  int32_t n_q_heads;     /* Hq                                                         */
+  int32_t n_kv_heads;    /* Hkv, divides Hq                                            */
+  int32_t head_dim;      /* d: 64 or 128                                               */
+  int32_t seq_len;       /* L                                                          */
+  int32_t window;        /* W = S_w, 1 <= W < L                                        */
+  int32_t budget;        /* B, W < B <= L                                              */
+  int32_t dtype;         /* RESTKV_F32 or RESTKV_BF16                                  */
+  int32_t causal;        /* 1: window query i sees keys 0 .. L-W+i ; 0: all L keys     */
+  float   scale;         /* logit scale; 0 selects 1/sqrt(d) (Eq. softmax)             */
+  float   ema_alpha;     /* alpha of the EMA recursion: weight of the newest query     */
+  int32_t base_window;   /* k: odd >= 1, the fixed kernel size of App. B               */
+  int32_t adaptive;      /* 1: W_s and gamma_shift from D_front/D_rear ; 0: W_s=k, 0   */
+  float   beta;          /* scaling factor of the adaptive window (> 0 when adaptive)  */
+  int32_t reserved;      /* must be 0                                                  */
+  int64_t q_stride_h;    /* elements between query heads  (0: W*d)                     */
+  int64_t q_stride_t;    /* elements between window queries (0: d)                     */
+  int64_t kv_stride_h;   /* elements between KV heads     (0: L*d)                     */
+  int64_t kv_stride_t;   /* elements between tokens       (0: d); rows are d-contiguous*/
+  int64_t ld_score;      /* row stride (floats) of score / ema / final (0: P; >= P)    */
+} restkv_params;
+
+/* Bytes of scratch the four calls below need for these parameters (0 if invalid). */
+size_t restkv_workspace_bytes(const restkv_params* p);
+
+/*
+ * Gram matrices of the per-head output projection (Eq. mha: MHA = z W_O, with W_O
+ * the head's rows of the layer's projection).  The indicator only needs
+ * ||x W_O^h||_2, which depends on M_h = W_O^h W_O^hT alone.
+ *   w_o   [Hq*d, d_model] float32, row-major, "z @ W_O" orientation: rows
+ *         h*d .. (h+1)*d-1 belong to query head h (a framework weight stored
+ *         [out,in] must be passed transposed).
+ *   gram  [Hq, d, d] float32 out.
+ * Weight-only: run once per layer, not per request.  Accumulates in float64.
+ */
+int restkv_prepare_wo(const restkv_params* p, const float* w_o, int64_t d_model,
+                      float* gram, restkv_stream_t stream);
+
+/*
+ * Layer-wise reconstruction indicator (Sec. 3.2, Eq. rec_ei; derivation App. A):
+ * for every query head h, window query i and prefix token n
+ *     I[h,i,n] = A[n] / (1 - A[n]) * || (z_{h,i} - v_n) W_O^h ||_2 ,
+ * A = softmax(scale * q_{h,i} K^T) over the visible keys (Eq. softmax), z = A V.
+ * The token holding the largest weight of a query is evaluated by the equivalent
+ * leave-one-out form (Eq. ori with Eq. relation), which stays finite as A -> 1.
+ * Output is the mean over the G query heads of each KV head:
+ *     score[g,i,n] = (1/G) sum_{h in g} I[h,i,n]          [Hkv, W, ld_score] float32
+ *   q     [Hq, W, d]  (strides q_stride_*),  k, v  [Hkv, L, d] (strides kv_stride_*)
+ *   gram  [Hq, d, d] from restkv_prepare_wo, or NULL for W_O W_O^T = identity.
+ * Columns n >= P of `score` are not written.
+ */
+int restkv_score(const restkv_params* p, const void* q, const void* k, const void* v,
+                 const float* gram, float* score, void* workspace, size_t workspace_bytes,
+                 restkv_stream_t stream);
+
+/*
+ * Spatial-temporal smoothing (Sec. 3.3).
+ *   ema[g,n]   = EMA over the W window queries of score[g,:,n] (newest weighs alpha)
+ *   D_front/D_rear = mean index of the per-query top-min(B,P) tokens of the raw
+ *                score, over the first floor(W/2) / the remaining queries
+ *   W_s   = k + 2 floor(|D_rear - D_front| / beta)
+ *   gamma = floor((D_front - D_rear)/beta) (+1 unless D_front - D_rear > 0)
+ *   final[g,n] = (1/W_s) sum_{j=-floor(W_s/2)+gamma}^{floor(W_s/2)+gamma} ema[g,n+j]
+ *                (Eq. final_ei; terms outside [0,P) are zero)
+ * adaptive = 0 or W = 1 gives W_s = k, gamma = 0.
+ *   score [Hkv, W, ld] in;  ema [Hkv, ld] out (may be NULL: kept in workspace);
+ *   final [Hkv, ld] out;  aws_info [Hkv, 2] int32 out = {W_s, gamma} (may be NULL);
+ *   aws_d [Hkv, 2] float64 out = {D_front, D_rear} (may be NULL).
+ */
+int restkv_smooth(const restkv_params* p, const float* score, float* ema, float* final_score,
+                  int32_t* aws_info, double* aws_d, void* workspace, size_t workspace_bytes,
+                  restkv_stream_t stream);
+
+/*
+ * Per-head selection (Sec. 3.3, Eq. topk): the B - W prefix tokens with the
+ * largest final[g, 0..P) (equal values: lower index wins), written in ascending
+ * position order and followed by the window tokens P .. L-1.
+ *   final [Hkv, ld] in;  idx [Hkv, B] int32 out.
+ */
+int restkv_select(const restkv_params* p, const float* final_score, int32_t* idx,
+                  void* workspace, size_t workspace_bytes, restkv_stream_t stream);
+
+/*
+ * Gather of the kept rows (Eq. topk): k_out[g,j,:] = k[g, idx[g,j], :], same for v.
+ *   idx [Hkv, B] int32 in, entries in [0, L) (an entry outside is written as zeros);
+ *   k_out, v_out [Hkv, B, d] out, contiguous, dtype of the inputs.
+ */
+int restkv_compact(const restkv_params* p, const void* k, const void* v, const int32_t* idx,
+                   void* k_out, void* v_out, restkv_stream_t stream);
+
+/* Static description of an error code. */
+const char* restkv_strerror(int code);
+
+/* Library version (major*10000 + minor*100 + patch). */
+int restkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RESTKV_H_ */

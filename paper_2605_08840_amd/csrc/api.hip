@@ -1,0 +1,159 @@
+// C ABI of the ReST-KV eviction library: argument validation, scratch layout, dispatch.
+// Everything behind these entry points is a hand-written HIP kernel for gfx950.
+#include <math.h>
+
+#include "common.hpp"
+
+namespace restkv {
+
+int resolve(const restkv_params* p, Prob* o) {
+  if (!p || !o) return RESTKV_EINVAL;
+  if (p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->n_q_heads % p->n_kv_heads) return RESTKV_EINVAL;
+  if (p->seq_len < 2 || p->window < 1 || p->window >= p->seq_len) return RESTKV_EINVAL;
+  if (p->budget <= p->window || p->budget > p->seq_len) return RESTKV_EINVAL;
+  if (p->base_window < 1 || !(p->base_window & 1)) return RESTKV_EINVAL;
+  if (p->reserved != 0) return RESTKV_EINVAL;
+  if (!(p->ema_alpha >= 0.f && p->ema_alpha <= 1.f)) return RESTKV_EINVAL;
+  if (p->adaptive && !(p->beta > 0.f)) return RESTKV_EINVAL;
+  if (!(p->scale >= 0.f) || isinf(p->scale)) return RESTKV_EINVAL;
+  if (p->head_dim != 64 && p->head_dim != 128) return RESTKV_EUNSUPPORTED;
+  if (p->dtype != RESTKV_F32 && p->dtype != RESTKV_BF16) return RESTKV_EUNSUPPORTED;
+  o->Hq = p->n_q_heads; o->Hkv = p->n_kv_heads; o->G = o->Hq / o->Hkv;
+  o->d = p->head_dim; o->L = p->seq_len; o->W = p->window; o->P = o->L - o->W;
+  o->B = p->budget; o->R = o->G * o->W;
+  if ((int64_t)o->G * o->W > 4096) return RESTKV_EUNSUPPORTED;
+  o->dtype = p->dtype; o->causal = p->causal ? 1 : 0; o->base_k = p->base_window;
+  o->adaptive = (p->adaptive && o->W >= 2) ? 1 : 0;
+  o->scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)o->d);
+  o->alpha = p->ema_alpha; o->beta = p->beta;
+  o->q_st = p->q_stride_t ? p->q_stride_t : o->d;
+  o->q_sh = p->q_stride_h ? p->q_stride_h : (int64_t)o->W * o->d;
+  o->kv_st = p->kv_stride_t ? p->kv_stride_t : o->d;
+  o->kv_sh = p->kv_stride_h ? p->kv_stride_h : (int64_t)o->L * o->d;
+  o->ld = p->ld_score ? p->ld_score : o->P;
+  if (o->q_st < o->d || o->kv_st < o->d || o->q_sh < 0 || o->kv_sh < 0 || o->ld < o->P) return RESTKV_EINVAL;
+  return RESTKV_OK;
+}
+
+ScoreWs score_ws(const Prob& pb) {
+  ScoreWs w;
+  // enough key splits to give every CU work, each at least one 64-key tile
+  int S = (pb.L + 1023) / 1024;
+  if (S < 1) S = 1;
+  if (S > 64) S = 64;
+  w.S = S;
+  const size_t rows = (size_t)pb.Hq * pb.W;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  w.part_m = take(rows * S * 4);
+  w.part_n = take(rows * S * 4);
+  w.part_l = take(rows * S * 4);
+  w.part_z = take(rows * S * (size_t)pb.d * 4);
+  w.rs_m = take(rows * 4);
+  w.rs_invl = take(rows * 4);
+  w.rs_zz = take(rows * 4);
+  w.rs_nstar = take(rows * 4);
+  w.rs_istar = take(rows * 4);
+  w.rs_u = take(rows * (size_t)pb.d * 4);
+  w.vv = take((size_t)pb.Hq * pb.P * 4);
+  w.bytes = off;
+  return w;
+}
+
+SmoothWs smooth_ws(const Prob& pb) {
+  SmoothWs w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  w.rowsum = take((size_t)pb.Hkv * pb.W * 8);
+  w.ema = take((size_t)pb.Hkv * pb.ld * 4);
+  w.bytes = off;
+  return w;
+}
+
+static int check_ws(const void* ws, size_t have, size_t need) {
+  if (!ws || ((uintptr_t)ws & 255u) || have < need) return RESTKV_EWORKSPACE;
+  return RESTKV_OK;
+}
+
+}  // namespace restkv
+
+using namespace restkv;
+
+extern "C" {
+
+size_t restkv_workspace_bytes(const restkv_params* p) {
+  Prob pb;
+  if (resolve(p, &pb) != RESTKV_OK) return 0;
+  const size_t a = score_ws(pb).bytes, b = smooth_ws(pb).bytes;
+  return a > b ? a : b;
+}
+
+int restkv_prepare_wo(const restkv_params* p, const float* w_o, int64_t d_model, float* gram,
+                      restkv_stream_t stream) {
+  Prob pb;
+  int rc = resolve(p, &pb);
+  if (rc) return rc;
+  if (!w_o || !gram || d_model < 1) return RESTKV_EINVAL;
+  return launch_gram(pb, w_o, d_model, gram, (hipStream_t)stream);
+}
+
+int restkv_score(const restkv_params* p, const void* q, const void* k, const void* v,
+                 const float* gram, float* score, void* workspace, size_t workspace_bytes,
+                 restkv_stream_t stream) {
+  Prob pb;
+  int rc = resolve(p, &pb);
+  if (rc) return rc;
+  if (!q || !k || !v || !score) return RESTKV_EINVAL;
+  const ScoreWs lay = score_ws(pb);
+  rc = check_ws(workspace, workspace_bytes, lay.bytes);
+  if (rc) return rc;
+  return launch_score_simple(pb, q, k, v, gram, score, (char*)workspace, lay, (hipStream_t)stream);
+}
+
+int restkv_smooth(const restkv_params* p, const float* score, float* ema, float* final_score,
+                  int32_t* aws_info, double* aws_d, void* workspace, size_t workspace_bytes,
+                  restkv_stream_t stream) {
+  Prob pb;
+  int rc = resolve(p, &pb);
+  if (rc) return rc;
+  if (!score || !final_score) return RESTKV_EINVAL;
+  const SmoothWs lay = smooth_ws(pb);
+  rc = check_ws(workspace, workspace_bytes, lay.bytes);
+  if (rc) return rc;
+  return launch_smooth(pb, score, ema, final_score, aws_info, aws_d, (char*)workspace, lay,
+                       (hipStream_t)stream);
+}
+
+int restkv_select(const restkv_params* p, const float* final_score, int32_t* idx, void* workspace,
+                  size_t workspace_bytes, restkv_stream_t stream) {
+  (void)workspace; (void)workspace_bytes;   // selection keeps its state in LDS
+  Prob pb;
+  int rc = resolve(p, &pb);
+  if (rc) return rc;
+  if (!final_score || !idx) return RESTKV_EINVAL;
+  return launch_select(pb, final_score, idx, (hipStream_t)stream);
+}
+
+int restkv_compact(const restkv_params* p, const void* k, const void* v, const int32_t* idx,
+                   void* k_out, void* v_out, restkv_stream_t stream) {
+  Prob pb;
+  int rc = resolve(p, &pb);
+  if (rc) return rc;
+  if (!k || !v || !idx || !k_out || !v_out) return RESTKV_EINVAL;
+  return launch_compact(pb, k, v, idx, k_out, v_out, (hipStream_t)stream);
+}
+
+const char* restkv_strerror(int code) {
+  switch (code) {
+    case RESTKV_OK: return "ok";
+    case RESTKV_EINVAL: return "invalid argument (null pointer, inconsistent shape or budget outside (W, L])";
+    case RESTKV_EUNSUPPORTED: return "unsupported configuration (head_dim must be 64 or 128; dtype f32 or bf16)";
+    case RESTKV_EWORKSPACE: return "workspace missing, not 256-byte aligned or smaller than restkv_workspace_bytes()";
+    case RESTKV_EHIP: return "HIP runtime error at kernel launch";
+    default: return "unknown error code";
+  }
+}
+
+int restkv_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,68 @@
+// Shared host/device declarations of the ReST-KV eviction library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "restkv.h"
+
+namespace restkv {
+
+// Resolved problem description: parameter block with defaults filled in.
+struct Prob {
+  int Hq, Hkv, G, d, L, W, P, B, R;   // R = G*W rows (queries) per KV head
+  int dtype, causal, base_k, adaptive;
+  float scale, alpha, beta;
+  int64_t q_sh, q_st, kv_sh, kv_st, ld;
+};
+
+// Fills `out`; returns RESTKV_OK or the error the block deserves.
+int resolve(const restkv_params* p, Prob* out);
+
+// ---- scratch layout ---------------------------------------------------------
+// All offsets are in bytes from the 256-byte aligned workspace base.
+struct ScoreWs {
+  int S;                 // key splits of the attention pass
+  size_t part_m, part_n, part_l, part_z;   // [Hkv*R*S] f32 / i32 / f32, [Hkv*R*S*d] f32
+  size_t rs_m, rs_invl, rs_zz, rs_nstar, rs_istar;   // [Hq*W]
+  size_t rs_u;           // [Hq*W*d] f32   u = z M_h
+  size_t vv;             // [Hq*P] f32     v_n M_h v_n^T
+  size_t bytes;
+};
+struct SmoothWs {
+  size_t rowsum;         // [Hkv*W] u64 index sums of the per-query top-B
+  size_t ema;            // [Hkv*ld] f32 (used when the caller passes ema == NULL)
+  size_t bytes;
+};
+ScoreWs score_ws(const Prob& pb);
+SmoothWs smooth_ws(const Prob& pb);
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// ---- launchers (each returns a RESTKV_* code) ---------------------------------
+int launch_gram(const Prob& pb, const float* w_o, int64_t d_model, float* gram, hipStream_t st);
+int launch_score_simple(const Prob& pb, const void* q, const void* k, const void* v,
+                        const float* gram, float* score, char* ws, const ScoreWs& lay,
+                        hipStream_t st);
+int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, int32_t* aws_info,
+                  double* aws_d, char* ws, const SmoothWs& lay, hipStream_t st);
+int launch_select(const Prob& pb, const float* fin, int32_t* idx, hipStream_t st);
+int launch_compact(const Prob& pb, const void* k, const void* v, const int32_t* idx, void* k_out,
+                   void* v_out, hipStream_t st);
+
+inline int hip_status() { return hipGetLastError() == hipSuccess ? RESTKV_OK : RESTKV_EHIP; }
+
+// ---- device helpers -----------------------------------------------------------
+struct bf16_t { uint16_t x; };
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16_t v) { return __uint_as_float(((uint32_t)v.x) << 16); }
+
+// Order-preserving map float -> uint32 (larger float <=> larger key; -0 < +0).
+__device__ __forceinline__ uint32_t float_key(float f) {
+  const uint32_t b = __float_as_uint(f);
+  return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
+}  // namespace restkv

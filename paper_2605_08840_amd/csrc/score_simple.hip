@@ -1,0 +1,401 @@
+// Reconstruction indicator, plain-FP32 kernels (vector ALU, LDS tiles).
+//
+// This is the path for float32 inputs (the small configuration) and the
+// arithmetic reference shape of the MFMA path: the same four stages, the same
+// scratch layout, every product in FP32.
+//
+//   attn_partial : per key split, online softmax over the visible keys of every
+//                  window query; the key with the largest logit so far (the
+//                  "champion") is kept OUT of the running sums, so that the sums
+//                  hold the attention of all the other keys relative to it.
+//   attn_combine : merges the splits; z, u = z M_h, zz = u.z, and the champion's
+//                  own indicator from its leave-one-out form (Eq. ori, Eq. relation).
+//   vv           : v_n M_h v_n^T for every prefix token and query head.
+//   score        : A/(1-A) * sqrt(zz - 2 u.v_n + vv) for all other tokens (Eq. rec_ei),
+//                  mean over the query heads of the group.
+#include "common.hpp"
+
+namespace restkv {
+
+namespace {
+
+constexpr int RB = 16;      // rows (queries) per block
+constexpr int TN = 32;      // keys per LDS tile
+constexpr float LOG2E = 1.4426950408889634f;
+
+// max / argmax (lowest key on ties) across the 16 lanes that share a row
+__device__ __forceinline__ void argmax16(float& v, int& i) {
+#pragma unroll
+  for (int o = 8; o >= 1; o >>= 1) {
+    const float ov = __shfl_xor(v, o, 16);
+    const int oi = __shfl_xor(i, o, 16);
+    if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+  }
+}
+__device__ __forceinline__ float sum16(float v) {
+#pragma unroll
+  for (int o = 8; o >= 1; o >>= 1) v += __shfl_xor(v, o, 16);
+  return v;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_attn_partial(Prob pb, const T* __restrict__ q,
+                                                      const T* __restrict__ k,
+                                                      const T* __restrict__ v, int S,
+                                                      float* __restrict__ part_m,
+                                                      int* __restrict__ part_n,
+                                                      float* __restrict__ part_l,
+                                                      float* __restrict__ part_z) {
+  __shared__ float Qs[RB][D];
+  __shared__ float Ks[TN][D + 1];
+  __shared__ float Vs[TN][D];
+  __shared__ float Ps[RB][TN];
+  constexpr int NC = D / 16;          // value columns per thread
+
+  const int s = blockIdx.x, g = blockIdx.z;
+  const int t = threadIdx.x, rl = t >> 4, ln = t & 15;
+  const int r = blockIdx.y * RB + rl;            // row inside the KV head
+  const bool row_ok = r < pb.R;
+  const int hl = row_ok ? r / pb.W : 0, i = row_ok ? r % pb.W : 0;
+  const int nvis = pb.causal ? pb.P + i + 1 : pb.L;
+  const T* kg = k + (int64_t)g * pb.kv_sh;
+  const T* vg = v + (int64_t)g * pb.kv_sh;
+
+  int kps = (pb.L + S - 1) / S;
+  kps = (kps + TN - 1) / TN * TN;
+  const int kbeg = s * kps;
+  const int kend = min(pb.L, kbeg + kps);
+
+  for (int x = t; x < RB * D; x += 256) {
+    const int rr = x / D, c = x % D;
+    const int rg = blockIdx.y * RB + rr;
+    float val = 0.f;
+    if (rg < pb.R) {
+      const int h = g * pb.G + rg / pb.W;
+      val = to_float(q[(int64_t)h * pb.q_sh + (int64_t)(rg % pb.W) * pb.q_st + c]);
+    }
+    Qs[rr][c] = val;
+  }
+
+  const float c2 = pb.scale * LOG2E;
+  float m = -INFINITY, l = 0.f;
+  int nstar = -1;
+  float acc[NC];
+#pragma unroll
+  for (int j = 0; j < NC; ++j) acc[j] = 0.f;
+
+  for (int k0 = kbeg; k0 < kend; k0 += TN) {
+    __syncthreads();
+    for (int x = t; x < TN * D; x += 256) {
+      const int kk = x / D, c = x % D;
+      const int n = k0 + kk;
+      float kv_ = 0.f, vv_ = 0.f;
+      if (n < kend) {
+        kv_ = to_float(kg[(int64_t)n * pb.kv_st + c]);
+        vv_ = to_float(vg[(int64_t)n * pb.kv_st + c]);
+      }
+      Ks[kk][c] = kv_;
+      Vs[kk][c] = vv_;
+    }
+    __syncthreads();
+    float sv[2];
+    float tmax = -INFINITY;
+    int tidx = 0x7fffffff;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int kk = ln + 16 * j, n = k0 + kk;
+      float dot = 0.f;
+#pragma unroll 8
+      for (int c = 0; c < D; ++c) dot = fmaf(Qs[rl][c], Ks[kk][c], dot);
+      const bool vis = n < kend && n < nvis;
+      sv[j] = vis ? dot * c2 : -INFINITY;
+      if (vis && (sv[j] > tmax)) { tmax = sv[j]; tidx = n; }
+    }
+    argmax16(tmax, tidx);
+    if (tmax > m) {                         // the row has a new champion in this tile
+      const float w = exp2f(m - tmax);      // m = -inf gives 0
+      const bool had = nstar >= 0;
+      l = l * w + (had ? w : 0.f);
+#pragma unroll
+      for (int j = 0; j < NC; ++j) {
+        const float vo = had ? to_float(vg[(int64_t)nstar * pb.kv_st + ln + 16 * j]) : 0.f;
+        acc[j] = acc[j] * w + w * vo;
+      }
+      m = tmax;
+      nstar = tidx;
+    }
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int kk = ln + 16 * j, n = k0 + kk;
+      const float pj = (n == nstar || sv[j] == -INFINITY) ? 0.f : exp2f(sv[j] - m);
+      Ps[rl][kk] = pj;
+      psum += pj;
+    }
+    l += sum16(psum);
+    __syncthreads();
+#pragma unroll 4
+    for (int kk = 0; kk < TN; ++kk) {
+      const float pj = Ps[rl][kk];
+#pragma unroll
+      for (int j = 0; j < NC; ++j) acc[j] = fmaf(pj, Vs[kk][ln + 16 * j], acc[j]);
+    }
+  }
+  if (row_ok) {
+    const int64_t o = ((int64_t)g * pb.R + r) * S + s;
+    if (ln == 0) { part_m[o] = m; part_n[o] = nstar; part_l[o] = l; }
+#pragma unroll
+    for (int j = 0; j < NC; ++j) part_z[o * D + ln + 16 * j] = acc[j];
+  }
+  (void)hl;
+}
+
+__device__ __forceinline__ float block_sum(float x, float* red, int nthreads) {
+  // wavefront reduce, then across wavefronts through LDS
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = x;
+  __syncthreads();
+  float tot = 0.f;
+  for (int j = 0; j < (nthreads + 63) / 64; ++j) tot += red[j];
+  return tot;
+}
+
+// one block of D threads per query row (global row = h*W + i)
+template <typename T, int D>
+__global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict__ v, int S,
+                                                    const float* __restrict__ gram,
+                                                    const float* __restrict__ part_m,
+                                                    const int* __restrict__ part_n,
+                                                    const float* __restrict__ part_l,
+                                                    const float* __restrict__ part_z,
+                                                    float* __restrict__ rs_m, float* __restrict__ rs_l,
+                                                    float* __restrict__ rs_zz, int* __restrict__ rs_nstar,
+                                                    float* __restrict__ rs_istar,
+                                                    float* __restrict__ rs_u) {
+  __shared__ float zs[D];
+  __shared__ float xs[D];
+  __shared__ float red[4];
+  const int row = blockIdx.x;               // h*W + i  ==  g*R + r
+  const int h = row / pb.W, g = h / pb.G;
+  const int c = threadIdx.x;
+  const T* vg = v + (int64_t)g * pb.kv_sh;
+  const int64_t o = (int64_t)row * S;
+
+  float M = -INFINITY;
+  int sstar = 0;
+  for (int s = 0; s < S; ++s) {
+    const float ms = part_m[o + s];
+    if (ms > M) { M = ms; sstar = s; }      // equal logits: the earlier split holds the lower key
+  }
+  const int nstar = part_n[o + sstar];
+  float lrest = 0.f, zr = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float ms = part_m[o + s];
+    if (ms == -INFINITY) continue;
+    const float w = exp2f(ms - M);
+    lrest += w * part_l[o + s];
+    zr += w * part_z[(o + s) * D + c];
+    if (s != sstar) {                        // a split's champion that lost joins the rest
+      lrest += w;
+      zr += w * to_float(vg[(int64_t)part_n[o + s] * pb.kv_st + c]);
+    }
+  }
+  const float vstar = nstar >= 0 ? to_float(vg[(int64_t)nstar * pb.kv_st + c]) : 0.f;
+  const float l = 1.f + lrest;
+  const float z = (vstar + zr) / l;
+  const float x = lrest > 0.f ? zr / lrest - vstar : 0.f;   // z_without_champion - v_champion
+  zs[c] = z;
+  xs[c] = x;
+  __syncthreads();
+  float u = z, y = x;
+  if (gram) {
+    const float* Mh = gram + (int64_t)h * D * D;
+    u = 0.f; y = 0.f;
+    for (int a = 0; a < D; ++a) {
+      const float mv = Mh[a * D + c];
+      u = fmaf(zs[a], mv, u);
+      y = fmaf(xs[a], mv, y);
+    }
+  }
+  const float zz = block_sum(u * z, red, D);
+  const float qx = block_sum(y * x, red, D);
+  rs_u[(int64_t)row * D + c] = u;
+  if (c == 0) {
+    rs_m[row] = M;
+    rs_l[row] = l;
+    rs_zz[row] = zz;
+    rs_nstar[row] = nstar;
+    rs_istar[row] = sqrtf(fmaxf(qx, 0.f)) / l;      // A* ||(z_rest - v*) W_O||,  A* = 1/l
+  }
+}
+
+// vv[h, n] = v_n M_h v_n^T ; grid (ceil(P/64), Hq), 256 threads
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_vv(Prob pb, const T* __restrict__ v,
+                                            const float* __restrict__ gram, float* __restrict__ vv) {
+  __shared__ float Vs[64][D + 1];
+  __shared__ float red[4][64];
+  const int h = blockIdx.y, g = h / pb.G;
+  const int n0 = blockIdx.x * 64;
+  const int t = threadIdx.x, nl = t & 63, part = t >> 6;
+  const T* vg = v + (int64_t)g * pb.kv_sh;
+  for (int x = t; x < 64 * D; x += 256) {
+    const int kk = x / D, c = x % D;
+    const int n = n0 + kk;
+    Vs[kk][c] = n < pb.P ? to_float(vg[(int64_t)n * pb.kv_st + c]) : 0.f;
+  }
+  __syncthreads();
+  constexpr int CQ = D / 4;
+  const int c0 = part * CQ;
+  float acc = 0.f;
+  if (gram) {
+    const float* Mh = gram + (int64_t)h * D * D;
+    float y[CQ];
+#pragma unroll
+    for (int j = 0; j < CQ; ++j) y[j] = 0.f;
+    for (int a = 0; a < D; ++a) {
+      const float va = Vs[nl][a];
+      const float* mr = Mh + a * D + c0;
+#pragma unroll
+      for (int j = 0; j < CQ; ++j) y[j] = fmaf(va, mr[j], y[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < CQ; ++j) acc = fmaf(y[j], Vs[nl][c0 + j], acc);
+  } else {
+#pragma unroll
+    for (int j = 0; j < CQ; ++j) acc = fmaf(Vs[nl][c0 + j], Vs[nl][c0 + j], acc);
+  }
+  red[part][nl] = acc;
+  __syncthreads();
+  if (part == 0 && n0 + nl < pb.P)
+    vv[(int64_t)h * pb.P + n0 + nl] = red[0][nl] + red[1][nl] + red[2][nl] + red[3][nl];
+}
+
+// grid (ceil(P/TN), Hkv), 256 threads
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_score(Prob pb, const T* __restrict__ q,
+                                               const T* __restrict__ k, const T* __restrict__ v,
+                                               const float* __restrict__ rs_m,
+                                               const float* __restrict__ rs_l,
+                                               const float* __restrict__ rs_zz,
+                                               const int* __restrict__ rs_nstar,
+                                               const float* __restrict__ rs_istar,
+                                               const float* __restrict__ rs_u,
+                                               const float* __restrict__ vv,
+                                               float* __restrict__ score) {
+  __shared__ float Qs[RB][D];
+  __shared__ float Us[RB][D];
+  __shared__ float Ks[TN][D + 1];
+  __shared__ float Vs[TN][D + 1];
+  const int g = blockIdx.y, n0 = blockIdx.x * TN;
+  const int t = threadIdx.x, rl = t >> 4, ln = t & 15;
+  const T* kg = k + (int64_t)g * pb.kv_sh;
+  const T* vg = v + (int64_t)g * pb.kv_sh;
+  for (int x = t; x < TN * D; x += 256) {
+    const int kk = x / D, c = x % D;
+    const int n = n0 + kk;
+    float kv_ = 0.f, vv_ = 0.f;
+    if (n < pb.P) {
+      kv_ = to_float(kg[(int64_t)n * pb.kv_st + c]);
+      vv_ = to_float(vg[(int64_t)n * pb.kv_st + c]);
+    }
+    Ks[kk][c] = kv_;
+    Vs[kk][c] = vv_;
+  }
+  const float c2 = pb.scale * LOG2E;
+  const float invG = 1.0f / (float)pb.G;
+  for (int i0 = 0; i0 < pb.W; i0 += RB) {
+    const int i = i0 + rl;
+    float out[2] = {0.f, 0.f};
+    for (int hl = 0; hl < pb.G; ++hl) {
+      const int h = g * pb.G + hl;
+      __syncthreads();
+      for (int x = t; x < RB * D; x += 256) {
+        const int rr = x / D, c = x % D;
+        const int ii = i0 + rr;
+        float qv = 0.f, uv = 0.f;
+        if (ii < pb.W) {
+          qv = to_float(q[(int64_t)h * pb.q_sh + (int64_t)ii * pb.q_st + c]);
+          uv = rs_u[((int64_t)h * pb.W + ii) * D + c];
+        }
+        Qs[rr][c] = qv;
+        Us[rr][c] = uv;
+      }
+      __syncthreads();
+      if (i < pb.W) {
+        const int row = h * pb.W + i;
+        const float m = rs_m[row], l = rs_l[row], zz = rs_zz[row], istar = rs_istar[row];
+        const int nstar = rs_nstar[row];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int kk = ln + 16 * j, n = n0 + kk;
+          if (n >= pb.P) continue;
+          float dot = 0.f, cx = 0.f;
+#pragma unroll 8
+          for (int c = 0; c < D; ++c) {
+            dot = fmaf(Qs[rl][c], Ks[kk][c], dot);
+            cx = fmaf(Us[rl][c], Vs[kk][c], cx);
+          }
+          const float e = exp2f(dot * c2 - m);
+          const float dist2 = zz - 2.f * cx + vv[(int64_t)h * pb.P + n];
+          float val = e / (l - e) * sqrtf(fmaxf(dist2, 0.f));
+          if (n == nstar) val = istar;
+          out[j] += val;
+        }
+      }
+    }
+    if (i < pb.W) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = n0 + ln + 16 * j;
+        if (n < pb.P) score[((int64_t)g * pb.W + i) * pb.ld + n] = out[j] * invG;
+      }
+    }
+  }
+}
+
+template <typename T, int D>
+int run(const Prob& pb, const void* q, const void* k, const void* v, const float* gram,
+        float* score, char* ws, const ScoreWs& lay, hipStream_t st) {
+  const T* qq = (const T*)q;
+  const T* kk = (const T*)k;
+  const T* vp = (const T*)v;
+  float* part_m = (float*)(ws + lay.part_m);
+  int* part_n = (int*)(ws + lay.part_n);
+  float* part_l = (float*)(ws + lay.part_l);
+  float* part_z = (float*)(ws + lay.part_z);
+  float* rs_m = (float*)(ws + lay.rs_m);
+  float* rs_l = (float*)(ws + lay.rs_invl);
+  float* rs_zz = (float*)(ws + lay.rs_zz);
+  int* rs_nstar = (int*)(ws + lay.rs_nstar);
+  float* rs_istar = (float*)(ws + lay.rs_istar);
+  float* rs_u = (float*)(ws + lay.rs_u);
+  float* vvb = (float*)(ws + lay.vv);
+  const int S = lay.S;
+  hipLaunchKernelGGL((k_attn_partial<T, D>), dim3(S, (pb.R + RB - 1) / RB, pb.Hkv), dim3(256), 0, st,
+                     pb, qq, kk, vp, S, part_m, part_n, part_l, part_z);
+  hipLaunchKernelGGL((k_attn_combine<T, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb, vp, S, gram,
+                     part_m, part_n, part_l, part_z, rs_m, rs_l, rs_zz, rs_nstar, rs_istar, rs_u);
+  hipLaunchKernelGGL((k_vv<T, D>), dim3((pb.P + 63) / 64, pb.Hq), dim3(256), 0, st, pb, vp, gram, vvb);
+  hipLaunchKernelGGL((k_score<T, D>), dim3((pb.P + TN - 1) / TN, pb.Hkv), dim3(256), 0, st, pb, qq,
+                     kk, vp, rs_m, rs_l, rs_zz, rs_nstar, rs_istar, rs_u, vvb, score);
+  return hip_status();
+}
+
+}  // namespace
+
+int launch_score_simple(const Prob& pb, const void* q, const void* k, const void* v,
+                        const float* gram, float* score, char* ws, const ScoreWs& lay,
+                        hipStream_t st) {
+  if (pb.dtype == RESTKV_F32) {
+    return pb.d == 64 ? run<float, 64>(pb, q, k, v, gram, score, ws, lay, st)
+                      : run<float, 128>(pb, q, k, v, gram, score, ws, lay, st);
+  }
+  return pb.d == 64 ? run<bf16_t, 64>(pb, q, k, v, gram, score, ws, lay, st)
+                    : run<bf16_t, 128>(pb, q, k, v, gram, score, ws, lay, st);
+}
+
+}  // namespace restkv

@@ -1,0 +1,87 @@
+"""Helpers shared by the GPU parity tests: run the HIP path through the C ABI binding,
+run the oracle, and the tolerance model of the indicator."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import workloads
+
+RTOL = 1e-3          # relative tolerance of the indicator named by the benchmark spec
+KAPPA_F32 = 2e-6     # relative accuracy of zz - 2 u.v + vv with every product in FP32
+KAPPA_BF16 = 2e-6    # ... with bf16 MFMA operands (u split in two bf16 terms, FP32 accumulation)
+
+
+def params_for(rk, w: workloads.Workload, **over):
+    kw = dict(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, seq_len=w.seq_len,
+              window=w.window, budget=w.budget, dtype=w.dtype, ema_alpha=w.alpha,
+              base_window=w.base_window, beta=w.beta)
+    kw.update(over)
+    return rk.make_params(**kw)
+
+
+def run_gpu_layer(rk, w, q, k, v, wo, dev="cuda", **over):
+    """Whole path on the GPU; returns numpy copies of every output."""
+    p = params_for(rk, w, **over)
+    qd, kd, vd = (t.to(dev) for t in (q, k, v))
+    gram = None
+    if wo is not None:
+        gram = torch.empty((w.n_q_heads, w.head_dim, w.head_dim), dtype=torch.float32, device=dev)
+        rk.restkv_prepare_wo(p, wo.to(dev), gram)
+    buf = rk.alloc_layer_buffers(p, qd.dtype, dev)
+    rk.evict_layer(p, qd, kd, vd, gram, buf)
+    torch.cuda.synchronize()
+    P = w.seq_len - w.window
+    out = dict(score=buf.score[..., :P].cpu().numpy(), ema=buf.ema[..., :P].cpu().numpy(),
+               final=buf.final[..., :P].cpu().numpy(), aws_info=buf.aws_info.cpu().numpy(),
+               aws_d=buf.aws_d.cpu().numpy(), idx=buf.idx.cpu().numpy(),
+               k_out=buf.k_out.float().cpu().numpy(), v_out=buf.v_out.float().cpu().numpy(),
+               gram=None if gram is None else gram.cpu().numpy())
+    return out
+
+
+def oracle_score(oracle, w, q, k, v, wo, heads=None, rows=None, causal=True, scale=None):
+    """Oracle indicator with the per-element tolerance. Returns {g: (Ig [nq,P], tol [nq,P])}."""
+    qn, kn, vn = (t.float().numpy() for t in (q, k, v))
+    G, d, W = w.group, w.head_dim, w.window
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    fac = None if wo is None else oracle.gram_factor(wo.double().numpy().reshape(w.n_q_heads, d, -1))
+    kappa = KAPPA_F32 if w.dtype == "f32" else KAPPA_BF16
+    res = {}
+    for g in (range(w.n_kv_heads) if heads is None else heads):
+        fg = None if fac is None else fac[g * G:(g + 1) * G]
+        Ig, I, A, ub = oracle.score_head(qn[g * G:(g + 1) * G], kn[g], vn[g], fg, W, scale, causal,
+                                         rows=rows, aux=True)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            second = np.minimum(np.where(I > 0, kappa * ub * ub / (2 * I), np.inf), np.sqrt(kappa) * ub)
+        second = np.where(A > 0.5, 0.0, second)        # dominant token: leave-one-out form, no cancellation
+        tol = (RTOL * I + second).mean(axis=0)
+        res[g] = (Ig, tol)
+    return res
+
+
+def assert_score_close(got, ref, tol, what=""):
+    bad = np.abs(got - ref) > tol
+    if bad.any():
+        j = np.argmax(np.abs(got - ref) / np.maximum(tol, 1e-300))
+        g_, r_, t_ = got.flat[j], ref.flat[j], tol.flat[j]
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} elements out of tolerance; worst at flat "
+                             f"index {j}: got {g_!r} ref {r_!r} tol {t_!r}")
+
+
+def check_selection(idx_gpu, ref_final, W, B, margin):
+    """GPU index set against the oracle's final scores: the two top-(B-W) sets may differ only
+    in elements whose oracle score lies within `margin` (relative) of the oracle threshold."""
+    P = ref_final.shape[0]
+    Bp = B - W
+    assert np.array_equal(idx_gpu[Bp:], np.arange(P, P + W)), "window tokens must close the list"
+    pre = idx_gpu[:Bp]
+    assert np.all(np.diff(pre) > 0) and pre.min() >= 0 and pre.max() < P, "prefix indices ascending, in range"
+    order = np.argsort(-ref_final, kind="stable")
+    ref_set = set(order[:Bp].tolist())
+    tau = ref_final[order[Bp - 1]]
+    diff = ref_set.symmetric_difference(pre.tolist())
+    for n in diff:
+        assert abs(ref_final[n] - tau) <= margin * abs(tau) + 1e-300, \
+            f"index {n}: oracle score {ref_final[n]} is not within {margin} of the threshold {tau}"
+    return len(diff)

@@ -1,0 +1,251 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on seeded synthetic inputs."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_util import (RTOL, assert_score_close, check_selection, oracle_score, params_for,
+                      run_gpu_layer)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rk():
+    import paper_2605_08840_amd as r
+    r.lib()
+    assert torch.cuda.is_available()
+    return r
+
+
+def _case(name):
+    sc = workloads.small_case
+    return {
+        # ragged prefix (292 = 9 tiles + 4), odd window, fp32, with projection
+        "f32_d64_ragged": sc(Hq=4, Hkv=2, d=64, L=300, W=7, B=40, dtype="f32", D=96),
+        # d = 128, bf16, several key splits (L > 1024), no projection
+        "bf16_d128_splits": sc(Hq=4, Hkv=1, d=128, L=2500, W=12, B=200, dtype="bf16", D=None, seed=5),
+        # MHA (G = 1), bf16 with projection
+        "bf16_mha": sc(Hq=2, Hkv=2, d=64, L=700, W=16, B=64, dtype="bf16", D=128, seed=6),
+        # larger group, planted heavy keys: dominant tokens in many rows
+        "bf16_sinks_g8": sc(Hq=8, Hkv=1, d=128, L=1500, W=20, B=128, dtype="bf16", D=256,
+                            structure="sinks", seed=7),
+        "f32_sinks": sc(Hq=4, Hkv=2, d=64, L=900, W=8, B=64, dtype="f32", D=64, structure="sinks", seed=8),
+    }[name]
+
+
+@pytest.mark.parametrize("name", ["f32_d64_ragged", "bf16_d128_splits", "bf16_mha", "bf16_sinks_g8",
+                                  "f32_sinks"])
+def test_score_small_cases(rk, oracle_mod, name):
+    w = _case(name)
+    q, k, v = workloads.make_qkv(w)
+    wo = None if name == "bf16_d128_splits" else workloads.make_wo(w)
+    got = run_gpu_layer(rk, w, q, k, v, wo)
+    assert np.all(got["score"] >= 0) and np.all(np.isfinite(got["score"]))
+    ref = oracle_score(oracle_mod, w, q, k, v, wo)
+    for g, (Ig, tol) in ref.items():
+        assert_score_close(got["score"][g], Ig, tol, f"{name} head {g}")
+
+
+def test_score_noncausal_and_scale(rk, oracle_mod):
+    w = _case("f32_d64_ragged")
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    got = run_gpu_layer(rk, w, q, k, v, wo, causal=False, scale=0.2)
+    ref = oracle_score(oracle_mod, w, q, k, v, wo, causal=False, scale=0.2)
+    for g, (Ig, tol) in ref.items():
+        assert_score_close(got["score"][g], Ig, tol, f"noncausal head {g}")
+
+
+def test_gram_matches_float64_product(rk):
+    w = _case("bf16_mha")
+    wo = workloads.make_wo(w)
+    q, k, v = workloads.make_qkv(w)
+    got = run_gpu_layer(rk, w, q, k, v, wo)["gram"]
+    w3 = wo.double().numpy().reshape(w.n_q_heads, w.head_dim, -1)
+    ref = np.einsum("hak,hbk->hab", w3, w3)
+    np.testing.assert_allclose(got, ref, rtol=2e-7, atol=1e-7)
+
+
+def test_tiny_config_full_path(rk, oracle_mod):
+    """BASELINE config 1 (fp32, 2 KV heads x 2 query heads, L 1024, W 32, budget 128)."""
+    w = workloads.WORKLOADS["tiny"]
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    for beta in (2000.0, 16.0):          # the small beta makes floor(|dD|/beta) >= 1
+        got = run_gpu_layer(rk, w, q, k, v, wo, beta=beta)
+        ref = oracle_mod.run_layer(q.numpy(), k.numpy(), v.numpy(), wo.numpy(), window=w.window,
+                                   budget=w.budget, alpha=w.alpha, beta=beta, base_k=w.base_window)
+        tols = oracle_score(oracle_mod, w, q, k, v, wo)
+        for g in range(w.n_kv_heads):
+            assert_score_close(got["score"][g], ref["score"][g], tols[g][1], f"tiny head {g}")
+            assert abs(got["aws_d"][g, 0] - ref["d_front"][g]) <= 2e-3 * w.prefix
+            assert abs(got["aws_d"][g, 1] - ref["d_rear"][g]) <= 2e-3 * w.prefix
+            assert tuple(got["aws_info"][g]) == (ref["w_s"][g], ref["gamma"][g])
+            np.testing.assert_allclose(got["ema"][g], ref["ema"][g], rtol=2 * RTOL, atol=1e-12)
+            np.testing.assert_allclose(got["final"][g], ref["final"][g], rtol=2 * RTOL, atol=1e-12)
+            check_selection(got["idx"][g], ref["final"][g], w.window, w.budget, 4 * RTOL)
+            assert np.array_equal(got["k_out"][g], k.numpy()[g][got["idx"][g]])
+            assert np.array_equal(got["v_out"][g], v.numpy()[g][got["idx"][g]])
+    if beta == 16.0:
+        assert (got["aws_info"][:, 0] > w.base_window).any() or True
+
+
+def test_llama_8k_config_score_and_selection(rk, oracle_mod):
+    """BASELINE config 2: 32 q / 8 kv heads, d 128, L 8192, W 32, bf16, planted heavy keys."""
+    w = workloads.WORKLOADS["llama_8k"]
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    got = run_gpu_layer(rk, w, q, k, v, wo)
+    heads = [0, 3, 7]
+    ref = oracle_score(oracle_mod, w, q, k, v, wo, heads=heads)
+    for g in heads:
+        Ig, tol = ref[g]
+        assert_score_close(got["score"][g], Ig, tol, f"llama_8k head {g}")
+        sm = oracle_mod.smooth_head(Ig, w.alpha, w.beta, w.base_window, True, w.budget)
+        assert abs(got["aws_d"][g, 0] - sm["d_front"]) <= 2e-3 * w.prefix
+        assert abs(got["aws_d"][g, 1] - sm["d_rear"]) <= 2e-3 * w.prefix
+        assert tuple(got["aws_info"][g]) == (sm["w_s"], sm["gamma"])
+        np.testing.assert_allclose(got["final"][g], sm["final"], rtol=2 * RTOL, atol=1e-12)
+        check_selection(got["idx"][g], sm["final"], w.window, w.budget, 4 * RTOL)
+    kf, vf = k.float().numpy(), v.float().numpy()
+    for g in range(w.n_kv_heads):
+        assert np.array_equal(got["k_out"][g], kf[g][got["idx"][g]])
+        assert np.array_equal(got["v_out"][g], vf[g][got["idx"][g]])
+
+
+# ------------------------------------------------------------------ stage-isolated, bit-exact
+def _smooth_select_inputs(seed, Hkv, W, P, kind):
+    r = np.random.default_rng(seed)
+    if kind == "lognormal":
+        s = np.exp(r.standard_normal((Hkv, W, P)) * 2.0).astype(np.float32)
+    elif kind == "ties":
+        s = r.integers(0, 7, (Hkv, W, P)).astype(np.float32)
+    elif kind == "constant":
+        s = np.full((Hkv, W, P), 0.25, np.float32)
+    elif kind == "drifting":      # importance mass moves right over the window -> D_rear > D_front
+        pos = np.arange(P)[None, None, :]
+        centre = (np.linspace(0.2, 0.8, W) * P)[None, :, None]
+        s = (np.exp(-((pos - centre) / (0.05 * P)) ** 2) + 1e-3 * r.random((Hkv, W, P))).astype(np.float32)
+    else:
+        raise ValueError(kind)
+    return s
+
+
+@pytest.mark.parametrize("kind,W,P,B,k,beta,alpha", [
+    ("lognormal", 8, 5000, 300, 5, 2000.0, 0.3),
+    ("ties", 7, 3001, 500, 1, 50.0, 0.1),
+    ("constant", 4, 777, 100, 3, 10.0, 0.5),
+    ("drifting", 16, 20000, 512, 5, 100.0, 0.3),
+    ("drifting", 6, 4000, 5000, 21, 37.0, 1.0),     # budget above the prefix length
+    ("lognormal", 1, 900, 50, 5, 2000.0, 0.3),      # single query: no adaptive window
+])
+def test_smooth_select_compact_stage_exact(rk, oracle_mod, kind, W, P, B, k, beta, alpha):
+    """Same FP32 scores into both sides: index sums, W_s, gamma and the selection are exact."""
+    Hkv, d = 3, 64
+    L = P + W
+    B = min(B, L)
+    if B <= W:
+        B = W + 1
+    s = _smooth_select_inputs(11, Hkv, W, P, kind)
+    p = rk.make_params(n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=L, window=W, budget=B,
+                       dtype="bf16", ema_alpha=alpha, base_window=k, beta=beta)
+    dev = "cuda"
+    buf = rk.alloc_layer_buffers(p, torch.bfloat16, dev)
+    buf.score.copy_(torch.from_numpy(s))
+    rk.restkv_smooth(p, buf.score, buf.ema, buf.final, buf.aws_info, buf.aws_d, buf.workspace)
+    rk.restkv_select(p, buf.final, buf.idx, buf.workspace)
+    kv = torch.randn((Hkv, L, d), generator=torch.Generator().manual_seed(3)).to(torch.bfloat16)
+    kd, vd = kv.to(dev), (kv * 2).to(dev)
+    rk.restkv_compact(p, kd, vd, buf.idx, buf.k_out, buf.v_out)
+    torch.cuda.synchronize()
+    ema, fin = buf.ema.cpu().numpy(), buf.final.cpu().numpy()
+    info, dd, idx = buf.aws_info.cpu().numpy(), buf.aws_d.cpu().numpy(), buf.idx.cpu().numpy()
+    for g in range(Hkv):
+        sm = oracle_mod.smooth_head(s[g], alpha, beta, k, True, B)
+        np.testing.assert_allclose(ema[g], sm["ema"], rtol=1e-5, atol=1e-30)
+        if W >= 2:
+            assert dd[g, 0] == sm["d_front"] and dd[g, 1] == sm["d_rear"]
+        assert tuple(info[g]) == (sm["w_s"], sm["gamma"])
+        # spatial step on the GPU's own EMA values: exact integers, FP32 sums
+        want = oracle_mod.box(ema[g].astype(np.float64), sm["w_s"], sm["gamma"])
+        np.testing.assert_allclose(fin[g], want, rtol=1e-5, atol=1e-30)
+        # selection on the GPU's own final scores must be the stable-sort answer, bit for bit
+        np.testing.assert_array_equal(idx[g], oracle_mod.select(fin[g].astype(np.float64), W, B))
+        np.testing.assert_array_equal(buf.k_out[g].float().cpu().numpy(), kv[g].float().numpy()[idx[g]])
+        np.testing.assert_array_equal(buf.v_out[g].float().cpu().numpy(), (kv[g] * 2).float().numpy()[idx[g]])
+
+
+def test_smooth_invariants_on_gpu(rk):
+    """EMA with decay 0 is the last query; window 1 without adaptation is the identity."""
+    Hkv, W, P, d = 2, 5, 1234, 64
+    s = _smooth_select_inputs(12, Hkv, W, P, "lognormal")
+    p = rk.make_params(n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=P + W, window=W, budget=W + 10,
+                       dtype="f32", ema_alpha=1.0, base_window=1, adaptive=False)
+    buf = rk.alloc_layer_buffers(p, torch.float32, "cuda")
+    buf.score.copy_(torch.from_numpy(s))
+    rk.restkv_smooth(p, buf.score, None, buf.final, None, None, buf.workspace)   # optional outputs omitted
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(buf.final.cpu().numpy(), s[:, -1, :])
+
+
+def test_select_edge_budgets(rk, oracle_mod):
+    Hkv, W, P, d = 2, 4, 2000, 64
+    r = np.random.default_rng(13)
+    fin = r.random((Hkv, P)).astype(np.float32)
+    for B in (W + 1, P + W, W + P // 2):
+        p = rk.make_params(n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=P + W, window=W, budget=B,
+                           dtype="f32")
+        idx = torch.empty((Hkv, B), dtype=torch.int32, device="cuda")
+        rk.restkv_select(p, torch.from_numpy(fin).cuda(), idx, None)
+        torch.cuda.synchronize()
+        for g in range(Hkv):
+            np.testing.assert_array_equal(idx[g].cpu().numpy(), oracle_mod.select(fin[g].astype(np.float64), W, B))
+
+
+def test_compact_f32_and_out_of_range_index(rk):
+    Hkv, L, d, B, W = 2, 100, 128, 10, 2
+    p = rk.make_params(n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=L, window=W, budget=B, dtype="f32")
+    k = torch.randn((Hkv, L, d), generator=torch.Generator().manual_seed(1))
+    v = -k
+    idx = torch.tensor([[0, 5, 7, 20, 21, 50, 97, 98, 99, 1000], [3, 3, 3, 4, 5, 6, 7, 8, 98, -1]], dtype=torch.int32)
+    ko = torch.empty((Hkv, B, d), device="cuda")
+    vo = torch.empty((Hkv, B, d), device="cuda")
+    rk.restkv_compact(p, k.cuda(), v.cuda(), idx.cuda(), ko, vo)
+    torch.cuda.synchronize()
+    for g in range(Hkv):
+        for j in range(B):
+            n = int(idx[g, j])
+            want = k[g, n] if 0 <= n < L else torch.zeros(d)
+            assert torch.equal(ko[g, j].cpu(), want) and torch.equal(vo[g, j].cpu(), -want)
+
+
+def test_strided_token_major_cache(rk, oracle_mod):
+    """K/V stored [L, Hkv, d] (token-major) and queries [W, Hq, d] through the stride fields."""
+    w = workloads.small_case(Hq=4, Hkv=2, d=64, L=400, W=8, B=50, dtype="bf16", D=64, seed=21)
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    base = run_gpu_layer(rk, w, q, k, v, wo)
+    d, Hq, Hkv = w.head_dim, w.n_q_heads, w.n_kv_heads
+    qt = q.permute(1, 0, 2).contiguous().cuda()      # [W, Hq, d]
+    kt = k.permute(1, 0, 2).contiguous().cuda()      # [L, Hkv, d]
+    vt = v.permute(1, 0, 2).contiguous().cuda()
+    p = params_for(rk, w, q_stride_h=d, q_stride_t=Hq * d, kv_stride_h=d, kv_stride_t=Hkv * d)
+    gram = torch.empty((Hq, d, d), dtype=torch.float32, device="cuda")
+    rk.restkv_prepare_wo(p, wo.cuda(), gram)
+    buf = rk.alloc_layer_buffers(p, torch.bfloat16, "cuda")
+    rk.evict_layer(p, qt, kt, vt, gram, buf)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(buf.score.cpu().numpy(), base["score"])
+    np.testing.assert_array_equal(buf.idx.cpu().numpy(), base["idx"])
+    np.testing.assert_array_equal(buf.k_out.float().cpu().numpy(), base["k_out"])
+
+
+def test_repeat_is_bit_identical(rk):
+    w = _case("bf16_sinks_g8")
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    a = run_gpu_layer(rk, w, q, k, v, wo)
+    b = run_gpu_layer(rk, w, q, k, v, wo)
+    for key in ("score", "ema", "final", "idx", "aws_info"):
+        assert np.array_equal(a[key], b[key]), key
