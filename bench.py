@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the ReST-KV eviction hot path on one MI355X.
+
+A step is one pass of the whole path (score -> smooth -> select -> compact) over every
+layer of one synthetic KV cache that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload drift_128k]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16 = 2.5e15      # dense bf16 MFMA, FLOP/s (published)
+PEAK_FP32 = 157.3e12         # vector FP32, FLOP/s
+PEAK_HBM = 8.0e12            # HBM3E, B/s
+
+
+def stage_work(w, stage: str):
+    """(bound, algorithmic work per launch) of each kernel: flops for the contractions,
+    bytes for the streaming passes.  Recomputed logits of the scoring pass are not counted."""
+    Hq, Hkv, d, L, W, P, B = w.n_q_heads, w.n_kv_heads, w.head_dim, w.seq_len, w.window, w.prefix, w.budget
+    esz = 4 if w.dtype == "f32" else 2
+    if stage == "attn_partial":      # q K^T and A V over all L keys
+        return "mfma", 2 * (2.0 * Hq * W * L * d)
+    if stage == "score":             # cross term u V^T (the logits are a recompute)
+        return "mfma", 2.0 * Hq * W * P * d
+    if stage == "vv":                # V M_h for every query head
+        return "mfma", 2.0 * Hq * P * d * d
+    if stage == "ema":
+        return "hbm", 4.0 * Hkv * W * P + 4.0 * Hkv * P
+    if stage == "row_topk":          # one read of the raw score
+        return "hbm", 4.0 * Hkv * W * P
+    if stage == "box":
+        return "hbm", 8.0 * Hkv * P
+    if stage == "select":
+        return "hbm", 4.0 * Hkv * P + 4.0 * Hkv * B
+    if stage == "compact":           # read and write of the kept K and V rows
+        return "hbm", 2.0 * 2.0 * Hkv * B * d * esz
+    if stage == "attn_combine":
+        return "hbm", 0.0
+    return "hbm", 0.0
+
+
+def cpu_baseline(w, q, k, v, wo, budget_s=25.0):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload:
+    the whole path for ONE KV head of layer 0, on a prefix of the cache sized so that the run
+    stays within about `budget_s` seconds (all W window queries, real head layout)."""
+    import numpy as np
+
+    import oracle
+    G, d, W = w.group, w.head_dim, w.window
+    threads = oracle.num_threads()
+    # cost model: ~ (G*d*d + 3*G*W*d) multiply-adds per token, ~0.7 GFLOP/s/thread sustained
+    per_tok = 2.0 * (G * d * d + 3.0 * G * W * d)
+    Ls = int(min(w.seq_len, max(4096, budget_s * 0.7e9 * threads / per_tok)))
+    Ls = max(W + 2, Ls // 1024 * 1024)
+    qn = q[:G].float().cpu().numpy()
+    kn = k[0, -Ls:].float().cpu().numpy()
+    vn = v[0, -Ls:].float().cpu().numpy()
+    won = None if wo is None else wo[:G * d].cpu().numpy()
+    B = max(W + 1, min(w.budget, Ls))
+    t0 = time.perf_counter()
+    oracle.run_layer(qn, kn[None], vn[None], won, window=W, budget=B, alpha=w.alpha, beta=w.beta,
+                     base_k=w.base_window)
+    dt = time.perf_counter() - t0
+    return {"value": Ls / dt, "unit": "KV-head-tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"layer 0, KV head 0 (its {G} query heads, all {W} window queries), last {Ls} "
+                      f"tokens of the cache, whole path, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="drift_128k")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket kernels with events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the path on ONE GPU (every (layer, KV head) is independent; "
+              "no collectives exist to time); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2605_08840_amd as rk
+    import workloads
+
+    rk.lib()      # fails loudly if the HIP library has not been built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = workloads.WORKLOADS[args.workload]
+    if args.layers:
+        w = w.with_(n_layers=args.layers)
+    p = rk.make_params(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                       seq_len=w.seq_len, window=w.window, budget=w.budget, dtype=w.dtype,
+                       ema_alpha=w.alpha, base_window=w.base_window, beta=w.beta)
+    dt = workloads.torch_dtype(w)
+
+    # ---- resident inputs: every layer's q, k, v and Gram matrices -----------------------------
+    layers = []
+    wo0 = None
+    for l in range(w.n_layers):
+        q, k, v = workloads.make_qkv(w, l, dev)
+        wo = workloads.make_wo(w, l, dev)
+        gram = torch.empty((w.n_q_heads, w.head_dim, w.head_dim), dtype=torch.float32, device=dev)
+        rk.restkv_prepare_wo(p, wo, gram)
+        if l == 0:
+            wo0 = wo.cpu()
+        del wo
+        layers.append((q, k, v, gram))
+    torch.cuda.synchronize()
+    buf = rk.alloc_layer_buffers(p, dt, dev)
+
+    def step():
+        for (q, k, v, gram) in layers:
+            rk.evict_layer(p, q, k, v, gram, buf)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rk.restkv_timing_enable(not args.no_kernel_events)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    stages = rk.restkv_timing_read() if not args.no_kernel_events else {}
+    rk.restkv_timing_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens = w.n_layers * w.n_kv_heads * w.seq_len           # KV-head-tokens scored and evicted
+    value = tokens / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel ------------------------------------------------------
+    per = {}
+    for name, (ms, n) in stages.items():
+        if n:
+            bound, work = stage_work(w, name)
+            avg = ms / n
+            peak = PEAK_MFMA_BF16 if bound == "mfma" else PEAK_HBM
+            if bound == "mfma" and w.dtype == "f32":
+                peak = PEAK_FP32
+            per[name] = {"avg_ms": avg, "launches": n, "bound": bound, "work": work,
+                         "achieved": work / (avg * 1e-3) if avg > 0 else 0.0, "peak": peak}
+    roof = None
+    if per:
+        dom = max((n for n in per if per[n]["work"] > 0), key=lambda n: per[n]["avg_ms"])
+        s = per[dom]
+        unit = "TFLOP/s" if s["bound"] == "mfma" else "GB/s"
+        div = 1e12 if s["bound"] == "mfma" else 1e9
+        roof = {"kernel": dom, "bound": s["bound"], "achieved": s["achieved"] / div, "peak": s["peak"] / div,
+                "unit": unit, "frac": s["achieved"] / s["peak"], "traffic": None,
+                "avg_ms": s["avg_ms"]}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        q0, k0, v0, _ = layers[0]
+        cpu = cpu_baseline(w, q0, k0, v0, wo0)
+
+    out = {
+        "metric": "scored+evicted KV tokens/sec", "value": value, "unit": "KV-head-tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "n_layers": w.n_layers, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "seq_len": w.seq_len,
+                   "window": w.window, "budget": w.budget, "layer_tokens_per_s": w.n_layers * w.seq_len / (ms_per_step * 1e-3)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "stages": {n: {"avg_ms": round(s["avg_ms"], 5), "launches": s["launches"], "bound": s["bound"],
+                       "frac": (s["achieved"] / s["peak"]) if s["work"] else None} for n, s in per.items()},
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

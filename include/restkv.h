@@ -145,6 +145,20 @@ int restkv_select(const restkv_params* p, const float* final_score, int32_t* idx
 int restkv_compact(const restkv_params* p, const void* k, const void* v, const int32_t* idx,
                    void* k_out, void* v_out, restkv_stream_t stream);
 
+/*
+ * Profiling aid (not part of the method): when enabled, every kernel the library
+ * launches is bracketed by two HIP events on the caller's stream.
+ * restkv_timing_read() blocks until those events have completed, adds the elapsed
+ * milliseconds and the number of launches per stage into ms[] / launches[] (host
+ * arrays of n_stages >= RESTKV_N_STAGES entries) and forgets them.  Disabled by
+ * default; enabling or disabling also forgets pending records.  Not thread-safe
+ * against concurrent launches on other host threads beyond a mutex on the records.
+ */
+#define RESTKV_N_STAGES 10
+int restkv_timing_enable(int on);
+int restkv_timing_read(double* ms, int64_t* launches, int n_stages);
+const char* restkv_stage_name(int stage);   /* "gram", "attn_partial", ... */
+
 /* Static description of an error code. */
 const char* restkv_strerror(int code);
 

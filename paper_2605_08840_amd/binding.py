@@ -61,7 +61,11 @@ def lib() -> ctypes.CDLL:
         L.restkv_compact.argtypes = [P, vp, vp, vp, vp, vp, vp]
         L.restkv_strerror.restype = ctypes.c_char_p
         L.restkv_strerror.argtypes = [ctypes.c_int]
-        for f in ("restkv_prepare_wo", "restkv_score", "restkv_smooth", "restkv_select",
+        L.restkv_timing_read.argtypes = [vp, vp, ctypes.c_int]
+        L.restkv_timing_enable.argtypes = [ctypes.c_int]
+        L.restkv_stage_name.restype = ctypes.c_char_p
+        L.restkv_stage_name.argtypes = [ctypes.c_int]
+        for f in ("restkv_timing_enable", "restkv_timing_read", "restkv_prepare_wo", "restkv_score", "restkv_smooth", "restkv_select",
                   "restkv_compact", "restkv_version"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
@@ -141,6 +145,21 @@ def restkv_select(p, final, idx, workspace, stream=None):
 def restkv_compact(p, k, v, idx, k_out, v_out, stream=None):
     _chk(lib().restkv_compact(ctypes.byref(p), _ptr(k), _ptr(v), _ptr(idx), _ptr(k_out), _ptr(v_out),
                               _stream(stream)), "restkv_compact")
+
+
+N_STAGES = 10
+
+
+def restkv_timing_enable(on: bool):
+    _chk(lib().restkv_timing_enable(int(bool(on))), "restkv_timing_enable")
+
+
+def restkv_timing_read():
+    """{stage name: (total ms, launches)} since the last read; waits for the recorded events."""
+    ms = (ctypes.c_double * N_STAGES)()
+    cnt = (ctypes.c_int64 * N_STAGES)()
+    _chk(lib().restkv_timing_read(ms, cnt, N_STAGES), "restkv_timing_read")
+    return {lib().restkv_stage_name(s).decode(): (ms[s], cnt[s]) for s in range(N_STAGES)}
 
 
 def restkv_version() -> int:

@@ -51,6 +51,22 @@ int launch_select(const Prob& pb, const float* fin, int32_t* idx, hipStream_t st
 int launch_compact(const Prob& pb, const void* k, const void* v, const int32_t* idx, void* k_out,
                    void* v_out, hipStream_t st);
 
+// Brackets one kernel launch with events when timing is enabled (see timing.hip).
+struct StageTimer {
+  StageTimer(int stage, hipStream_t st);
+  ~StageTimer();
+  hipStream_t st_;
+  long slot_;
+};
+enum Stage { ST_GRAM = 0, ST_ATTN, ST_COMBINE, ST_VV, ST_SCORE, ST_EMA, ST_ROWTOPK, ST_BOX, ST_SELECT,
+             ST_COMPACT };
+
+#define RK_LAUNCH(stage, st, ...)            \
+  do {                                       \
+    ::restkv::StageTimer tm_((stage), (st)); \
+    hipLaunchKernelGGL(__VA_ARGS__);         \
+  } while (0)
+
 inline int hip_status() { return hipGetLastError() == hipSuccess ? RESTKV_OK : RESTKV_EHIP; }
 
 // ---- device helpers -----------------------------------------------------------

@@ -53,15 +53,15 @@ int launch_compact(const Prob& pb, const void* k, const void* v, const int32_t* 
                    (((uintptr_t)k | (uintptr_t)v | (uintptr_t)k_out | (uintptr_t)v_out) & 15u) == 0;
   if (vec) {
     const int cpr = pb.d / per16;
-    hipLaunchKernelGGL(k_compact, dim3((pb.B * cpr + 255) / 256, pb.Hkv, 2), dim3(256), 0, st, pb,
+    RK_LAUNCH(ST_COMPACT, st, k_compact, dim3((pb.B * cpr + 255) / 256, pb.Hkv, 2), dim3(256), 0, st, pb,
                        (const uint4*)k, (const uint4*)v, idx, (uint4*)k_out, (uint4*)v_out, cpr,
                        pb.kv_sh / per16, pb.kv_st / per16);
   } else if (esz == 4) {
-    hipLaunchKernelGGL(k_compact_elem<float>, dim3(((int64_t)pb.B * pb.d + 255) / 256, pb.Hkv, 2),
+    RK_LAUNCH(ST_COMPACT, st, k_compact_elem<float>, dim3(((int64_t)pb.B * pb.d + 255) / 256, pb.Hkv, 2),
                        dim3(256), 0, st, pb, (const float*)k, (const float*)v, idx, (float*)k_out,
                        (float*)v_out);
   } else {
-    hipLaunchKernelGGL(k_compact_elem<uint16_t>, dim3(((int64_t)pb.B * pb.d + 255) / 256, pb.Hkv, 2),
+    RK_LAUNCH(ST_COMPACT, st, k_compact_elem<uint16_t>, dim3(((int64_t)pb.B * pb.d + 255) / 256, pb.Hkv, 2),
                        dim3(256), 0, st, pb, (const uint16_t*)k, (const uint16_t*)v, idx,
                        (uint16_t*)k_out, (uint16_t*)v_out);
   }

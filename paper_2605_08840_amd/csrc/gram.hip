@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void k_gram(int d, int64_t D, const float* __r
 }  // namespace
 
 int launch_gram(const Prob& pb, const float* w_o, int64_t d_model, float* gram, hipStream_t st) {
-  hipLaunchKernelGGL(k_gram, dim3(pb.d / 16, pb.d / 16, pb.Hq), dim3(256), 0, st, pb.d, d_model,
+  RK_LAUNCH(ST_GRAM, st, k_gram, dim3(pb.d / 16, pb.d / 16, pb.Hq), dim3(256), 0, st, pb.d, d_model,
                      w_o, gram);
   return hip_status();
 }

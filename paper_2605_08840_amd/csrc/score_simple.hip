@@ -375,12 +375,12 @@ int run(const Prob& pb, const void* q, const void* k, const void* v, const float
   float* rs_u = (float*)(ws + lay.rs_u);
   float* vvb = (float*)(ws + lay.vv);
   const int S = lay.S;
-  hipLaunchKernelGGL((k_attn_partial<T, D>), dim3(S, (pb.R + RB - 1) / RB, pb.Hkv), dim3(256), 0, st,
+  RK_LAUNCH(ST_ATTN, st, (k_attn_partial<T, D>), dim3(S, (pb.R + RB - 1) / RB, pb.Hkv), dim3(256), 0, st,
                      pb, qq, kk, vp, S, part_m, part_n, part_l, part_z);
-  hipLaunchKernelGGL((k_attn_combine<T, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb, vp, S, gram,
+  RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<T, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb, vp, S, gram,
                      part_m, part_n, part_l, part_z, rs_m, rs_l, rs_zz, rs_nstar, rs_istar, rs_u);
-  hipLaunchKernelGGL((k_vv<T, D>), dim3((pb.P + 63) / 64, pb.Hq), dim3(256), 0, st, pb, vp, gram, vvb);
-  hipLaunchKernelGGL((k_score<T, D>), dim3((pb.P + TN - 1) / TN, pb.Hkv), dim3(256), 0, st, pb, qq,
+  RK_LAUNCH(ST_VV, st, (k_vv<T, D>), dim3((pb.P + 63) / 64, pb.Hq), dim3(256), 0, st, pb, vp, gram, vvb);
+  RK_LAUNCH(ST_SCORE, st, (k_score<T, D>), dim3((pb.P + TN - 1) / TN, pb.Hkv), dim3(256), 0, st, pb, qq,
                      kk, vp, rs_m, rs_l, rs_zz, rs_nstar, rs_istar, rs_u, vvb, score);
   return hip_status();
 }

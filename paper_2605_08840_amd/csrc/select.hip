@@ -25,7 +25,7 @@ __global__ __launch_bounds__(SEL_NT) void k_select(Prob pb, const float* __restr
 }  // namespace
 
 int launch_select(const Prob& pb, const float* fin, int32_t* idx, hipStream_t st) {
-  hipLaunchKernelGGL(k_select, dim3(pb.Hkv), dim3(SEL_NT), 0, st, pb, fin, idx);
+  RK_LAUNCH(ST_SELECT, st, k_select, dim3(pb.Hkv), dim3(SEL_NT), 0, st, pb, fin, idx);
   return hip_status();
 }
 

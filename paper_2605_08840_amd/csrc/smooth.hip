@@ -97,10 +97,10 @@ int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, in
   unsigned long long* rowsum = (unsigned long long*)(ws + lay.rowsum);
   float* e = ema ? ema : (float*)(ws + lay.ema);
   const dim3 gl((pb.P + 255) / 256, pb.Hkv);
-  hipLaunchKernelGGL(k_ema, gl, dim3(256), 0, st, pb, score, e);
+  RK_LAUNCH(ST_EMA, st, k_ema, gl, dim3(256), 0, st, pb, score, e);
   if (pb.adaptive)
-    hipLaunchKernelGGL(k_row_topk_sum, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
-  hipLaunchKernelGGL(k_box, gl, dim3(256), 0, st, pb, e, rowsum, fin, aws_info, aws_d);
+    RK_LAUNCH(ST_ROWTOPK, st, k_row_topk_sum, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
+  RK_LAUNCH(ST_BOX, st, k_box, gl, dim3(256), 0, st, pb, e, rowsum, fin, aws_info, aws_d);
   return hip_status();
 }
 

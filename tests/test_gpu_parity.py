@@ -87,8 +87,6 @@ def test_tiny_config_full_path(rk, oracle_mod):
             check_selection(got["idx"][g], ref["final"][g], w.window, w.budget, 4 * RTOL)
             assert np.array_equal(got["k_out"][g], k.numpy()[g][got["idx"][g]])
             assert np.array_equal(got["v_out"][g], v.numpy()[g][got["idx"][g]])
-    if beta == 16.0:
-        assert (got["aws_info"][:, 0] > w.base_window).any() or True
 
 
 def test_llama_8k_config_score_and_selection(rk, oracle_mod):
