@@ -159,6 +159,12 @@ int restkv_timing_enable(int on);
 int restkv_timing_read(double* ms, int64_t* launches, int n_stages);
 const char* restkv_stage_name(int stage);   /* "gram", "attn_partial", ... */
 
+/*
+ * Debug aid: with on != 0 restkv_score runs bf16 inputs through the FP32 vector kernels
+ * instead of the MFMA kernels (same stages, every product in FP32).  Process-wide.
+ */
+int restkv_debug_force_fp32(int on);
+
 /* Static description of an error code. */
 const char* restkv_strerror(int code);
 

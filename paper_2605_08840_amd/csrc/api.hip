@@ -41,21 +41,25 @@ ScoreWs score_ws(const Prob& pb) {
   int S = (pb.L + 1023) / 1024;
   if (S < 1) S = 1;
   if (S > 64) S = 64;
-  w.S = S;
+  w.S_simple = S;
+  w.S_max = 64;
+  S = w.S_max;
+  w.ldv = (pb.P + 3) / 4 * 4;
   const size_t rows = (size_t)pb.Hq * pb.W;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   w.part_m = take(rows * S * 4);
   w.part_n = take(rows * S * 4);
+  w.part_ref = take(rows * S * 4);
   w.part_l = take(rows * S * 4);
   w.part_z = take(rows * S * (size_t)pb.d * 4);
   w.rs_m = take(rows * 4);
-  w.rs_invl = take(rows * 4);
+  w.rs_l = take(rows * 4);
   w.rs_zz = take(rows * 4);
   w.rs_nstar = take(rows * 4);
   w.rs_istar = take(rows * 4);
   w.rs_u = take(rows * (size_t)pb.d * 4);
-  w.vv = take((size_t)pb.Hq * pb.P * 4);
+  w.vv = take((size_t)pb.Hq * w.ldv * 4);
   w.bytes = off;
   return w;
 }
@@ -69,6 +73,8 @@ SmoothWs smooth_ws(const Prob& pb) {
   w.bytes = off;
   return w;
 }
+
+static bool g_force_fp32 = false;   // see restkv_debug_force_fp32
 
 static int check_ws(const void* ws, size_t have, size_t need) {
   if (!ws || ((uintptr_t)ws & 255u) || have < need) return RESTKV_EWORKSPACE;
@@ -107,6 +113,8 @@ int restkv_score(const restkv_params* p, const void* q, const void* k, const voi
   const ScoreWs lay = score_ws(pb);
   rc = check_ws(workspace, workspace_bytes, lay.bytes);
   if (rc) return rc;
+  if (mfma_eligible(pb, q, k, v) && !g_force_fp32)
+    return launch_score_mfma(pb, q, k, v, gram, score, (char*)workspace, lay, (hipStream_t)stream);
   return launch_score_simple(pb, q, k, v, gram, score, (char*)workspace, lay, (hipStream_t)stream);
 }
 
@@ -155,5 +163,10 @@ const char* restkv_strerror(int code) {
 }
 
 int restkv_version(void) { return 100; }
+
+int restkv_debug_force_fp32(int on) {
+  g_force_fp32 = on != 0;
+  return RESTKV_OK;
+}
 
 }  // extern "C"

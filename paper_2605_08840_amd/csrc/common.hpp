@@ -23,11 +23,13 @@ int resolve(const restkv_params* p, Prob* out);
 // ---- scratch layout ---------------------------------------------------------
 // All offsets are in bytes from the 256-byte aligned workspace base.
 struct ScoreWs {
-  int S;                 // key splits of the attention pass
-  size_t part_m, part_n, part_l, part_z;   // [Hkv*R*S] f32 / i32 / f32, [Hkv*R*S*d] f32
-  size_t rs_m, rs_invl, rs_zz, rs_nstar, rs_istar;   // [Hq*W]
+  int S_simple;          // key splits of the attention pass, FP32 path
+  int S_max;             // capacity of the split dimension
+  int ldv;               // row stride of vv (P rounded up to 4)
+  size_t part_m, part_n, part_ref, part_l, part_z;   // [Hq*W*S] , part_z [Hq*W*S*d] f32
+  size_t rs_m, rs_l, rs_zz, rs_nstar, rs_istar;   // [Hq*W]
   size_t rs_u;           // [Hq*W*d] f32   u = z M_h
-  size_t vv;             // [Hq*P] f32     v_n M_h v_n^T
+  size_t vv;             // [Hq*ldv] f32   v_n M_h v_n^T
   size_t bytes;
 };
 struct SmoothWs {
@@ -45,6 +47,9 @@ int launch_gram(const Prob& pb, const float* w_o, int64_t d_model, float* gram, 
 int launch_score_simple(const Prob& pb, const void* q, const void* k, const void* v,
                         const float* gram, float* score, char* ws, const ScoreWs& lay,
                         hipStream_t st);
+bool mfma_eligible(const Prob& pb, const void* q, const void* k, const void* v);
+int launch_score_mfma(const Prob& pb, const void* q, const void* k, const void* v, const float* gram,
+                      float* score, char* ws, const ScoreWs& lay, hipStream_t st);
 int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, int32_t* aws_info,
                   double* aws_d, char* ws, const SmoothWs& lay, hipStream_t st);
 int launch_select(const Prob& pb, const float* fin, int32_t* idx, hipStream_t st);

@@ -1,0 +1,121 @@
+// Pieces shared by the FP32 and the MFMA scoring paths: scratch pointers and the kernel
+// that merges the key splits of the attention pass into per-query statistics.
+#pragma once
+
+#include "common.hpp"
+
+namespace restkv {
+
+struct ScorePtrs {
+  float* part_m; int* part_n; float* part_ref; float* part_l; float* part_z;
+  float* rs_m; float* rs_l; float* rs_zz; int* rs_nstar; float* rs_istar; float* rs_u;
+  float* vv;
+};
+
+inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
+  ScorePtrs p;
+  p.part_m = (float*)(ws + lay.part_m); p.part_n = (int*)(ws + lay.part_n);
+  p.part_ref = (float*)(ws + lay.part_ref); p.part_l = (float*)(ws + lay.part_l);
+  p.part_z = (float*)(ws + lay.part_z);
+  p.rs_m = (float*)(ws + lay.rs_m); p.rs_l = (float*)(ws + lay.rs_l); p.rs_zz = (float*)(ws + lay.rs_zz);
+  p.rs_nstar = (int*)(ws + lay.rs_nstar); p.rs_istar = (float*)(ws + lay.rs_istar);
+  p.rs_u = (float*)(ws + lay.rs_u); p.vv = (float*)(ws + lay.vv);
+  return p;
+}
+
+// Per split s and query row the attention pass leaves (all logits in log2 units, scaled):
+//   part_m    largest logit seen (the split's champion), -inf if the split saw no key
+//   part_n    its key index
+//   part_ref  reference the sums are relative to
+//   part_l    sum over the other keys of 2^(logit - ref)
+//   part_z    sum over the other keys of 2^(logit - ref) * v
+// The merge keeps the overall champion apart and folds every other split champion back in:
+//   l = 1 + l_rest (relative to the champion), z = (v* + z_rest)/l, A* = 1/l,
+//   u = z M_h, zz = u.z, and the champion's indicator in its leave-one-out form
+//   I* = A* ||(z_rest/l_rest - v*) W_O||  (Eq. ori with Eq. relation; equals Eq. rec_ei).
+__device__ __forceinline__ float block_sum(float x, float* red, int nthreads) {
+  // wavefront reduce, then across wavefronts through LDS
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = x;
+  __syncthreads();
+  float tot = 0.f;
+  for (int j = 0; j < (nthreads + 63) / 64; ++j) tot += red[j];
+  return tot;
+}
+
+// one block of D threads per query row (global row = h*W + i)
+template <typename T, int D>
+__global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict__ v, int S,
+                                                    const float* __restrict__ gram,
+                                                    const float* __restrict__ part_m,
+                                                    const int* __restrict__ part_n,
+                                                    const float* __restrict__ part_ref,
+                                                    const float* __restrict__ part_l,
+                                                    const float* __restrict__ part_z,
+                                                    float* __restrict__ rs_m, float* __restrict__ rs_l,
+                                                    float* __restrict__ rs_zz, int* __restrict__ rs_nstar,
+                                                    float* __restrict__ rs_istar,
+                                                    float* __restrict__ rs_u) {
+  __shared__ float zs[D];
+  __shared__ float xs[D];
+  __shared__ float red[4];
+  const int row = blockIdx.x;               // h*W + i  ==  g*R + r
+  const int h = row / pb.W, g = h / pb.G;
+  const int c = threadIdx.x;
+  const T* vg = v + (int64_t)g * pb.kv_sh;
+  const int64_t o = (int64_t)row * S;
+
+  float M = -INFINITY;
+  int sstar = 0;
+  for (int s = 0; s < S; ++s) {
+    const float ms = part_m[o + s];
+    if (ms > M) { M = ms; sstar = s; }      // equal logits: the earlier split holds the lower key
+  }
+  const int nstar = part_n[o + sstar];
+  float lrest = 0.f, zr = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float ms = part_m[o + s];
+    if (ms == -INFINITY) continue;
+    const float wr = exp2f(part_ref[o + s] - M);   // the split's sums are relative to its reference
+    lrest += wr * part_l[o + s];
+    zr += wr * part_z[(o + s) * D + c];
+    if (s != sstar) {                        // a split's champion that lost joins the rest
+      const float w = exp2f(ms - M);
+      lrest += w;
+      zr += w * to_float(vg[(int64_t)part_n[o + s] * pb.kv_st + c]);
+    }
+  }
+  const float vstar = nstar >= 0 ? to_float(vg[(int64_t)nstar * pb.kv_st + c]) : 0.f;
+  const float l = 1.f + lrest;
+  const float z = (vstar + zr) / l;
+  const float x = lrest > 0.f ? zr / lrest - vstar : 0.f;   // z_without_champion - v_champion
+  zs[c] = z;
+  xs[c] = x;
+  __syncthreads();
+  float u = z, y = x;
+  if (gram) {
+    const float* Mh = gram + (int64_t)h * D * D;
+    u = 0.f; y = 0.f;
+    for (int a = 0; a < D; ++a) {
+      const float mv = Mh[a * D + c];
+      u = fmaf(zs[a], mv, u);
+      y = fmaf(xs[a], mv, y);
+    }
+  }
+  const float zz = block_sum(u * z, red, D);
+  const float qx = block_sum(y * x, red, D);
+  rs_u[(int64_t)row * D + c] = u;
+  if (c == 0) {
+    rs_m[row] = M;
+    rs_l[row] = l;
+    rs_zz[row] = zz;
+    rs_nstar[row] = nstar;
+    rs_istar[row] = sqrtf(fmaxf(qx, 0.f)) / l;      // A* ||(z_rest - v*) W_O||,  A* = 1/l
+  }
+}
+
+
+}  // namespace restkv

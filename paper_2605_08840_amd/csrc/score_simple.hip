@@ -13,7 +13,7 @@
 //   vv           : v_n M_h v_n^T for every prefix token and query head.
 //   score        : A/(1-A) * sqrt(zz - 2 u.v_n + vv) for all other tokens (Eq. rec_ei),
 //                  mean over the query heads of the group.
-#include "common.hpp"
+#include "score_common.hpp"
 
 namespace restkv {
 
@@ -44,6 +44,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(Prob pb, const T* __restri
                                                       const T* __restrict__ v, int S,
                                                       float* __restrict__ part_m,
                                                       int* __restrict__ part_n,
+                                                      float* __restrict__ part_ref,
                                                       float* __restrict__ part_l,
                                                       float* __restrict__ part_z) {
   __shared__ float Qs[RB][D];
@@ -143,99 +144,18 @@ __global__ __launch_bounds__(256) void k_attn_partial(Prob pb, const T* __restri
   }
   if (row_ok) {
     const int64_t o = ((int64_t)g * pb.R + r) * S + s;
-    if (ln == 0) { part_m[o] = m; part_n[o] = nstar; part_l[o] = l; }
+    if (ln == 0) { part_m[o] = m; part_n[o] = nstar; part_ref[o] = m; part_l[o] = l; }
 #pragma unroll
     for (int j = 0; j < NC; ++j) part_z[o * D + ln + 16 * j] = acc[j];
   }
   (void)hl;
 }
 
-__device__ __forceinline__ float block_sum(float x, float* red, int nthreads) {
-  // wavefront reduce, then across wavefronts through LDS
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-  const int w = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[w] = x;
-  __syncthreads();
-  float tot = 0.f;
-  for (int j = 0; j < (nthreads + 63) / 64; ++j) tot += red[j];
-  return tot;
-}
-
-// one block of D threads per query row (global row = h*W + i)
-template <typename T, int D>
-__global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict__ v, int S,
-                                                    const float* __restrict__ gram,
-                                                    const float* __restrict__ part_m,
-                                                    const int* __restrict__ part_n,
-                                                    const float* __restrict__ part_l,
-                                                    const float* __restrict__ part_z,
-                                                    float* __restrict__ rs_m, float* __restrict__ rs_l,
-                                                    float* __restrict__ rs_zz, int* __restrict__ rs_nstar,
-                                                    float* __restrict__ rs_istar,
-                                                    float* __restrict__ rs_u) {
-  __shared__ float zs[D];
-  __shared__ float xs[D];
-  __shared__ float red[4];
-  const int row = blockIdx.x;               // h*W + i  ==  g*R + r
-  const int h = row / pb.W, g = h / pb.G;
-  const int c = threadIdx.x;
-  const T* vg = v + (int64_t)g * pb.kv_sh;
-  const int64_t o = (int64_t)row * S;
-
-  float M = -INFINITY;
-  int sstar = 0;
-  for (int s = 0; s < S; ++s) {
-    const float ms = part_m[o + s];
-    if (ms > M) { M = ms; sstar = s; }      // equal logits: the earlier split holds the lower key
-  }
-  const int nstar = part_n[o + sstar];
-  float lrest = 0.f, zr = 0.f;
-  for (int s = 0; s < S; ++s) {
-    const float ms = part_m[o + s];
-    if (ms == -INFINITY) continue;
-    const float w = exp2f(ms - M);
-    lrest += w * part_l[o + s];
-    zr += w * part_z[(o + s) * D + c];
-    if (s != sstar) {                        // a split's champion that lost joins the rest
-      lrest += w;
-      zr += w * to_float(vg[(int64_t)part_n[o + s] * pb.kv_st + c]);
-    }
-  }
-  const float vstar = nstar >= 0 ? to_float(vg[(int64_t)nstar * pb.kv_st + c]) : 0.f;
-  const float l = 1.f + lrest;
-  const float z = (vstar + zr) / l;
-  const float x = lrest > 0.f ? zr / lrest - vstar : 0.f;   // z_without_champion - v_champion
-  zs[c] = z;
-  xs[c] = x;
-  __syncthreads();
-  float u = z, y = x;
-  if (gram) {
-    const float* Mh = gram + (int64_t)h * D * D;
-    u = 0.f; y = 0.f;
-    for (int a = 0; a < D; ++a) {
-      const float mv = Mh[a * D + c];
-      u = fmaf(zs[a], mv, u);
-      y = fmaf(xs[a], mv, y);
-    }
-  }
-  const float zz = block_sum(u * z, red, D);
-  const float qx = block_sum(y * x, red, D);
-  rs_u[(int64_t)row * D + c] = u;
-  if (c == 0) {
-    rs_m[row] = M;
-    rs_l[row] = l;
-    rs_zz[row] = zz;
-    rs_nstar[row] = nstar;
-    rs_istar[row] = sqrtf(fmaxf(qx, 0.f)) / l;      // A* ||(z_rest - v*) W_O||,  A* = 1/l
-  }
-}
-
 // vv[h, n] = v_n M_h v_n^T ; grid (ceil(P/64), Hq), 256 threads
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_vv(Prob pb, const T* __restrict__ v,
-                                            const float* __restrict__ gram, float* __restrict__ vv) {
+                                            const float* __restrict__ gram, float* __restrict__ vv,
+                                            int ldv) {
   __shared__ float Vs[64][D + 1];
   __shared__ float red[4][64];
   const int h = blockIdx.y, g = h / pb.G;
@@ -271,7 +191,7 @@ __global__ __launch_bounds__(256) void k_vv(Prob pb, const T* __restrict__ v,
   red[part][nl] = acc;
   __syncthreads();
   if (part == 0 && n0 + nl < pb.P)
-    vv[(int64_t)h * pb.P + n0 + nl] = red[0][nl] + red[1][nl] + red[2][nl] + red[3][nl];
+    vv[(int64_t)h * ldv + n0 + nl] = red[0][nl] + red[1][nl] + red[2][nl] + red[3][nl];
 }
 
 // grid (ceil(P/TN), Hkv), 256 threads
@@ -284,7 +204,7 @@ __global__ __launch_bounds__(256) void k_score(Prob pb, const T* __restrict__ q,
                                                const int* __restrict__ rs_nstar,
                                                const float* __restrict__ rs_istar,
                                                const float* __restrict__ rs_u,
-                                               const float* __restrict__ vv,
+                                               const float* __restrict__ vv, int ldv,
                                                float* __restrict__ score) {
   __shared__ float Qs[RB][D];
   __shared__ float Us[RB][D];
@@ -340,7 +260,7 @@ __global__ __launch_bounds__(256) void k_score(Prob pb, const T* __restrict__ q,
             cx = fmaf(Us[rl][c], Vs[kk][c], cx);
           }
           const float e = exp2f(dot * c2 - m);
-          const float dist2 = zz - 2.f * cx + vv[(int64_t)h * pb.P + n];
+          const float dist2 = zz - 2.f * cx + vv[(int64_t)h * ldv + n];
           float val = e / (l - e) * sqrtf(fmaxf(dist2, 0.f));
           if (n == nstar) val = istar;
           out[j] += val;
@@ -363,25 +283,16 @@ int run(const Prob& pb, const void* q, const void* k, const void* v, const float
   const T* qq = (const T*)q;
   const T* kk = (const T*)k;
   const T* vp = (const T*)v;
-  float* part_m = (float*)(ws + lay.part_m);
-  int* part_n = (int*)(ws + lay.part_n);
-  float* part_l = (float*)(ws + lay.part_l);
-  float* part_z = (float*)(ws + lay.part_z);
-  float* rs_m = (float*)(ws + lay.rs_m);
-  float* rs_l = (float*)(ws + lay.rs_invl);
-  float* rs_zz = (float*)(ws + lay.rs_zz);
-  int* rs_nstar = (int*)(ws + lay.rs_nstar);
-  float* rs_istar = (float*)(ws + lay.rs_istar);
-  float* rs_u = (float*)(ws + lay.rs_u);
-  float* vvb = (float*)(ws + lay.vv);
-  const int S = lay.S;
+  const ScorePtrs w = score_ptrs(ws, lay);
+  const int S = lay.S_simple;
   RK_LAUNCH(ST_ATTN, st, (k_attn_partial<T, D>), dim3(S, (pb.R + RB - 1) / RB, pb.Hkv), dim3(256), 0, st,
-                     pb, qq, kk, vp, S, part_m, part_n, part_l, part_z);
+                     pb, qq, kk, vp, S, w.part_m, w.part_n, w.part_ref, w.part_l, w.part_z);
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<T, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb, vp, S, gram,
-                     part_m, part_n, part_l, part_z, rs_m, rs_l, rs_zz, rs_nstar, rs_istar, rs_u);
-  RK_LAUNCH(ST_VV, st, (k_vv<T, D>), dim3((pb.P + 63) / 64, pb.Hq), dim3(256), 0, st, pb, vp, gram, vvb);
+            w.part_m, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m, w.rs_l, w.rs_zz, w.rs_nstar,
+            w.rs_istar, w.rs_u);
+  RK_LAUNCH(ST_VV, st, (k_vv<T, D>), dim3((pb.P + 63) / 64, pb.Hq), dim3(256), 0, st, pb, vp, gram, w.vv, lay.ldv);
   RK_LAUNCH(ST_SCORE, st, (k_score<T, D>), dim3((pb.P + TN - 1) / TN, pb.Hkv), dim3(256), 0, st, pb, qq,
-                     kk, vp, rs_m, rs_l, rs_zz, rs_nstar, rs_istar, rs_u, vvb, score);
+                     kk, vp, w.rs_m, w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, w.vv, lay.ldv, score);
   return hip_status();
 }
 
