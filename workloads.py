@@ -98,9 +98,9 @@ def make_qkv(w: Workload, layer: int = 0, device="cpu"):
         q += torch.bmm(cq, F.repeat_interleave(G, dim=0))
     elif w.structure == "drift":
         g = _gen(w, layer, 3, dev)
-        for h in range(Hkv):       # per head to bound the temporary
-            step = torch.randn((L, d), generator=g, device=dev, dtype=f32) * 0.01
-            k[h] += torch.cumsum(step, dim=0)
+        for h in range(Hkv):       # per head to bound the temporary; scan along the fast axis
+            step = torch.randn((d, L), generator=g, device=dev, dtype=f32) * 0.01
+            k[h] += torch.cumsum(step, dim=1).t()
     elif w.structure != "plain":
         raise ValueError(w.structure)
     dt = torch_dtype(w)
