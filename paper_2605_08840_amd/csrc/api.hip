@@ -70,6 +70,13 @@ SmoothWs smooth_ws(const Prob& pb) {
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   w.rowsum = take((size_t)pb.Hkv * pb.W * 8);
   w.ema = take((size_t)pb.Hkv * pb.ld * 4);
+  const size_t rows = (size_t)pb.Hkv * pb.W;
+  w.thr = take(rows * 8);
+  w.cnt_hi = take(rows * 4);
+  w.sum_hi = take(rows * 8);
+  w.ncand = take(rows * 4);
+  w.cand_val = take(rows * 4096 * 4);
+  w.cand_idx = take(rows * 4096 * 4);
   w.bytes = off;
   return w;
 }

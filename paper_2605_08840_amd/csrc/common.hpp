@@ -35,6 +35,9 @@ struct ScoreWs {
 struct SmoothWs {
   size_t rowsum;         // [Hkv*W] u64 index sums of the per-query top-B
   size_t ema;            // [Hkv*ld] f32 (used when the caller passes ema == NULL)
+  size_t thr;            // [Hkv*W] float2 bracket {lo, hi} of each row's top-B threshold
+  size_t cnt_hi, sum_hi, ncand;   // [Hkv*W] u32 / u64 / u32
+  size_t cand_val, cand_idx;      // [Hkv*W, 4096] f32 / i32 candidates inside the bracket
   size_t bytes;
 };
 ScoreWs score_ws(const Prob& pb);

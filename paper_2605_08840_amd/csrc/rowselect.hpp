@@ -90,6 +90,161 @@ __device__ inline void block_kth_key(const float* __restrict__ row, int n, int k
   k_eq = krem;
 }
 
+__device__ __forceinline__ float key_float(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+}
+
+constexpr int SEL_NS = 4096;     // samples / candidate capacity of the bracketed search
+
+// Block-wide counting on keys held in registers (NPT per thread; empty slots hold key 0, which
+// no pivot >= 1 counts).  One barrier per call; `it` alternates the two reduction buffers.
+struct CountSmem { uint32_t red[2][2][SEL_NW]; };
+
+template <int NPT>
+__device__ __forceinline__ void block_count_ge2(const uint32_t (&k)[NPT], uint32_t va, uint32_t vb,
+                                                CountSmem& cs, int& it, uint32_t& ca, uint32_t& cb) {
+  uint32_t a = 0, b = 0;
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    a += (uint32_t)__popcll(__ballot(k[j] >= va));
+    b += (uint32_t)__popcll(__ballot(k[j] >= vb));
+  }
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6, p = it & 1;
+  if ((threadIdx.x & 63) == 0) { cs.red[p][0][w] = a; cs.red[p][1][w] = b; }
+  __syncthreads();
+  a = 0; b = 0;
+  for (int j = 0; j < nw; ++j) { a += cs.red[p][0][j]; b += cs.red[p][1][j]; }
+  ca = a; cb = b;
+  ++it;
+}
+
+// Largest values ta, tb with count(key >= ta) >= ka and count(key >= tb) >= kb, i.e. the
+// ka-th and kb-th largest keys of the block (0 if fewer keys than that), bit by bit.
+// With low_bit > 0 only the bits above it are resolved (ta, tb are then lower bounds with the
+// unresolved bits zero).
+template <int NPT>
+__device__ inline void block_kth2(const uint32_t (&k)[NPT], uint32_t ka, uint32_t kb, CountSmem& cs,
+                                  int& it, uint32_t& ta, uint32_t& tb, int low_bit = 0) {
+  uint32_t a = 0, b = 0;
+  for (int bit = 31; bit >= low_bit; --bit) {
+    const uint32_t pa = a | (1u << bit), pb = b | (1u << bit);
+    uint32_t ca, cb;
+    block_count_ge2<NPT>(k, pa, pb, cs, it, ca, cb);
+    if (ca >= ka) a = pa;
+    if (cb >= kb) b = pb;
+  }
+  ta = a; tb = b;
+}
+
+// Sample ranks that bracket the k-th largest of a population of n from a sample of ns
+// (1-based, descending order): five standard deviations of the hypergeometric rank plus 2.
+__device__ __forceinline__ void bracket_ranks(int n, int ns, int k, int& r_hi, int& r_lo) {
+  const float f = (float)ns / (float)n;
+  const float kp = (float)k * f;
+  const int margin = (int)(5.0f * sqrtf(fmaxf(kp * (1.0f - f), 0.f))) + 2;
+  r_hi = (int)kp - margin;          // <= 0: no upper bound
+  r_lo = (int)kp + 2 + margin;      // > ns: no lower bound
+}
+
+// Evenly spread sample of a row in runs of RUN consecutive floats, NPT keys per thread
+// (the whole row if it has at most NPT*blockDim.x entries).  Returns the sample size.
+template <int NPT, int RUN>
+__device__ inline int block_sample_regs(const float* __restrict__ row, int n, uint32_t (&k)[NPT]) {
+  const int cap = NPT * blockDim.x;
+  if (n <= cap) {
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+      const int x = threadIdx.x + j * blockDim.x;
+      k[j] = x < n ? float_key(row[x]) : 0u;
+    }
+    return n;
+  }
+  const int nch = cap / RUN;
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    const int x = threadIdx.x + j * blockDim.x;
+    const int c = x / RUN, e = x % RUN;
+    const int start = (int)(((long long)c * (n - RUN)) / (nch - 1));
+    k[j] = float_key(row[start + e]);
+  }
+  return cap;
+}
+
+// Bracket {klo, khi} (keys) of the k-th largest of row[0..n): the k-th largest key lies in
+// (klo, khi] unless the sample misled us.  khi = 0xFFFFFFFF / klo = 0 mean "unbounded".
+template <int NPT, int RUN>
+__device__ inline void block_bracket(const float* __restrict__ row, int n, int k, CountSmem& cs, int& it,
+                                     uint32_t& klo, uint32_t& khi) {
+  uint32_t keys[NPT];
+  const int ns = block_sample_regs<NPT, RUN>(row, n, keys);
+  int r_hi, r_lo;
+  bracket_ranks(n, ns, k, r_hi, r_lo);
+  // a bracket only has to hold the threshold: 16 resolved bits (sign, exponent, 7 mantissa
+  // bits) are plenty; the upper end is rounded up, the lower end down
+  uint32_t thi, tlo;
+  block_kth2<NPT>(keys, (uint32_t)max(r_hi, 1), (uint32_t)min(r_lo, ns), cs, it, thi, tlo, 16);
+  khi = r_hi >= 1 ? (thi | 0xFFFFu) : 0xFFFFFFFFu;
+  klo = r_lo <= ns ? tlo : 0u;
+}
+
+// Same contract as block_kth_key, but the threshold is first bracketed from a sample; one pass
+// over the row then counts the elements above the bracket and collects the few inside it in
+// LDS, among which the threshold is found by bisection.  Falls back to the radix search when
+// the bracket misses (heavy ties, adversarial order).  `buf` holds SEL_NS uint32; the block has
+// SEL_NT threads.
+__device__ inline void block_kth_key_fast(const float* __restrict__ row, int n, int k, SelectSmem& sm,
+                                          CountSmem& cs, uint32_t* buf, uint32_t& tau, uint32_t& n_gt,
+                                          uint32_t& k_eq) {
+  constexpr int NPT = SEL_NS / SEL_NT;
+  int it = 0;
+  uint32_t klo, khi;
+  block_bracket<NPT, 1>(row, n, k, cs, it, klo, khi);   // smoothed rows: single, spread samples
+  if (threadIdx.x == 0) { sm.take = 0; sm.below = 0; }
+  __syncthreads();
+  uint32_t cnt = 0;
+  for (int x0 = threadIdx.x; x0 < n; x0 += 8 * blockDim.x) {
+    uint32_t kk[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {            // eight loads in flight
+      const int x = x0 + u * blockDim.x;
+      kk[u] = x < n ? float_key(row[x]) : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (kk[u] > khi) {
+        ++cnt;
+      } else if (kk[u] > klo) {
+        const uint32_t slot = atomicAdd(&sm.take, 1u);
+        if (slot < (uint32_t)SEL_NS) buf[slot] = kk[u];
+      }
+    }
+  }
+  if (cnt) atomicAdd(&sm.below, cnt);
+  __syncthreads();
+  const uint32_t nc = sm.take, above = sm.below;
+  const bool ok = above < (uint32_t)k && (uint32_t)k <= above + nc && nc <= (uint32_t)SEL_NS;
+  if (!ok) {                                  // block-uniform
+    __syncthreads();
+    block_kth_key(row, n, k, sm, tau, n_gt, k_eq);
+    return;
+  }
+  uint32_t ck[NPT];
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    const uint32_t x = threadIdx.x + j * blockDim.x;
+    ck[j] = x < nc ? buf[x] : 0u;
+  }
+  const uint32_t need = (uint32_t)k - above;
+  uint32_t t, dummy;
+  block_kth2<NPT>(ck, need, need, cs, it, t, dummy);
+  uint32_t cge, cgt;
+  block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);     // t < 0xFFFFFFFF for any real float
+  tau = t;
+  n_gt = above + cgt;
+  k_eq = need - cgt;
+  __syncthreads();
+}
+
 // Visits row[0..n) in position order, wave after wave; f(position, selected_rank)
 // is called for every selected element, ranks ascending with position.
 // Returns through `sm.cnt_*` nothing the caller needs.
@@ -101,12 +256,19 @@ __device__ inline void block_visit_topk(const float* __restrict__ row, int n, ui
   seg = (seg + 63) / 64 * 64;
   const int beg = min(n, w * seg), end = min(n, beg + seg);
   uint32_t cgt = 0, ceq = 0;
-  for (int x0 = beg; x0 < end; x0 += 64) {
-    const int x = x0 + lane;
-    const uint32_t key = x < end ? float_key(row[x]) : 0u;
-    const bool ok = x < end;
-    cgt += __popcll(__ballot(ok && key > tau));
-    ceq += __popcll(__ballot(ok && key == tau));
+  for (int x0 = beg; x0 < end; x0 += 512) {
+    uint32_t kk[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int x = x0 + 64 * u + lane;
+      kk[u] = x < end ? float_key(row[x]) : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const bool ok = x0 + 64 * u + lane < end;
+      cgt += __popcll(__ballot(ok && kk[u] > tau));
+      ceq += __popcll(__ballot(ok && kk[u] == tau));
+    }
   }
   __syncthreads();
   if (lane == 0) { sm.cnt_gt[w] = cgt; sm.cnt_eq[w] = ceq; }
@@ -116,17 +278,25 @@ __device__ inline void block_visit_topk(const float* __restrict__ row, int n, ui
     out_run += sm.cnt_gt[j] + min(sm.cnt_eq[j], k_eq - min(k_eq, eq_run));
     eq_run += sm.cnt_eq[j];
   }
-  for (int x0 = beg; x0 < end; x0 += 64) {
-    const int x = x0 + lane;
-    const bool ok = x < end;
-    const uint32_t key = ok ? float_key(row[x]) : 0u;
-    const bool gt = ok && key > tau, eq = ok && key == tau;
-    const unsigned long long beq = __ballot(eq);
-    const bool take = gt || (eq && eq_run + rank_in_ballot(beq) < k_eq);
-    const unsigned long long btk = __ballot(take);
-    if (take) f(x, out_run + rank_in_ballot(btk));
-    eq_run += __popcll(beq);
-    out_run += __popcll(btk);
+  for (int x0 = beg; x0 < end; x0 += 512) {
+    uint32_t kk[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int x = x0 + 64 * u + lane;
+      kk[u] = x < end ? float_key(row[x]) : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int x = x0 + 64 * u + lane;
+      const bool ok = x < end;
+      const bool gt = ok && kk[u] > tau, eq = ok && kk[u] == tau;
+      const unsigned long long beq = __ballot(eq);
+      const bool take = gt || (eq && eq_run + rank_in_ballot(beq) < k_eq);
+      const unsigned long long btk = __ballot(take);
+      if (take) f(x, out_run + rank_in_ballot(btk));
+      eq_run += __popcll(beq);
+      out_run += __popcll(btk);
+    }
   }
 }
 

@@ -287,83 +287,96 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* 
 }
 
 // ------------------------------------------------------------------------------------------
-// vv[h, n] = v_n M_h v_n^T.  Y^T = M_h V^T on the MFMA (M_h in LDS as bf16 hi + lo parts,
-// value rows straight from global memory as the B operand), then a row dot with v_n.
-// grid (key chunks, Hq), 256 threads; every wavefront takes 64 keys per iteration.
-template <int D>
-__global__ __launch_bounds__(256) void k_vv_mfma(Prob pb, const uint16_t* __restrict__ v,
-                                                 const float* __restrict__ gram,
-                                                 float* __restrict__ vv, int ldv, int blocks_per_wg) {
-  constexpr int KS = D / 16, CB = D / 32, MST = D + 8;
-  __shared__ __attribute__((aligned(16))) uint16_t Mhi[D * MST];
-  __shared__ __attribute__((aligned(16))) uint16_t Mlo[D * MST];
-  const int h = blockIdx.y, g = h / pb.G;
+// vv[h, n] = v_n M_h v_n^T :  Y^T = M_h V^T on the MFMA, then a row dot with v_n.
+// A wavefront owns 32 rows of one head's Gram matrix (hi + lo bf16 parts, resident in
+// registers for the whole kernel); the value tile in LDS is the B operand shared by all
+// wavefronts of the workgroup (HPW heads x D/32 row blocks).  Partial row dots of the D/32
+// wavefronts of a head meet in LDS.
+// grid (key chunks, ceil(G/HPW), Hkv), HPW*(D/32)*64 threads.
+template <int D, int HPW>
+__global__ __launch_bounds__(HPW * (D / 32) * 64) void k_vv_mfma(Prob pb, const uint16_t* __restrict__ v,
+                                                                 const float* __restrict__ gram,
+                                                                 float* __restrict__ vv, int ldv,
+                                                                 int tiles_per_wg) {
+  constexpr int KS = D / 16, CB = D / 32, KST = D + 8, NW = HPW * CB, NTHR = NW * 64;
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[2][TN * KST];
+  __shared__ float part[2][HPW][CB][TN];
+  const int g = blockIdx.z;
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
+  const int hw = wv / CB, mb = wv % CB;               // head inside the workgroup, Gram row block
+  const int hloc = blockIdx.y * HPW + hw;
+  const bool head_ok = hloc < pb.G;
+  const int h = g * pb.G + (head_ok ? hloc : 0);
   const uint16_t* vg = v + (int64_t)g * pb.kv_sh;
-  const float* Mh = gram + (int64_t)h * D * D;
-  for (int x = threadIdx.x; x < D * D; x += 256) {
-    const int a = x / D, c = x % D;
-    const float f = Mh[x];
-    const __bf16 hi = (__bf16)f;
-    const __bf16 lo = (__bf16)(f - (float)hi);
-    union { __bf16 b; uint16_t u; } u1, u2;
-    u1.b = hi; u2.b = lo;
-    Mhi[a * MST + c] = u1.u;
-    Mlo[a * MST + c] = u2.u;
-  }
-  __syncthreads();
-  for (int it = 0; it < blocks_per_wg; ++it) {
-    const int kb = ((blockIdx.x * blocks_per_wg + it) * 4 + wv) * 64;
-    if (kb >= pb.P) break;
-    bf16x8 vf[2][KS];
+
+  bf16x8 ahi[KS], alo[KS];
+  {
+    const float* mrow = gram + ((int64_t)h * D + 32 * mb + rr) * D;
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const int n = kb + 32 * nb + rr;
+    for (int ks = 0; ks < KS; ++ks) {
+      const f32x4 x0 = *(const f32x4*)(mrow + 16 * ks + 8 * hf);
+      const f32x4 x1 = *(const f32x4*)(mrow + 16 * ks + 8 * hf + 4);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        uint4 u = make_uint4(0, 0, 0, 0);
-        if (n < pb.P) u = *(const uint4*)(vg + (int64_t)n * pb.kv_st + 16 * ks + 8 * hf);
-        vf[nb][ks] = as_bf16x8(u);
+      for (int e = 0; e < 8; ++e) {
+        const float f = e < 4 ? x0[e] : x1[e - 4];
+        const __bf16 hi = (__bf16)f;
+        ahi[ks][e] = hi;
+        alo[ks][e] = (__bf16)(f - (float)hi);
       }
     }
-    f32x16 y[2][CB];
+  }
+  const int NT = (pb.P + TN - 1) / TN;
+  const int t0 = blockIdx.x * tiles_per_wg;
+  const int t1 = min(NT, t0 + tiles_per_wg);
+  if (t0 >= t1) return;
+
+  TileRegs<D, NTHR> tv;
+  tv.load(vg, pb.kv_st, t0 * TN, pb.L);
+  tv.store(Vs[0], KST);
+  __syncthreads();
+
+  for (int t = t0; t < t1; ++t) {
+    const int buf = (t - t0) & 1;
+    if (t + 1 < t1) tv.load(vg, pb.kv_st, (t + 1) * TN, pb.L);
+    f32x16 y[2];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-      for (int mb = 0; mb < CB; ++mb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) y[nb][mb][j] = 0.f;
+      for (int j = 0; j < 16; ++j) y[nb][j] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int mb = 0; mb < CB; ++mb) {
-        const bf16x8 ah = as_bf16x8(*(const uint4*)&Mhi[(32 * mb + rr) * MST + 16 * ks + 8 * hf]);
-        const bf16x8 al = as_bf16x8(*(const uint4*)&Mlo[(32 * mb + rr) * MST + 16 * ks + 8 * hf]);
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-          y[nb][mb] = MFMA(ah, vf[nb][ks], y[nb][mb]);
-          y[nb][mb] = MFMA(al, vf[nb][ks], y[nb][mb]);
-        }
+      for (int nb = 0; nb < 2; ++nb) {
+        const bf16x8 b = as_bf16x8(*(const uint4*)&Vs[buf][(32 * nb + rr) * KST + 16 * ks + 8 * hf]);
+        y[nb] = MFMA(ahi[ks], b, y[nb]);
+        y[nb] = MFMA(alo[ks], b, y[nb]);
       }
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-      const int n = kb + 32 * nb + rr;
       float acc = 0.f;
-      if (n < pb.P) {
-        const uint16_t* vr = vg + (int64_t)n * pb.kv_st;
 #pragma unroll
-        for (int mb = 0; mb < CB; ++mb)
-#pragma unroll
-          for (int jq = 0; jq < 4; ++jq) {
-            const uint2 u = *(const uint2*)(vr + 32 * mb + 8 * jq + 4 * hf);
-            acc = fmaf(y[nb][mb][4 * jq + 0], __uint_as_float(u.x << 16), acc);
-            acc = fmaf(y[nb][mb][4 * jq + 1], __uint_as_float(u.x & 0xFFFF0000u), acc);
-            acc = fmaf(y[nb][mb][4 * jq + 2], __uint_as_float(u.y << 16), acc);
-            acc = fmaf(y[nb][mb][4 * jq + 3], __uint_as_float(u.y & 0xFFFF0000u), acc);
-          }
+      for (int jq = 0; jq < 4; ++jq) {
+        const uint2 u = *(const uint2*)&Vs[buf][(32 * nb + rr) * KST + 32 * mb + 8 * jq + 4 * hf];
+        acc = fmaf(y[nb][4 * jq + 0], __uint_as_float(u.x << 16), acc);
+        acc = fmaf(y[nb][4 * jq + 1], __uint_as_float(u.x & 0xFFFF0000u), acc);
+        acc = fmaf(y[nb][4 * jq + 2], __uint_as_float(u.y << 16), acc);
+        acc = fmaf(y[nb][4 * jq + 3], __uint_as_float(u.y & 0xFFFF0000u), acc);
       }
       acc = xhalf_sum(acc);
-      if (hf == 0 && n < pb.P) vv[(int64_t)h * ldv + n] = acc;
+      if (hf == 0) part[buf][hw][mb][32 * nb + rr] = acc;
+    }
+    if (t + 1 < t1) tv.store(Vs[buf ^ 1], KST);
+    __syncthreads();
+    if (threadIdx.x < HPW * TN) {
+      const int hh = threadIdx.x / TN, key = threadIdx.x % TN;
+      const int n = t * TN + key;
+      const int hl2 = blockIdx.y * HPW + hh;
+      if (n < pb.P && hl2 < pb.G) {
+        float sum = 0.f;
+#pragma unroll
+        for (int m2 = 0; m2 < CB; ++m2) sum += part[buf][hh][m2][key];
+        vv[(int64_t)(g * pb.G + hl2) * ldv + n] = sum;
+      }
     }
   }
 }
@@ -577,10 +590,13 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
             (const bf16_t*)v, S, gram, w.part_m, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
             w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u);
   if (gram) {
-    const int bpw = 8;
-    const int chunks = (pb.P + 256 * bpw - 1) / (256 * bpw);
-    RK_LAUNCH(ST_VV, st, (k_vv_mfma<D>), dim3(chunks, pb.Hq), dim3(256), 0, st, pb, vp, gram, w.vv,
-              lay.ldv, bpw);
+    constexpr int HPW = D == 128 ? 2 : 4;
+    const int NTv = (pb.P + TN - 1) / TN;
+    const int hg = (pb.G + HPW - 1) / HPW;
+    int tpv = (int)(((int64_t)NTv * hg * pb.Hkv + 1023) / 1024);
+    if (tpv < 1) tpv = 1;
+    RK_LAUNCH(ST_VV, st, (k_vv_mfma<D, HPW>), dim3((NTv + tpv - 1) / tpv, hg, pb.Hkv),
+              dim3(HPW * (D / 32) * 64), 0, st, pb, vp, gram, w.vv, lay.ldv, tpv);
   } else {
     RK_LAUNCH(ST_VV, st, (k_vnorm2<D>), dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, vp,
               w.vv, lay.ldv);

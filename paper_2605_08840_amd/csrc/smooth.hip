@@ -1,32 +1,288 @@
 // Spatial-temporal smoothing (Sec. 3.3): EMA over the window queries, drift statistic of
 // the per-query top-B positions, adaptive window size / shift, shifted box mean.
+//
+// The raw score [Hkv, W, P] is read from HBM once: a sorted sample of every (head, query) row
+// brackets the row's top-B threshold; the fused pass computes the EMA and, per row, counts and
+// sums the positions above the bracket and collects the few entries inside it; a finishing
+// kernel decides the threshold exactly among those candidates.
 #include "rowselect.hpp"
 
 namespace restkv {
 
 namespace {
 
-// ema[g,n] by the recursion: first query as is, every later one enters with weight alpha.
-// grid (ceil(P/256), Hkv), 256 threads; reads of score are coalesced along n.
-__global__ __launch_bounds__(256) void k_ema(Prob pb, const float* __restrict__ score,
-                                             float* __restrict__ ema) {
-  const int g = blockIdx.y;
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  if (n >= pb.P) return;
-  const float* s = score + (int64_t)g * pb.W * pb.ld + n;
-  const float a = pb.alpha, b = 1.0f - pb.alpha;
-  float e = s[0];
-  for (int i = 1; i < pb.W; ++i) e = a * s[(int64_t)i * pb.ld] + b * e;
-  ema[(int64_t)g * pb.ld + n] = e;
+constexpr int CAND_CAP = 4096;      // candidates kept per (head, query) row
+constexpr int SMP_NS = 8192;        // samples per row for the bracket
+constexpr int RG = 4;               // rows per flush group of the fused pass
+constexpr int NPB = 1024;           // prefix positions per workgroup of the fused pass
+
+// Bracket of the top-min(B,P) threshold of one (head, query) row from a sample of the row.
+// thr[row] = {lo, hi}: the threshold lies in (lo, hi] unless the sample misled us (then the
+// finishing kernel falls back to the exact radix search).  Also clears the row's counters.
+// grid (W, Hkv), 256 threads, SMP_NS / 256 samples per thread in registers.
+__global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __restrict__ score,
+                                                        float2* __restrict__ thr,
+                                                        uint32_t* __restrict__ cnt_hi,
+                                                        unsigned long long* __restrict__ sum_hi,
+                                                        uint32_t* __restrict__ ncand) {
+  __shared__ CountSmem cs;
+  const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
+  const float* row = score + (int64_t)r * pb.ld;
+  const int k = min(pb.B, pb.P);
+  if (threadIdx.x == 0) { cnt_hi[r] = 0; sum_hi[r] = 0ull; ncand[r] = 0; }
+  if (k >= pb.P) {                       // every prefix position is taken: nothing to search
+    if (threadIdx.x == 0) thr[r] = make_float2(INFINITY, INFINITY);
+    return;
+  }
+  int it = 0;
+  uint32_t klo, khi;
+  block_bracket<SMP_NS / 256, 16>(row, pb.P, k, cs, it, klo, khi);
+  {
+    // when everything above the lower bound is expected to fit the candidate list, no upper
+    // bound is used (the fused pass then has a single test per entry)
+    const int ns = min(pb.P, SMP_NS);
+    int r_hi, r_lo;
+    bracket_ranks(pb.P, ns, k, r_hi, r_lo);
+    if ((float)r_lo * (float)pb.P / (float)ns <= 0.75f * (float)CAND_CAP) khi = 0xFFFFFFFFu;
+  }
+  if (threadIdx.x == 0)
+    thr[r] = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
 }
 
-// Sum of the positions of the top-min(B,P) entries of one (head, query) row of the raw score.
-// grid (W, Hkv), SEL_NT threads.
-__global__ __launch_bounds__(SEL_NT) void k_row_topk_sum(Prob pb, const float* __restrict__ score,
+// Fused single read of the raw score: EMA over the window queries (the recursion of Sec. 3.3:
+// first query as is, every later one enters with weight alpha) and, per (head, query) row,
+// the count / position sum of the entries above the bracket and the list of entries inside it.
+// A workgroup owns NPB prefix positions of one head for all W queries.  Entries above the
+// bracket go straight into per-row LDS counters; entries inside it are staged in an LDS list
+// that is flushed (one global atomic per row) at the end; an entry that finds the list full is
+// appended to its row directly.  grid (ceil(P/NPB), Hkv), 256 threads, 4 positions per thread.
+// sum of the positions of the set bits of a 64-bit lane mask (scalar work)
+__device__ __forceinline__ unsigned long long bit_position_sum(unsigned long long m) {
+  return (unsigned long long)(__popcll(m & 0xAAAAAAAAAAAAAAAAull) + 2 * __popcll(m & 0xCCCCCCCCCCCCCCCCull) +
+                              4 * __popcll(m & 0xF0F0F0F0F0F0F0F0ull) + 8 * __popcll(m & 0xFF00FF00FF00FF00ull) +
+                              16 * __popcll(m & 0xFFFF0000FFFF0000ull) + 32 * __popcll(m & 0xFFFFFFFF00000000ull));
+}
+
+constexpr int LIST_CAP = 6144;      // staged candidates per workgroup
+constexpr int ROWS_BLK = 256;       // rows between forced flushes (bounds the LDS counters)
+
+__global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restrict__ score,
+                                                  float* __restrict__ ema, const float2* __restrict__ thr,
+                                                  uint32_t* __restrict__ cnt_hi,
+                                                  unsigned long long* __restrict__ sum_hi,
+                                                  uint32_t* __restrict__ ncand,
+                                                  float* __restrict__ cand_val, int* __restrict__ cand_idx,
+                                                  int vec) {
+  __shared__ uint32_t list[LIST_CAP];     // position in the workgroup (10 bits) | row since flush << 10
+  __shared__ uint32_t lcnt, ccnt[ROWS_BLK], hcnt[ROWS_BLK], base[ROWS_BLK];
+  __shared__ unsigned long long hsum[ROWS_BLK];
+  const int g = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+  const unsigned long long lane_lt = (1ull << lane) - 1ull;
+  const int nb0 = blockIdx.x * NPB, n0 = nb0 + tid * 4;
+  const float* s = score + (int64_t)g * pb.W * pb.ld;
+  const float a = pb.alpha, b = 1.0f - pb.alpha;
+  const bool scan = pb.adaptive != 0;
+  if (tid == 0) lcnt = 0;
+  for (int x = tid; x < ROWS_BLK; x += 256) { ccnt[x] = 0; hcnt[x] = 0; hsum[x] = 0ull; }
+  __syncthreads();
+
+  // rows [rb0, rb1) have been scanned since the last flush
+  auto flush = [&](int rb0, int rb1) {
+    __syncthreads();
+    const uint32_t E = min(lcnt, (uint32_t)LIST_CAP);
+    for (uint32_t x = tid; x < E; x += 256) {
+      const uint32_t rl = (list[x] >> 10) & 255u;
+      list[x] |= atomicAdd(&ccnt[rl], 1u) << 18;
+    }
+    __syncthreads();
+    for (int x = tid; x < rb1 - rb0; x += 256) {
+      const int row = g * pb.W + rb0 + x;
+      if (ccnt[x]) base[x] = atomicAdd(&ncand[row], ccnt[x]);
+      if (hcnt[x]) { atomicAdd(&cnt_hi[row], hcnt[x]); atomicAdd(&sum_hi[row], hsum[x]); }
+    }
+    __syncthreads();
+    for (uint32_t x = tid; x < E; x += 256) {
+      const uint32_t en = list[x];
+      const uint32_t rl = (en >> 10) & 255u;
+      const uint32_t pos = base[rl] + (en >> 18);
+      if (pos < (uint32_t)CAND_CAP) {
+        const int n = nb0 + (int)(en & 1023u);
+        const int64_t o = (int64_t)(g * pb.W + rb0 + (int)rl) * CAND_CAP + pos;
+        cand_val[o] = s[(int64_t)(rb0 + (int)rl) * pb.ld + n];     // value read back (cache hit)
+        cand_idx[o] = n;
+      }
+    }
+    __syncthreads();
+    if (tid == 0) lcnt = 0;
+    for (int x = tid; x < ROWS_BLK; x += 256) { ccnt[x] = 0; hcnt[x] = 0; hsum[x] = 0ull; }
+    __syncthreads();
+  };
+
+  float e[4] = {0.f, 0.f, 0.f, 0.f};
+  // the rows of the next group are fetched while the current group is scanned
+  float xs[RG][4];
+  float2 ths[RG];
+  auto fetch = [&](int i0) {
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+      const int i = i0 + r;
+      if (i < pb.W) {
+        const float* rp = s + (int64_t)i * pb.ld + n0;
+        if (vec && n0 + 3 < pb.P) {
+          const float4 v4 = *(const float4*)rp;
+          xs[r][0] = v4.x; xs[r][1] = v4.y; xs[r][2] = v4.z; xs[r][3] = v4.w;
+        } else {
+#pragma unroll
+          for (int el = 0; el < 4; ++el) xs[r][el] = n0 + el < pb.P ? rp[el] : -INFINITY;
+        }
+        ths[r] = scan ? thr[g * pb.W + i] : make_float2(INFINITY, INFINITY);
+      }
+    }
+  };
+  fetch(0);
+  int rb0 = 0;                       // first row since the last flush
+  for (int i0 = 0; i0 < pb.W; i0 += RG) {
+    float xc[RG][4];
+    float2 thc[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+      thc[r] = ths[r];
+#pragma unroll
+      for (int el = 0; el < 4; ++el) xc[r][el] = xs[r][el];
+    }
+    if (i0 + RG < pb.W) fetch(i0 + RG);
+    if (scan && i0 + RG - rb0 > ROWS_BLK) {        // block-uniform: bounds the LDS row counters
+      flush(rb0, i0);
+      rb0 = i0;
+    }
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+      const int i = i0 + r;
+      if (i >= pb.W) break;
+      const float* x = xc[r];
+      const float2 th = thc[r];
+      const uint32_t rl = (uint32_t)(i - rb0);
+      const bool has_hi = th.y < INFINITY;        // wave-uniform (same row for every lane)
+      // hits are found with wave-wide ballots: one LDS atomic per wavefront and row
+      unsigned long long mh[4], mc[4];
+      uint32_t nh = 0, nc = 0;
+#pragma unroll
+      for (int el = 0; el < 4; ++el) {
+        e[el] = i == 0 ? x[el] : a * x[el] + b * e[el];
+        mh[el] = has_hi ? __ballot(x[el] > th.y) : 0ull;
+        mc[el] = __ballot(x[el] > th.x) & ~mh[el];
+        nh += (uint32_t)__popcll(mh[el]);
+        nc += (uint32_t)__popcll(mc[el]);
+      }
+      if (nh) {                                   // wave-uniform
+        unsigned long long ps = 0;
+#pragma unroll
+        for (int el = 0; el < 4; ++el)
+          ps += 4ull * bit_position_sum(mh[el]) +
+                (unsigned long long)__popcll(mh[el]) * (unsigned long long)(nb0 + (tid & ~63) * 4 + el);
+        if (lane == 0) { atomicAdd(&hcnt[rl], nh); atomicAdd(&hsum[rl], ps); }
+      }
+      if (nc) {                                   // wave-uniform
+        uint32_t slot0 = 0;
+        if (lane == 0) slot0 = atomicAdd(&lcnt, nc);
+        slot0 = __builtin_amdgcn_readfirstlane(slot0);
+#pragma unroll
+        for (int el = 0; el < 4; ++el) {
+          if ((mc[el] >> lane) & 1ull) {
+            const uint32_t slot = slot0 + (uint32_t)__popcll(mc[el] & lane_lt);
+            if (slot < (uint32_t)LIST_CAP) {
+              list[slot] = (uint32_t)(tid * 4 + el) | (rl << 10);
+            } else {                 // staging list full (a dense cluster of hits): append directly
+              const int row = g * pb.W + i;
+              const uint32_t pos = atomicAdd(&ncand[row], 1u);
+              if (pos < (uint32_t)CAND_CAP) {
+                cand_val[(int64_t)row * CAND_CAP + pos] = x[el];
+                cand_idx[(int64_t)row * CAND_CAP + pos] = n0 + el;
+              }
+            }
+          }
+          slot0 += (uint32_t)__popcll(mc[el]);
+        }
+      }
+    }
+  }
+  if (scan) flush(rb0, pb.W);
+#pragma unroll
+  for (int el = 0; el < 4; ++el)
+    if (n0 + el < pb.P) ema[(int64_t)g * pb.ld + n0 + el] = e[el];
+}
+
+constexpr unsigned long long ROW_PENDING = ~0ull;   // rowsum marker: the bracket missed this row
+
+// Sum of the positions of the top-min(B,P) entries of one (head, query) row: the entries above
+// the bracket were summed by the fused pass; the threshold is found among the candidates by
+// bisection on their keys, equal values are taken in position order (a second bisection on the
+// position, only when a tie straddles the cut).  A row whose bracket missed is marked pending
+// and searched exactly by k_row_fallback.  grid (W, Hkv), 256 threads.
+__global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __restrict__ cnt_hi,
+                                                    const unsigned long long* __restrict__ sum_hi,
+                                                    const uint32_t* __restrict__ ncand,
+                                                    const float* __restrict__ cand_val,
+                                                    const int* __restrict__ cand_idx,
+                                                    unsigned long long* __restrict__ rowsum) {
+  constexpr int NPT = CAND_CAP / 256;
+  __shared__ CountSmem cs;
+  __shared__ unsigned long long isum[4];
+  const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
+  const int k = min(pb.B, pb.P);
+  if (k >= pb.P) {
+    if (threadIdx.x == 0) rowsum[r] = (unsigned long long)pb.P * (unsigned long long)(pb.P - 1) / 2ull;
+    return;
+  }
+  const uint32_t ch = cnt_hi[r], nc = ncand[r];
+  const bool ok = ch < (uint32_t)k && (uint32_t)k <= ch + nc && nc <= (uint32_t)CAND_CAP;
+  if (!ok) {
+    if (threadIdx.x == 0) rowsum[r] = ROW_PENDING;
+    return;
+  }
+  const uint32_t need = (uint32_t)k - ch;
+  uint32_t ck[NPT], ci[NPT];
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    const uint32_t x = threadIdx.x + j * 256;
+    const int64_t o = (int64_t)r * CAND_CAP + x;
+    ck[j] = x < nc ? float_key(cand_val[o]) : 0u;
+    ci[j] = x < nc ? (uint32_t)cand_idx[o] : 0u;
+  }
+  int it = 0;
+  uint32_t t, dummy, cge, cgt;
+  block_kth2<NPT>(ck, need, need, cs, it, t, dummy);
+  block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);
+  const uint32_t k_eq = need - cgt;              // ties at t to take, lowest positions first
+  uint32_t pos_cut = 0xFFFFFFFFu;                // take tied entries with position <= pos_cut
+  if (cge - cgt > k_eq) {
+    // k_eq-th smallest position among the ties = k_eq-th largest inverted position
+    uint32_t inv[NPT];
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) inv[j] = ck[j] == t ? 0xFFFFFFFFu - ci[j] : 0u;
+    uint32_t ti;
+    block_kth2<NPT>(inv, k_eq, k_eq, cs, it, ti, dummy);
+    pos_cut = 0xFFFFFFFFu - ti;
+  }
+  unsigned long long acc = 0;
+#pragma unroll
+  for (int j = 0; j < NPT; ++j)
+    if (ck[j] > t || (ck[j] == t && ci[j] <= pos_cut)) acc += (unsigned long long)ci[j];
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  if ((threadIdx.x & 63) == 0) isum[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) rowsum[r] = isum[0] + isum[1] + isum[2] + isum[3] + sum_hi[r];
+}
+
+// Exact search (radix select + ordered visit) of the rows k_row_finish marked pending.
+// grid (W, Hkv), SEL_NT threads; a workgroup whose row is done exits at once.
+__global__ __launch_bounds__(SEL_NT) void k_row_fallback(Prob pb, const float* __restrict__ score,
                                                          unsigned long long* __restrict__ rowsum) {
   __shared__ SelectSmem sm;
-  const int i = blockIdx.x, g = blockIdx.y;
-  const float* row = score + ((int64_t)g * pb.W + i) * pb.ld;
+  const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
+  if (rowsum[r] != ROW_PENDING) return;
+  const float* row = score + (int64_t)r * pb.ld;
   const int k = min(pb.B, pb.P);
   uint32_t tau, n_gt, k_eq;
   block_kth_key(row, pb.P, k, sm, tau, n_gt, k_eq);
@@ -40,7 +296,7 @@ __global__ __launch_bounds__(SEL_NT) void k_row_topk_sum(Prob pb, const float* _
   if (threadIdx.x == 0) {
     unsigned long long tot = 0;
     for (int j = 0; j < SEL_NW; ++j) tot += sm.isum[j];
-    rowsum[g * pb.W + i] = tot;
+    rowsum[r] = tot;
   }
 }
 
@@ -73,13 +329,19 @@ __global__ __launch_bounds__(256) void k_box(Prob pb, const float* __restrict__ 
                                              float* __restrict__ fin, int32_t* __restrict__ aws_info,
                                              double* __restrict__ aws_d) {
   const int g = blockIdx.y;
-  int w_s, gamma;
-  double df, dr;
-  aws_window(pb, rowsum, g, w_s, gamma, df, dr);
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    if (aws_info) { aws_info[2 * g] = w_s; aws_info[2 * g + 1] = gamma; }
-    if (aws_d) { aws_d[2 * g] = df; aws_d[2 * g + 1] = dr; }
+  __shared__ int sh_ws, sh_gamma;
+  if (threadIdx.x == 0) {
+    int w_s0, gamma0;
+    double df, dr;
+    aws_window(pb, rowsum, g, w_s0, gamma0, df, dr);
+    sh_ws = w_s0; sh_gamma = gamma0;
+    if (blockIdx.x == 0) {
+      if (aws_info) { aws_info[2 * g] = w_s0; aws_info[2 * g + 1] = gamma0; }
+      if (aws_d) { aws_d[2 * g] = df; aws_d[2 * g + 1] = dr; }
+    }
   }
+  __syncthreads();
+  const int w_s = sh_ws, gamma = sh_gamma;
   const int n = blockIdx.x * 256 + threadIdx.x;
   if (n >= pb.P) return;
   const float* e = ema + (int64_t)g * pb.ld;
@@ -95,12 +357,26 @@ __global__ __launch_bounds__(256) void k_box(Prob pb, const float* __restrict__ 
 int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, int32_t* aws_info,
                   double* aws_d, char* ws, const SmoothWs& lay, hipStream_t st) {
   unsigned long long* rowsum = (unsigned long long*)(ws + lay.rowsum);
+  float2* thr = (float2*)(ws + lay.thr);
+  uint32_t* cnt_hi = (uint32_t*)(ws + lay.cnt_hi);
+  unsigned long long* sum_hi = (unsigned long long*)(ws + lay.sum_hi);
+  uint32_t* ncand = (uint32_t*)(ws + lay.ncand);
+  float* cand_val = (float*)(ws + lay.cand_val);
+  int* cand_idx = (int*)(ws + lay.cand_idx);
   float* e = ema ? ema : (float*)(ws + lay.ema);
-  const dim3 gl((pb.P + 255) / 256, pb.Hkv);
-  RK_LAUNCH(ST_EMA, st, k_ema, gl, dim3(256), 0, st, pb, score, e);
+  const int vec = ((pb.ld & 3) == 0 && ((uintptr_t)score & 15u) == 0) ? 1 : 0;
   if (pb.adaptive)
-    RK_LAUNCH(ST_ROWTOPK, st, k_row_topk_sum, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
-  RK_LAUNCH(ST_BOX, st, k_box, gl, dim3(256), 0, st, pb, e, rowsum, fin, aws_info, aws_d);
+    RK_LAUNCH(ST_ROWTOPK, st, k_sample_bracket, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, score, thr,
+              cnt_hi, sum_hi, ncand);
+  RK_LAUNCH(ST_EMA, st, k_ema_scan, dim3((pb.P + NPB - 1) / NPB, pb.Hkv), dim3(256), 0, st, pb, score, e,
+            thr, cnt_hi, sum_hi, ncand, cand_val, cand_idx, vec);
+  if (pb.adaptive) {
+    RK_LAUNCH(ST_ROWTOPK, st, k_row_finish, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, cnt_hi, sum_hi,
+              ncand, cand_val, cand_idx, rowsum);
+    RK_LAUNCH(ST_ROWTOPK, st, k_row_fallback, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
+  }
+  RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, e, rowsum, fin,
+            aws_info, aws_d);
   return hip_status();
 }
 
