@@ -49,6 +49,7 @@ ScoreWs score_ws(const Prob& pb) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   w.part_m = take(rows * S * 4);
+  w.part_mx = take(rows * S * 4);
   w.part_n = take(rows * S * 4);
   w.part_ref = take(rows * S * 4);
   w.part_l = take(rows * S * 4);
@@ -97,8 +98,10 @@ extern "C" {
 size_t restkv_workspace_bytes(const restkv_params* p) {
   Prob pb;
   if (resolve(p, &pb) != RESTKV_OK) return 0;
-  const size_t a = score_ws(pb).bytes, b = smooth_ws(pb).bytes;
-  return a > b ? a : b;
+  size_t n = score_ws(pb).bytes;
+  if (smooth_ws(pb).bytes > n) n = smooth_ws(pb).bytes;
+  if (select_ws_bytes(pb) > n) n = select_ws_bytes(pb);
+  return n;
 }
 
 int restkv_prepare_wo(const restkv_params* p, const float* w_o, int64_t d_model, float* gram,
@@ -141,12 +144,13 @@ int restkv_smooth(const restkv_params* p, const float* score, float* ema, float*
 
 int restkv_select(const restkv_params* p, const float* final_score, int32_t* idx, void* workspace,
                   size_t workspace_bytes, restkv_stream_t stream) {
-  (void)workspace; (void)workspace_bytes;   // selection keeps its state in LDS
   Prob pb;
   int rc = resolve(p, &pb);
   if (rc) return rc;
   if (!final_score || !idx) return RESTKV_EINVAL;
-  return launch_select(pb, final_score, idx, (hipStream_t)stream);
+  rc = check_ws(workspace, workspace_bytes, select_ws_bytes(pb));
+  if (rc) return rc;
+  return launch_select(pb, final_score, idx, (char*)workspace, (hipStream_t)stream);
 }
 
 int restkv_compact(const restkv_params* p, const void* k, const void* v, const int32_t* idx,

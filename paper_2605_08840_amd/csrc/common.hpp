@@ -26,7 +26,7 @@ struct ScoreWs {
   int S_simple;          // key splits of the attention pass, FP32 path
   int S_max;             // capacity of the split dimension
   int ldv;               // row stride of vv (P rounded up to 4)
-  size_t part_m, part_n, part_ref, part_l, part_z;   // [Hq*W*S] , part_z [Hq*W*S*d] f32
+  size_t part_m, part_mx, part_n, part_ref, part_l, part_z;   // [Hq*W*S] , part_z [Hq*W*S*d] f32
   size_t rs_m, rs_l, rs_zz, rs_nstar, rs_istar;   // [Hq*W]
   size_t rs_u;           // [Hq*W*d] f32   u = z M_h
   size_t vv;             // [Hq*ldv] f32   v_n M_h v_n^T
@@ -55,7 +55,8 @@ int launch_score_mfma(const Prob& pb, const void* q, const void* k, const void* 
                       float* score, char* ws, const ScoreWs& lay, hipStream_t st);
 int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, int32_t* aws_info,
                   double* aws_d, char* ws, const SmoothWs& lay, hipStream_t st);
-int launch_select(const Prob& pb, const float* fin, int32_t* idx, hipStream_t st);
+size_t select_ws_bytes(const Prob& pb);
+int launch_select(const Prob& pb, const float* fin, int32_t* idx, char* ws, hipStream_t st);
 int launch_compact(const Prob& pb, const void* k, const void* v, const int32_t* idx, void* k_out,
                    void* v_out, hipStream_t st);
 
@@ -82,6 +83,19 @@ struct bf16_t { uint16_t x; };
 
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(bf16_t v) { return __uint_as_float(((uint32_t)v.x) << 16); }
+
+// Sum over the 64 lanes of a wavefront, result in every lane: rotations inside the 16-lane
+// DPP rows, then the two row swaps of gfx950 (no LDS traffic).
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
+  x += __builtin_amdgcn_update_dpp(0u, x, 0x121, 0xF, 0xF, false);   // row_ror:1
+  x += __builtin_amdgcn_update_dpp(0u, x, 0x122, 0xF, 0xF, false);   // row_ror:2
+  x += __builtin_amdgcn_update_dpp(0u, x, 0x124, 0xF, 0xF, false);   // row_ror:4
+  x += __builtin_amdgcn_update_dpp(0u, x, 0x128, 0xF, 0xF, false);   // row_ror:8
+  auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  x = r[0] + r[1];
+  r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  return r[0] + r[1];
+}
 
 // Order-preserving map float -> uint32 (larger float <=> larger key; -0 < +0).
 __device__ __forceinline__ uint32_t float_key(float f) {

@@ -103,19 +103,47 @@ struct CountSmem { uint32_t red[2][2][SEL_NW]; };
 template <int NPT>
 __device__ __forceinline__ void block_count_ge2(const uint32_t (&k)[NPT], uint32_t va, uint32_t vb,
                                                 CountSmem& cs, int& it, uint32_t& ca, uint32_t& cb) {
-  uint32_t a = 0, b = 0;
+  uint32_t a = 0, b = 0;            // per-lane counts (vector ALU), reduced across the wave below
 #pragma unroll
   for (int j = 0; j < NPT; ++j) {
-    a += (uint32_t)__popcll(__ballot(k[j] >= va));
-    b += (uint32_t)__popcll(__ballot(k[j] >= vb));
+    a += k[j] >= va ? 1u : 0u;
+    b += k[j] >= vb ? 1u : 0u;
   }
+  const uint32_t ab = wave_sum(a | (b << 16));   // NPT * 64 < 65536: both counts in one register
   const int w = threadIdx.x >> 6, nw = blockDim.x >> 6, p = it & 1;
-  if ((threadIdx.x & 63) == 0) { cs.red[p][0][w] = a; cs.red[p][1][w] = b; }
+  if ((threadIdx.x & 63) == 0) cs.red[p][0][w] = ab;
   __syncthreads();
   a = 0; b = 0;
-  for (int j = 0; j < nw; ++j) { a += cs.red[p][0][j]; b += cs.red[p][1][j]; }
+  for (int j = 0; j < nw; ++j) { const uint32_t x = cs.red[p][0][j]; a += x & 0xFFFFu; b += x >> 16; }
   ca = a; cb = b;
   ++it;
+}
+
+template <int NPT>
+__device__ __forceinline__ uint32_t block_count_ge(const uint32_t (&k)[NPT], uint32_t v, CountSmem& cs,
+                                                   int& it) {
+  uint32_t a = 0;
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) a += k[j] >= v ? 1u : 0u;
+  a = wave_sum(a);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6, p = it & 1;
+  if ((threadIdx.x & 63) == 0) cs.red[p][0][w] = a;
+  __syncthreads();
+  a = 0;
+  for (int j = 0; j < nw; ++j) a += cs.red[p][0][j];
+  ++it;
+  return a;
+}
+
+// k-th largest key of the block (largest t with count(key >= t) >= k), bit by bit.
+template <int NPT>
+__device__ inline uint32_t block_kth(const uint32_t (&k)[NPT], uint32_t kk, CountSmem& cs, int& it) {
+  uint32_t a = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t pa = a | (1u << bit);
+    if (block_count_ge<NPT>(k, pa, cs, it) >= kk) a = pa;
+  }
+  return a;
 }
 
 // Largest values ta, tb with count(key >= ta) >= ka and count(key >= tb) >= kb, i.e. the
@@ -235,8 +263,7 @@ __device__ inline void block_kth_key_fast(const float* __restrict__ row, int n, 
     ck[j] = x < nc ? buf[x] : 0u;
   }
   const uint32_t need = (uint32_t)k - above;
-  uint32_t t, dummy;
-  block_kth2<NPT>(ck, need, need, cs, it, t, dummy);
+  const uint32_t t = block_kth<NPT>(ck, need, cs, it);
   uint32_t cge, cgt;
   block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);     // t < 0xFFFFFFFF for any real float
   tau = t;

@@ -7,14 +7,15 @@
 namespace restkv {
 
 struct ScorePtrs {
-  float* part_m; int* part_n; float* part_ref; float* part_l; float* part_z;
+  float* part_m; float* part_mx; int* part_n; float* part_ref; float* part_l; float* part_z;
   float* rs_m; float* rs_l; float* rs_zz; int* rs_nstar; float* rs_istar; float* rs_u;
   float* vv;
 };
 
 inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
   ScorePtrs p;
-  p.part_m = (float*)(ws + lay.part_m); p.part_n = (int*)(ws + lay.part_n);
+  p.part_m = (float*)(ws + lay.part_m); p.part_mx = (float*)(ws + lay.part_mx);
+  p.part_n = (int*)(ws + lay.part_n);
   p.part_ref = (float*)(ws + lay.part_ref); p.part_l = (float*)(ws + lay.part_l);
   p.part_z = (float*)(ws + lay.part_z);
   p.rs_m = (float*)(ws + lay.rs_m); p.rs_l = (float*)(ws + lay.rs_l); p.rs_zz = (float*)(ws + lay.rs_zz);
@@ -24,15 +25,19 @@ inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
 }
 
 // Per split s and query row the attention pass leaves (all logits in log2 units, scaled):
-//   part_m    largest logit seen (the split's champion), -inf if the split saw no key
-//   part_n    its key index
+//   part_m    largest logit seen, -inf if the split saw no key
+//   part_mx   logit of the key the split kept OUT of its sums (valid if part_n >= 0)
+//   part_n    index of that key, or -1
 //   part_ref  reference the sums are relative to
-//   part_l    sum over the other keys of 2^(logit - ref)
-//   part_z    sum over the other keys of 2^(logit - ref) * v
-// The merge keeps the overall champion apart and folds every other split champion back in:
-//   l = 1 + l_rest (relative to the champion), z = (v* + z_rest)/l, A* = 1/l,
-//   u = z M_h, zz = u.z, and the champion's indicator in its leave-one-out form
-//   I* = A* ||(z_rest/l_rest - v*) W_O||  (Eq. ori with Eq. relation; equals Eq. rec_ei).
+//   part_l    sum over the included keys of 2^(logit - ref)
+//   part_z    sum over the included keys of 2^(logit - ref) * v
+// A split keeps a key out when, on arrival, it is the largest so far and holds more than 1/9
+// of the mass seen so far (always true for a key that ends with more than 1/9 of the total).
+// The merge keeps out the excluded key that is the overall maximum (if any) and folds every
+// other excluded key back in.  With a key kept out ("champion", weight A* = 1/l):
+//   l = 1 + l_rest, z = (v* + z_rest)/l, u = z M_h, zz = u.z, and the champion's indicator
+//   in its leave-one-out form I* = A* ||(z_rest/l_rest - v*) W_O||  (Eq. ori with Eq. relation;
+//   equals Eq. rec_ei).  Without one, l and z are the plain softmax sums relative to the maximum.
 __device__ __forceinline__ float block_sum(float x, float* red, int nthreads) {
   // wavefront reduce, then across wavefronts through LDS
 #pragma unroll
@@ -51,6 +56,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict__ v, int S,
                                                     const float* __restrict__ gram,
                                                     const float* __restrict__ part_m,
+                                                    const float* __restrict__ part_mx,
                                                     const int* __restrict__ part_n,
                                                     const float* __restrict__ part_ref,
                                                     const float* __restrict__ part_l,
@@ -69,12 +75,11 @@ __global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict
   const int64_t o = (int64_t)row * S;
 
   float M = -INFINITY;
-  int sstar = 0;
-  for (int s = 0; s < S; ++s) {
-    const float ms = part_m[o + s];
-    if (ms > M) { M = ms; sstar = s; }      // equal logits: the earlier split holds the lower key
-  }
-  const int nstar = part_n[o + sstar];
+  for (int s = 0; s < S; ++s) M = fmaxf(M, part_m[o + s]);
+  int sstar = -1;                            // split whose kept-out key is the overall maximum
+  for (int s = 0; s < S; ++s)
+    if (sstar < 0 && part_n[o + s] >= 0 && part_mx[o + s] == M) sstar = s;   // earliest split = lowest key
+  const int nstar = sstar >= 0 ? part_n[o + sstar] : -1;
   float lrest = 0.f, zr = 0.f;
   for (int s = 0; s < S; ++s) {
     const float ms = part_m[o + s];
@@ -82,16 +87,23 @@ __global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict
     const float wr = exp2f(part_ref[o + s] - M);   // the split's sums are relative to its reference
     lrest += wr * part_l[o + s];
     zr += wr * part_z[(o + s) * D + c];
-    if (s != sstar) {                        // a split's champion that lost joins the rest
-      const float w = exp2f(ms - M);
+    if (s != sstar && part_n[o + s] >= 0) {        // a kept-out key that is not the maximum joins the rest
+      const float w = exp2f(part_mx[o + s] - M);
       lrest += w;
       zr += w * to_float(vg[(int64_t)part_n[o + s] * pb.kv_st + c]);
     }
   }
-  const float vstar = nstar >= 0 ? to_float(vg[(int64_t)nstar * pb.kv_st + c]) : 0.f;
-  const float l = 1.f + lrest;
-  const float z = (vstar + zr) / l;
-  const float x = lrest > 0.f ? zr / lrest - vstar : 0.f;   // z_without_champion - v_champion
+  float l, z, x;
+  if (nstar >= 0) {
+    const float vstar = to_float(vg[(int64_t)nstar * pb.kv_st + c]);
+    l = 1.f + lrest;
+    z = (vstar + zr) / l;
+    x = lrest > 0.f ? zr / lrest - vstar : 0.f;   // z_without_champion - v_champion
+  } else {
+    l = lrest;
+    z = zr / l;
+    x = 0.f;
+  }
   zs[c] = z;
   xs[c] = x;
   __syncthreads();

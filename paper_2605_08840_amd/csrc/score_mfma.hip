@@ -129,8 +129,8 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* 
   const int vis_last = (pb.causal && ri.valid) ? pb.P + ri.i : pb.L - 1;
   const float c2 = pb.scale * LOG2E;
 
-  float m = -INFINITY, mref = -INFINITY, lsum = 0.f;
-  int nstar = -1;
+  float mall = -INFINITY, mref = -INFINITY, mx = -INFINITY, lsum = 0.f;
+  int nx = -1;                       // key kept out of the sums (see below), -1: none
   f32x16 oacc[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb)
@@ -188,37 +188,51 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* 
       for (int j = 0; j < 16; ++j) tm = fmaxf(tm, sacc[mb][j]);
     tm = xhalf_max(tm);
 
-    const bool newchamp = tm > m;
+    // A key is kept out of the sums only if, on arrival, it is the largest so far AND would
+    // hold more than 1/9 of the mass seen so far; such keys are rare after the first tile, so
+    // the expensive part of the bookkeeping (index search, folding the previous kept-out key
+    // back in) almost never runs.  The reference of the exponentials follows the maximum lazily.
+    const bool newmax = tm > mall;
     const bool resc = (tm - mref) * c2 > RESCALE_TH;
-    const bool slow = __ballot(newchamp || resc) != 0ull;
-    if (slow) {
-      int cand = INT_MAX;
-      if (newchamp) {
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int j = 0; j < 16; ++j)
-            if (sacc[mb][j] == tm) cand = min(cand, kb + 32 * mb + cidx(j, hf));
+    bool excl_here = false;
+    if (__ballot(newmax || resc) != 0ull) {
+      bool dominant = false;
+      if (newmax) {
+        const float pstar = __builtin_amdgcn_exp2f((tm - mref) * c2);      // inf on the first tile
+        float total = xhalf_sum(lsum);
+        if (nx >= 0) total += __builtin_amdgcn_exp2f((mx - mref) * c2);
+        dominant = pstar * 8.0f > total;
       }
-      cand = xhalf_min(cand);
-      if (newchamp) {
-        if (nstar >= 0) {          // the dethroned champion joins the running sums
-          const float w = __builtin_amdgcn_exp2f((m - mref) * c2);
-          if (hf == 0) lsum += w;
-          const uint16_t* vr = vg + (int64_t)nstar * pb.kv_st;
+      if (__ballot(dominant) != 0ull) {
+        int cand = INT_MAX;
+        if (dominant) {
 #pragma unroll
-          for (int cb = 0; cb < CB; ++cb)
+          for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int jq = 0; jq < 4; ++jq) {
-              const uint2 u = *(const uint2*)(vr + 32 * cb + 8 * jq + 4 * hf);
-              oacc[cb][4 * jq + 0] += w * __uint_as_float(u.x << 16);
-              oacc[cb][4 * jq + 1] += w * __uint_as_float(u.x & 0xFFFF0000u);
-              oacc[cb][4 * jq + 2] += w * __uint_as_float(u.y << 16);
-              oacc[cb][4 * jq + 3] += w * __uint_as_float(u.y & 0xFFFF0000u);
-            }
+            for (int j = 0; j < 16; ++j)
+              if (sacc[mb][j] == tm) cand = min(cand, kb + 32 * mb + cidx(j, hf));
         }
-        m = tm;
-        nstar = cand;
+        cand = xhalf_min(cand);
+        if (dominant) {
+          if (nx >= 0) {             // the key kept out so far joins the running sums
+            const float w = __builtin_amdgcn_exp2f((mx - mref) * c2);
+            if (hf == 0) lsum += w;
+            const uint16_t* vr = vg + (int64_t)nx * pb.kv_st;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+              for (int jq = 0; jq < 4; ++jq) {
+                const uint2 u = *(const uint2*)(vr + 32 * cb + 8 * jq + 4 * hf);
+                oacc[cb][4 * jq + 0] += w * __uint_as_float(u.x << 16);
+                oacc[cb][4 * jq + 1] += w * __uint_as_float(u.x & 0xFFFF0000u);
+                oacc[cb][4 * jq + 2] += w * __uint_as_float(u.y << 16);
+                oacc[cb][4 * jq + 3] += w * __uint_as_float(u.y & 0xFFFF0000u);
+              }
+          }
+          mx = tm;
+          nx = cand;
+        }
+        excl_here = true;
       }
       if (resc) {
         const float f = __builtin_amdgcn_exp2f((mref - tm) * c2);   // first tile: 2^-inf = 0
@@ -229,19 +243,31 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* 
           for (int j = 0; j < 16; ++j) oacc[cb][j] *= f;
         mref = tm;
       }
+      mall = fmaxf(mall, tm);
     }
-    // ---- weights relative to the reference, champion left out ----
+    // ---- weights relative to the reference ----
     const float nm = -mref * c2;
     bf16x8 pv[2][2];
+    if (excl_here) {                 // wave-uniform: this tile holds a key that is being kept out
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+      for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nm));
-        if (slow && (kb + 32 * mb + cidx(j, hf)) == nstar) p = 0.f;
-        lsum += p;
-        pv[mb][j >> 3][j & 7] = (__bf16)p;
-      }
+        for (int j = 0; j < 16; ++j) {
+          float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nm));
+          if ((kb + 32 * mb + cidx(j, hf)) == nx) p = 0.f;
+          lsum += p;
+          pv[mb][j >> 3][j & 7] = (__bf16)p;
+        }
+    } else {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nm));
+          lsum += p;
+          pv[mb][j >> 3][j & 7] = (__bf16)p;
+        }
+    }
     // ---- O^T[c, row] += V^T P^T ; value operand through the transposing LDS read ----
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -270,8 +296,9 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* 
   if (ri.valid) {
     const int64_t po = (int64_t)ri.row * S + s;
     if (hf == 0) {
-      o.part_m[po] = m * c2;
-      o.part_n[po] = nstar;
+      o.part_m[po] = mall * c2;
+      o.part_mx[po] = mx * c2;
+      o.part_n[po] = nx;
       o.part_ref[po] = ntiles > 0 ? mref * c2 : 0.f;
       o.part_l[po] = ltot;
     }
@@ -427,6 +454,11 @@ constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 // ------------------------------------------------------------------------------------------
 // Score pass: logits again, cross term u.v_n, closed form, mean over the group.
 // grid (key chunks, row blocks, Hkv), NW*64 threads.
+//
+// Per element (query row r of head h, key n), with everything relative to the row maximum M:
+//   e = 2^(s - M) / G,  den = l - G e,  d2 = vv[h,n] - 2 (u.v_n - zz/2),
+//   I/G = e * sqrt(d2) / den = e * x * rsq(x * den^2),  x = max(d2, tiny)
+// (1/G of the group mean is folded into the exponent, zz/2 into the accumulator's start value).
 template <int D, int NW, int GP>
 __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t* __restrict__ q,
                                                         const uint16_t* __restrict__ k,
@@ -436,6 +468,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t*
   constexpr int KS = D / 16, KST = D + 8, NTHR = NW * 64, LOG2IW = ilog2(32 / GP);
   __shared__ __attribute__((aligned(16))) uint16_t Ks[2][TN * KST];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[2][TN * KST];
+  __shared__ __attribute__((aligned(16))) float vvs[2][GP][TN];
 
   const int g = blockIdx.z;
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
@@ -459,13 +492,12 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t*
     }
   }
   const float c2 = pb.scale * LOG2E;
-  const float nM2 = ri.valid ? -o.rs_m[ri.row] : 0.f;
-  const float lrow = ri.valid ? o.rs_l[ri.row] : INFINITY;      // an idle lane scores exactly 0
-  const float zz = ri.valid ? o.rs_zz[ri.row] : 0.f;
+  const float Gf = (float)pb.G;
+  const float nM2 = ri.valid ? -o.rs_m[ri.row] - log2f(Gf) : 0.f;     // e comes out divided by G
+  const float lrow = ri.valid ? o.rs_l[ri.row] : INFINITY;           // an idle lane scores exactly 0
+  const float nhzz = ri.valid ? -0.5f * o.rs_zz[ri.row] : 0.f;
   const int nstar = ri.valid ? o.rs_nstar[ri.row] : -1;
-  const float istar = ri.valid ? o.rs_istar[ri.row] : 0.f;
-  const float invG = 1.0f / (float)pb.G;
-  const float* vvh = o.vv + (int64_t)ri.h * ldv;
+  const float istar = ri.valid ? o.rs_istar[ri.row] / Gf : 0.f;
   const bool writer = ri.hloc == 0 && ri.i < pb.W;
   float* orow = score + ((int64_t)g * pb.W + (writer ? ri.i : 0)) * pb.ld;
 
@@ -474,11 +506,23 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t*
   const int t1 = min(NT, t0 + tiles_per_wg);
   if (t0 >= t1) return;
 
+  // v M v^T of the tile for the heads of the group: GP*TN floats, one float4 per loader thread
+  const bool vv_loader = threadIdx.x < GP * (TN / 4);
+  const int vv_h = threadIdx.x / (TN / 4), vv_q = threadIdx.x % (TN / 4);
+  const float* vv_src = o.vv + (int64_t)(g * pb.G + min(vv_h, pb.G - 1)) * ldv + 4 * vv_q;
+  auto load_vv = [&](int kb) {
+    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+    if (vv_loader && vv_h < pb.G && kb + 4 * vv_q < pb.P) x = *(const f32x4*)(vv_src + kb);
+    return x;
+  };
+
   TileRegs<D, NTHR> tk, tv;
   tk.load(kg, pb.kv_st, t0 * TN, pb.L);
   tv.load(vg, pb.kv_st, t0 * TN, pb.L);
+  f32x4 vvr = load_vv(t0 * TN);
   tk.store(Ks[0], KST);
   tv.store(Vs[0], KST);
+  if (vv_loader) *(f32x4*)&vvs[0][vv_h][4 * vv_q] = vvr;
   __syncthreads();
 
   for (int t = t0; t < t1; ++t) {
@@ -487,12 +531,13 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t*
     if (t + 1 < t1) {
       tk.load(kg, pb.kv_st, kb + TN, pb.L);
       tv.load(vg, pb.kv_st, kb + TN, pb.L);
+      vvr = load_vv(kb + TN);
     }
     f32x16 sacc[2], cacc[2];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) { sacc[mb][j] = 0.f; cacc[mb][j] = 0.f; }
+      for (int j = 0; j < 16; ++j) { sacc[mb][j] = 0.f; cacc[mb][j] = nhzz; }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -503,28 +548,41 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t*
         cacc[mb] = MFMA(av, uhi[ks], cacc[mb]);
         cacc[mb] = MFMA(av, ulo[ks], cacc[mb]);
       }
-    const bool champ_here = __ballot(nstar >= kb && nstar < kb + TN) != 0ull;
+    // ---- epilogue: values in place of the logits ----
+    const float* vvrow = &vvs[buf][ri.hloc < GP ? ri.hloc : 0][0];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int jq = 0; jq < 4; ++jq) {
+        const f32x4 vv4 = *(const f32x4*)(vvrow + 32 * mb + 8 * jq + 4 * hf);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = 4 * jq + e;
+          const float ev = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nM2));
+          const float den = fmaf(-Gf, ev, lrow);
+          const float x = fmaxf(fmaf(-2.f, cacc[mb][j], vv4[e]), 1e-30f);
+          sacc[mb][j] = ev * x * __builtin_amdgcn_rsqf(x * den * den);
+        }
+      }
+    if (__ballot(nstar >= kb && nstar < kb + TN) != 0ull) {     // a champion of this wavefront is here
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+          if (kb + 32 * mb + cidx(j, hf) == nstar) sacc[mb][j] = istar;
+    }
+    // ---- mean over the group, store ----
+    const bool full = kb + TN <= pb.P;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int jq = 0; jq < 4; ++jq) {
         const int n0 = kb + 32 * mb + 8 * jq + 4 * hf;
-        f32x4 vv4 = {0.f, 0.f, 0.f, 0.f};
-        if (n0 < pb.P) vv4 = *(const f32x4*)(vvh + n0);
         f32x4 out;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int j = 4 * jq + e;
-          const float ev = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nM2));
-          const float den = lrow - ev;
-          const float d2 = fmaf(-2.f, cacc[mb][j], zz) + vv4[e];
-          const float x = fmaxf(d2, 1e-30f);
-          float val = ev * x * __builtin_amdgcn_rsqf(x * den * den);    // ev/den * sqrt(x)
-          if (champ_here && n0 + e == nstar) val = istar;
-          out[e] = group_sum<GP>(val) * invG;
-        }
-        if (writer && n0 < pb.P) {
-          if (vec_store && n0 + 3 < pb.P) {
+        for (int e = 0; e < 4; ++e) out[e] = group_sum<GP>(sacc[mb][4 * jq + e]);
+        if (writer) {
+          if (full && vec_store) {
             *(f32x4*)(orow + n0) = out;
           } else {
 #pragma unroll
@@ -536,6 +594,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t*
     if (t + 1 < t1) {
       tk.store(Ks[buf ^ 1], KST);
       tv.store(Vs[buf ^ 1], KST);
+      if (vv_loader) *(f32x4*)&vvs[buf ^ 1][vv_h][4 * vv_q] = vvr;
     }
     __syncthreads();
   }
@@ -587,7 +646,7 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
   if (nw == 4) launch_attn<D, 4>(pb, g1, st, qq, kk, vp, S, kps, log2iw, w);
   else launch_attn<D, 8>(pb, g1, st, qq, kk, vp, S, kps, log2iw, w);
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<bf16_t, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb,
-            (const bf16_t*)v, S, gram, w.part_m, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
+            (const bf16_t*)v, S, gram, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
             w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u);
   if (gram) {
     constexpr int HPW = D == 128 ? 2 : 4;

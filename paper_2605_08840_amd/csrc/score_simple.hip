@@ -43,6 +43,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(Prob pb, const T* __restri
                                                       const T* __restrict__ k,
                                                       const T* __restrict__ v, int S,
                                                       float* __restrict__ part_m,
+                                                      float* __restrict__ part_mx,
                                                       int* __restrict__ part_n,
                                                       float* __restrict__ part_ref,
                                                       float* __restrict__ part_l,
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(Prob pb, const T* __restri
   }
   if (row_ok) {
     const int64_t o = ((int64_t)g * pb.R + r) * S + s;
-    if (ln == 0) { part_m[o] = m; part_n[o] = nstar; part_ref[o] = m; part_l[o] = l; }
+    if (ln == 0) { part_m[o] = m; part_mx[o] = m; part_n[o] = nstar; part_ref[o] = m; part_l[o] = l; }
 #pragma unroll
     for (int j = 0; j < NC; ++j) part_z[o * D + ln + 16 * j] = acc[j];
   }
@@ -286,9 +287,9 @@ int run(const Prob& pb, const void* q, const void* k, const void* v, const float
   const ScorePtrs w = score_ptrs(ws, lay);
   const int S = lay.S_simple;
   RK_LAUNCH(ST_ATTN, st, (k_attn_partial<T, D>), dim3(S, (pb.R + RB - 1) / RB, pb.Hkv), dim3(256), 0, st,
-                     pb, qq, kk, vp, S, w.part_m, w.part_n, w.part_ref, w.part_l, w.part_z);
+                     pb, qq, kk, vp, S, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z);
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<T, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb, vp, S, gram,
-            w.part_m, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m, w.rs_l, w.rs_zz, w.rs_nstar,
+            w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m, w.rs_l, w.rs_zz, w.rs_nstar,
             w.rs_istar, w.rs_u);
   RK_LAUNCH(ST_VV, st, (k_vv<T, D>), dim3((pb.P + 63) / 64, pb.Hq), dim3(256), 0, st, pb, vp, gram, w.vv, lay.ldv);
   RK_LAUNCH(ST_SCORE, st, (k_score<T, D>), dim3((pb.P + TN - 1) / TN, pb.Hkv), dim3(256), 0, st, pb, qq,

@@ -250,8 +250,8 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __r
     ci[j] = x < nc ? (uint32_t)cand_idx[o] : 0u;
   }
   int it = 0;
-  uint32_t t, dummy, cge, cgt;
-  block_kth2<NPT>(ck, need, need, cs, it, t, dummy);
+  uint32_t cge, cgt;
+  const uint32_t t = block_kth<NPT>(ck, need, cs, it);
   block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);
   const uint32_t k_eq = need - cgt;              // ties at t to take, lowest positions first
   uint32_t pos_cut = 0xFFFFFFFFu;                // take tied entries with position <= pos_cut
@@ -260,9 +260,7 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __r
     uint32_t inv[NPT];
 #pragma unroll
     for (int j = 0; j < NPT; ++j) inv[j] = ck[j] == t ? 0xFFFFFFFFu - ci[j] : 0u;
-    uint32_t ti;
-    block_kth2<NPT>(inv, k_eq, k_eq, cs, it, ti, dummy);
-    pos_cut = 0xFFFFFFFFu - ti;
+    pos_cut = 0xFFFFFFFFu - block_kth<NPT>(inv, k_eq, cs, it);
   }
   unsigned long long acc = 0;
 #pragma unroll

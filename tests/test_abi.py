@@ -59,6 +59,7 @@ def test_error_codes_without_launch(rk):
     assert L.restkv_score(ctypes.byref(p), None, one, one, None, one, one, ws_n, None) == -1
     assert L.restkv_smooth(ctypes.byref(p), None, None, one, None, None, one, ws_n, None) == -1
     assert L.restkv_select(ctypes.byref(p), one, None, None, 0, None) == -1
+    assert L.restkv_select(ctypes.byref(p), one, one, None, 0, None) == -3
     assert L.restkv_compact(ctypes.byref(p), one, one, None, one, one, None) == -1
     assert L.restkv_prepare_wo(ctypes.byref(p), None, 128, one, None) == -1
     # workspace: missing, too small, misaligned

@@ -195,7 +195,7 @@ def test_select_edge_budgets(rk, oracle_mod):
         p = rk.make_params(n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=P + W, window=W, budget=B,
                            dtype="f32")
         idx = torch.empty((Hkv, B), dtype=torch.int32, device="cuda")
-        rk.restkv_select(p, torch.from_numpy(fin).cuda(), idx, None)
+        rk.restkv_select(p, torch.from_numpy(fin).cuda(), idx, rk.alloc_workspace(p))
         torch.cuda.synchronize()
         for g in range(Hkv):
             np.testing.assert_array_equal(idx[g].cpu().numpy(), oracle_mod.select(fin[g].astype(np.float64), W, B))
