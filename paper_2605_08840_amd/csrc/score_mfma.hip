@@ -84,8 +84,10 @@ struct TileRegs {
     for (int j = 0; j < CPT; ++j) {
       const int x = threadIdx.x + j * NTHR;
       const int key = x / (D / 8), c8 = x % (D / 8);
-      const int n = kb + key;
-      r[j] = n < L ? *(const uint4*)(base + (int64_t)n * stride + c8 * 8) : make_uint4(0, 0, 0, 0);
+      // rows past the end are clamped, not skipped (their keys are masked, their weights zero):
+      // unconditional loads keep the prefetch free of branches
+      const int n = min(kb + key, L - 1);
+      r[j] = *(const uint4*)(base + (int64_t)n * stride + c8 * 8);
     }
   }
   __device__ __forceinline__ void store(uint16_t* lds, int lds_stride) const {
@@ -97,6 +99,11 @@ struct TileRegs {
     }
   }
 };
+
+// Compiler-only fence: memory operations are not moved across it.  Placed right after the global
+// loads of the next tile so that they are issued BEFORE the tile's matrix work instead of being
+// sunk down to the LDS stores that consume them (which would expose the full memory latency).
+__device__ __forceinline__ void pin_issue() { asm volatile("" ::: "memory"); }
 
 // ------------------------------------------------------------------------------------------
 // Attention pass: per key split, champion-excluded online softmax statistics and A.V sums.
@@ -123,9 +130,12 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* 
     if (ri.valid) u = *(const uint4*)(q + (int64_t)ri.h * pb.q_sh + (int64_t)ri.i * pb.q_st + 16 * ks + 8 * hf);
     qf[ks] = as_bf16x8(u);
   }
+  // Split s owns one contiguous key range (a sequential stream per workgroup measured faster
+  // than tiles interleaved across the splits).
   const int kbeg = s * kps;
   const int kend = min(pb.L, kbeg + kps);
   const int ntiles = kend > kbeg ? (kend - kbeg + TN - 1) / TN : 0;
+  auto tile_key = [&](int t) { return kbeg + t * TN; };
   const int vis_last = (pb.causal && ri.valid) ? pb.P + ri.i : pb.L - 1;
   const float c2 = pb.scale * LOG2E;
 
@@ -143,8 +153,8 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* 
 
   TileRegs<D, NTHR> tk, tv;
   if (ntiles > 0) {
-    tk.load(kg, pb.kv_st, kbeg, pb.L);
-    tv.load(vg, pb.kv_st, kbeg, pb.L);
+    tk.load(kg, pb.kv_st, tile_key(0), pb.L);
+    tv.load(vg, pb.kv_st, tile_key(0), pb.L);
     tk.store(Ks[0], KST);
     tv.store(Vs[0], VST);
   }
@@ -152,10 +162,14 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* 
 
   for (int t = 0; t < ntiles; ++t) {
     const int buf = t & 1;
-    const int kb = kbeg + t * TN;
-    if (t + 1 < ntiles) {
-      tk.load(kg, pb.kv_st, kb + TN, pb.L);
-      tv.load(vg, pb.kv_st, kb + TN, pb.L);
+    const int kb = tile_key(t);
+    {
+      // the next tile travels through registers while this one is computed (the last iteration
+      // re-fetches its own tile: no branch around the loads, nothing reads that copy)
+      const int tn = min(t + 1, ntiles - 1);
+      tk.load(kg, pb.kv_st, tile_key(tn), pb.L);
+      tv.load(vg, pb.kv_st, tile_key(tn), pb.L);
+      pin_issue();
     }
     // ---- logits S^T[key, row] = K Q^T ----
     f32x16 sacc[2];
@@ -286,10 +300,9 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* 
           oacc[cb] = MFMA(a.b, pv[mb][kg2], oacc[cb]);
         }
       }
-    if (t + 1 < ntiles) {
-      tk.store(Ks[buf ^ 1], KST);
-      tv.store(Vs[buf ^ 1], VST);
-    }
+    pin_issue();                     // ... and their LDS stores stay behind the tile's work
+    tk.store(Ks[buf ^ 1], KST);
+    tv.store(Vs[buf ^ 1], VST);
     __syncthreads();
   }
   const float ltot = xhalf_sum(lsum);
@@ -364,7 +377,8 @@ __global__ __launch_bounds__(HPW * (D / 32) * 64) void k_vv_mfma(Prob pb, const 
 
   for (int t = t0; t < t1; ++t) {
     const int buf = (t - t0) & 1;
-    if (t + 1 < t1) tv.load(vg, pb.kv_st, (t + 1) * TN, pb.L);
+    tv.load(vg, pb.kv_st, min(t + 1, t1 - 1) * TN, pb.L);     // unconditional: see pin_issue
+    pin_issue();
     f32x16 y[2];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
@@ -392,7 +406,8 @@ __global__ __launch_bounds__(HPW * (D / 32) * 64) void k_vv_mfma(Prob pb, const 
       acc = xhalf_sum(acc);
       if (hf == 0) part[buf][hw][mb][32 * nb + rr] = acc;
     }
-    if (t + 1 < t1) tv.store(Vs[buf ^ 1], KST);
+    pin_issue();
+    tv.store(Vs[buf ^ 1], KST);
     __syncthreads();
     if (threadIdx.x < HPW * TN) {
       const int hh = threadIdx.x / TN, key = threadIdx.x % TN;
@@ -528,10 +543,12 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t*
   for (int t = t0; t < t1; ++t) {
     const int buf = (t - t0) & 1;
     const int kb = t * TN;
-    if (t + 1 < t1) {
-      tk.load(kg, pb.kv_st, kb + TN, pb.L);
-      tv.load(vg, pb.kv_st, kb + TN, pb.L);
-      vvr = load_vv(kb + TN);
+    {
+      const int kn = min(t + 1, t1 - 1) * TN;                 // unconditional: see pin_issue
+      tk.load(kg, pb.kv_st, kn, pb.L);
+      tv.load(vg, pb.kv_st, kn, pb.L);
+      vvr = load_vv(kn);
+      pin_issue();
     }
     f32x16 sacc[2], cacc[2];
 #pragma unroll
@@ -591,11 +608,10 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t*
           }
         }
       }
-    if (t + 1 < t1) {
-      tk.store(Ks[buf ^ 1], KST);
-      tv.store(Vs[buf ^ 1], KST);
-      if (vv_loader) *(f32x4*)&vvs[buf ^ 1][vv_h][4 * vv_q] = vvr;
-    }
+    pin_issue();
+    tk.store(Ks[buf ^ 1], KST);
+    tv.store(Vs[buf ^ 1], KST);
+    if (vv_loader) *(f32x4*)&vvs[buf ^ 1][vv_h][4 * vv_q] = vvr;
     __syncthreads();
   }
 }
@@ -603,7 +619,8 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t*
 template <int D, int NW>
 void launch_attn(const Prob& pb, dim3 grid, hipStream_t st, const uint16_t* q, const uint16_t* k,
                  const uint16_t* v, int S, int kps, int log2iw, const ScorePtrs& w) {
-  RK_LAUNCH(ST_ATTN, st, (k_attn_mfma<D, NW>), grid, dim3(NW * 64), 0, st, pb, q, k, v, S, kps, log2iw, w);
+  RK_LAUNCH(ST_ATTN, st, (k_attn_mfma<D, NW>), grid, dim3(NW * 64), 0, st, pb, q, k, v, S, kps,
+            log2iw, w);
 }
 
 template <int D, int NW>
