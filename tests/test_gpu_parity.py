@@ -247,3 +247,70 @@ def test_repeat_is_bit_identical(rk):
     b = run_gpu_layer(rk, w, q, k, v, wo)
     for key in ("score", "ema", "final", "idx", "aws_info"):
         assert np.array_equal(a[key], b[key]), key
+
+
+# ------------------------------------------------------------------ full-size configurations
+def _full_size_head_check(rk, oracle_mod, w, layer, g, budget=None, rows_only=None):
+    """One layer of a benchmark configuration generated on the GPU, the whole path run exactly as
+    bench.py launches it, and ONE KV head (its G query heads, full context) checked against the
+    oracle: every score row (or a sample of rows), EMA, window, final score, selection, gather."""
+    if budget is not None:
+        w = w.with_(budget=budget)
+    q, k, v = workloads.make_qkv(w, layer, "cuda")
+    wo = workloads.make_wo(w, layer, "cuda")
+    p = params_for(rk, w)
+    gram = torch.empty((w.n_q_heads, w.head_dim, w.head_dim), dtype=torch.float32, device="cuda")
+    rk.restkv_prepare_wo(p, wo, gram)
+    buf = rk.alloc_layer_buffers(p, q.dtype, "cuda")
+    rk.evict_layer(p, q, k, v, gram, buf)
+    torch.cuda.synchronize()
+    G, d, P = w.group, w.head_dim, w.prefix
+    # slices the oracle needs, as CPU tensors shaped like a one-KV-head problem
+    w1 = w.with_(n_q_heads=G, n_kv_heads=1)
+    q1 = q[g * G:(g + 1) * G].cpu()
+    k1, v1 = k[g:g + 1].cpu(), v[g:g + 1].cpu()
+    wo1 = wo[g * G * d:(g + 1) * G * d].cpu()
+    del wo
+    ref = oracle_score(oracle_mod, w1, q1, k1, v1, wo1, heads=[0], rows=rows_only)
+    Ig, tol = ref[0]
+    got = buf.score[g, :, :P].cpu().numpy()
+    if rows_only is not None:
+        assert_score_close(got[rows_only], Ig, tol, f"{w.name} head {g} rows {rows_only}")
+        return
+    assert_score_close(got, Ig, tol, f"{w.name} layer {layer} head {g}")
+    sm = oracle_mod.smooth_head(Ig, w.alpha, w.beta, w.base_window, True, w.budget)
+    dd = buf.aws_d[g].cpu().numpy()
+    assert abs(dd[0] - sm["d_front"]) <= 2e-3 * P and abs(dd[1] - sm["d_rear"]) <= 2e-3 * P
+    x = (sm["d_front"] - sm["d_rear"]) / w.beta
+    info = tuple(buf.aws_info[g].cpu().numpy().tolist())
+    if min(abs(x - round(x)), 1.0) > 4e-3 * P / w.beta:       # away from a floor() boundary
+        assert info == (sm["w_s"], sm["gamma"])
+    if info == (sm["w_s"], sm["gamma"]):
+        np.testing.assert_allclose(buf.final[g, :P].cpu().numpy(), sm["final"], rtol=2 * RTOL, atol=1e-12)
+        check_selection(buf.idx[g].cpu().numpy(), sm["final"], w.window, w.budget, 4 * RTOL)
+    idx = buf.idx[g].cpu().numpy()
+    assert np.array_equal(buf.k_out[g].float().cpu().numpy(), k1[0].float().numpy()[idx])
+    assert np.array_equal(buf.v_out[g].float().cpu().numpy(), v1[0].float().numpy()[idx])
+
+
+def test_drift_128k_full_size_one_head(rk, oracle_mod):
+    """BASELINE config 4 at full size (L 131072, W 64, 32q/8kv, d 128, budget 2048)."""
+    _full_size_head_check(rk, oracle_mod, workloads.WORKLOADS["drift_128k"], layer=3, g=5)
+
+
+def test_drift_128k_kernel21_sampled_rows(rk, oracle_mod):
+    """Same configuration with the paper's kernel size 21 (RULER setting); sampled score rows of
+    another head and layer."""
+    w = workloads.WORKLOADS["drift_128k"].with_(base_window=21)
+    _full_size_head_check(rk, oracle_mod, w, layer=17, g=0, rows_only=[0, 31, 63])
+
+
+def test_gqa8_128k_full_size_one_head(rk, oracle_mod):
+    """BASELINE config 5 at full size: 64 query heads over 8 KV heads (G = 8), budget 1024."""
+    _full_size_head_check(rk, oracle_mod, workloads.WORKLOADS["gqa8_128k"], layer=1, g=2)
+
+
+@pytest.mark.parametrize("budget", [256, 1024, 2048])
+def test_lowrank_32k_budgets(rk, oracle_mod, budget):
+    """BASELINE config 3 (rank-16 key/query structure, L 32768, W 64) at its three budgets."""
+    _full_size_head_check(rk, oracle_mod, workloads.WORKLOADS["lowrank_32k"], layer=9, g=budget % 7, budget=budget)
