@@ -445,175 +445,298 @@ __global__ __launch_bounds__(256) void k_vnorm2(Prob pb, const uint16_t* __restr
   for (int hl = 0; hl < pb.G; ++hl) vv[(int64_t)(g * pb.G + hl) * ldv + n] = acc;
 }
 
-// Sum over the lanes that hold the same window position for the GP (padded) heads of the
-// group: lanes IW = 32/GP apart inside each 32-lane half.  Rotations inside the 16-lane DPP
-// rows cover the strides below 16, a row swap the stride 16.
-template <int GP>
-__device__ __forceinline__ float group_sum(float x) {
-  constexpr int IW = 32 / GP;
-#define RK_ROR(n) x += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x120 + (n), 0xF, 0xF, false))
-  if constexpr (IW <= 1) RK_ROR(1);
-  if constexpr (IW <= 2) RK_ROR(2);
-  if constexpr (IW <= 4) RK_ROR(4);
-  if constexpr (IW <= 8) RK_ROR(8);
-#undef RK_ROR
-  if constexpr (IW <= 16) {
-    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-  }
-  return x;
-}
-
 constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 
 // ------------------------------------------------------------------------------------------
-// Score pass: logits again, cross term u.v_n, closed form, mean over the group.
-// grid (key chunks, row blocks, Hkv), NW*64 threads.
+// Asynchronous tile ring shared by the pipelined kernels.
 //
-// Per element (query row r of head h, key n), with everything relative to the row maximum M:
-//   e = 2^(s - M) / G,  den = l - G e,  d2 = vv[h,n] - 2 (u.v_n - zz/2),
-//   I/G = e * sqrt(d2) / den = e * x * rsq(x * den^2),  x = max(d2, tiny)
-// (1/G of the group mean is folded into the exponent, zz/2 into the accumulator's start value).
-template <int D, int NW, int GP>
-__global__ __launch_bounds__(NW * 64) void k_score_mfma(Prob pb, const uint16_t* __restrict__ q,
-                                                        const uint16_t* __restrict__ k,
-                                                        const uint16_t* __restrict__ v, ScorePtrs o,
-                                                        int ldv, float* __restrict__ score,
-                                                        int tiles_per_wg, int vec_store) {
-  constexpr int KS = D / 16, KST = D + 8, NTHR = NW * 64, LOG2IW = ilog2(32 / GP);
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][TN * KST];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[2][TN * KST];
-  __shared__ __attribute__((aligned(16))) float vvs[2][GP][TN];
+// A 64-key tile of a [tokens, D] bf16 matrix is copied global -> LDS by global_load_lds_dwordx4:
+// each wave-instruction moves 1 KiB (64 lanes x 16 B) to consecutive LDS bytes, while every
+// lane picks its own global source.  The 16-byte chunk c of tile row r is stored at chunk
+// position c ^ swz(r) of that row, swz(r) = (r >> log2(16 / chunks_per_row)) & (chunks_per_row-1),
+// so that the 16 lanes that fetch one MFMA operand column (16 rows, same chunk) hit 16 different
+// bank groups.  The copies are issued from inline asm and waited for with explicit s_waitcnt
+// vmcnt(n): a wave's loads retire in order, and a later store can only make the count higher,
+// so "count <= number of loads issued after the group" implies that the group has landed.
+// One 1 KiB asynchronous copy: lane i moves the 16 bytes at base + voff_i to LDS bytes
+// [16 i, 16 i + 16) of lds_dst.  base and lds_dst are wave-uniform.
+__device__ __forceinline__ void dma_1k(const void* base, uint32_t voff, void* lds_dst) {
+  const uint32_t dst =
+      __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_dst);
+  const uint64_t sb = (uint64_t)base;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)sb);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(sb >> 32));
+  const uint64_t ub = ((uint64_t)hi << 32) | lo;
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(ub), "s"(dst)
+               : "memory", "m0");
+}
+template <int D>
+struct TileRing {
+  static constexpr int CH = D / 8;                 // 16-byte chunks per row
+  static constexpr int RPI = 64 / CH;              // rows per wave-instruction
+  static constexpr int NI = TN / RPI;              // wave-instructions per tile
+  static constexpr int SH = CH == 16 ? 0 : 1;      // swizzle shift (D = 128: 0, D = 64: 1)
+  __device__ static __forceinline__ int swz(int r) { return (r >> SH) & (CH - 1); }
+  // offset in uint16 units of chunk c of row r
+  __device__ static __forceinline__ int off(int r, int c) { return r * D + ((c ^ swz(r)) << 3); }
+  // wave wv of NW issues its share of one tile: rows [kb, kb+64) of the matrix at `base`
+  // (wave-uniform pointer, row pitch `pitch` bytes), clamped to row L-1.  Byte offsets are 32-bit:
+  // the host checks that the matrix of one head spans less than 4 GiB.
+  template <int NW>
+  __device__ static __forceinline__ void issue(const uint16_t* base, uint32_t pitch, int kb, int L,
+                                               uint16_t* lds_tile, int wv, int lane) {
+    static_assert(NI % NW == 0, "tile instructions must divide over the wavefronts");
+#pragma unroll
+    for (int j = 0; j < NI / NW; ++j) {
+      const int blk = wv * (NI / NW) + j;
+      const int r = blk * RPI + lane / CH, cs = lane % CH;
+      const uint32_t voff = (uint32_t)min(kb + r, L - 1) * pitch + (uint32_t)((cs ^ swz(r)) * 16);
+      dma_1k(base, voff, lds_tile + blk * 512);
+    }
+  }
+};
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  static_assert(N == 0 || N == 3 || N == 5, "add the literal");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if constexpr (N == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+  if constexpr (N == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+}
+
+// ------------------------------------------------------------------------------------------
+// Score pass: logits again, cross term u.v_n, closed form, mean over the group.
+// grid (key chunks, row blocks, Hkv), 512 threads = 8 wavefronts of 32 query rows each.
+//
+// Per element (query row r of head h, key n), with M, l, zz the row's softmax maximum,
+// denominator and z M_h z^T from the attention pass:
+//   a = 2^(s c2 - M - log2(G l)) = A / G,   den = 1 - G a = 1 - A,
+//   x = vv[h,n] - 2 (u.v_n - zz/2),          I/G = a sqrt(x) / den = a x rsq(x den^2)
+// (1/G of the group mean and 1/l are folded into the exponent, zz/2 into the accumulator's
+// start value).  Here the query rows sit on the M side of the MFMA and the keys on the N side:
+// a lane owns ONE key of each 32-key block and 16 query rows, ordered so that the heads of a
+// group that share a window position are consecutive registers of one lane (local row =
+// position * Gp + head).  The group mean is then a few in-lane adds (plus one half swap from
+// Gp = 8 on), and a store instruction writes 32 consecutive keys of a row.
+//
+// Schedule:
+//   * K, V and vv tiles arrive through a 3-deep (vv: 4-deep) asynchronous LDS ring, two tiles
+//     ahead of their use, so no wavefront waits on a global load in the steady state;
+//   * every tile has a matrix half-step (48 MFMAs per wavefront) and a vector half-step
+//     (closed form, group mean, stores) separated by workgroup barriers, and wavefronts 4..7
+//     run ONE half-step behind wavefronts 0..3 (they pass one extra barrier before the loop,
+//     the others one extra after it).  The two wavefronts of a SIMD are therefore always in
+//     different half-steps: one feeds the matrix cores while the other uses the vector ALUs;
+//   * a workgroup walks a long run of tiles, so the per-row setup is paid once.
+// Ring safety, with barriers E_0, E_1, ... and tile t handled by the early half in
+// (E_2t, E_2t+2) and by the late half in (E_2t+1, E_2t+3):  the copy of tile t+2 is issued at
+// the top of a wavefront's step t, i.e. after E_2t at the earliest, into the K/V slot of tile
+// t-1 (last read before E_2t) and the vv slot of tile t-2 (last read before E_2t-1); each
+// wavefront waits for its own share of tile t+1 before its mid-step barrier, which for both
+// halves precedes E_2t+2, the first barrier after which tile t+1 is read.
+template <int D, int GP>
+__global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __restrict__ q,
+                                                    const uint16_t* __restrict__ k,
+                                                    const uint16_t* __restrict__ v, ScorePtrs o, int ldv,
+                                                    float* __restrict__ score, int tiles_per_wg) {
+  constexpr int NW = 8, KS = D / 16, LG = ilog2(GP), IW = 32 / GP;
+  constexpr int GV = GP < 4 ? 4 : GP;               // vv rows per ring slot (whole 1 KiB copies)
+  constexpr int NVB = GV / 4;                       // 1 KiB copies per vv tile
+  constexpr int ND = GP <= 4 ? GP : GP / 2;         // distinct heads among a lane's 16 registers
+  using Ring = TileRing<D>;
+  constexpr int NG = 2 * (Ring::NI / NW) + 1;       // copies per wavefront and tile
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks[3][TN * D];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[3][TN * D];
+  __shared__ __attribute__((aligned(1024))) float vvs[4][GV][TN];
+  __shared__ __attribute__((aligned(16))) float rowc[NW][4][32];   // per local row: accumulator start values, champion key and score
 
   const int g = blockIdx.z;
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
-  const RowInfo ri = row_info(pb, g, blockIdx.y * NW + wv, l, LOG2IW);
+  const int wb = blockIdx.y * NW + wv;              // block of IW window positions
   const uint16_t* kg = k + (int64_t)g * pb.kv_sh;
   const uint16_t* vg = v + (int64_t)g * pb.kv_sh;
-
-  bf16x8 qf[KS], uhi[KS], ulo[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    uint4 u = make_uint4(0, 0, 0, 0);
-    if (ri.valid) u = *(const uint4*)(q + (int64_t)ri.h * pb.q_sh + (int64_t)ri.i * pb.q_st + 16 * ks + 8 * hf);
-    qf[ks] = as_bf16x8(u);
-    const float* up = o.rs_u + (int64_t)ri.row * D + 16 * ks + 8 * hf;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float f = ri.valid ? up[e] : 0.f;
-      const __bf16 hi = (__bf16)f;
-      uhi[ks][e] = hi;
-      ulo[ks][e] = (__bf16)(f - (float)hi);
-    }
-  }
-  const float c2 = pb.scale * LOG2E;
-  const float Gf = (float)pb.G;
-  const float nM2 = ri.valid ? -o.rs_m[ri.row] - log2f(Gf) : 0.f;     // e comes out divided by G
-  const float lrow = ri.valid ? o.rs_l[ri.row] : INFINITY;           // an idle lane scores exactly 0
-  const float nhzz = ri.valid ? -0.5f * o.rs_zz[ri.row] : 0.f;
-  const int nstar = ri.valid ? o.rs_nstar[ri.row] : -1;
-  const float istar = ri.valid ? o.rs_istar[ri.row] / Gf : 0.f;
-  const bool writer = ri.hloc == 0 && ri.i < pb.W;
-  float* orow = score + ((int64_t)g * pb.W + (writer ? ri.i : 0)) * pb.ld;
 
   const int NT = (pb.P + TN - 1) / TN;
   const int t0 = blockIdx.x * tiles_per_wg;
   const int t1 = min(NT, t0 + tiles_per_wg);
   if (t0 >= t1) return;
 
-  // v M v^T of the tile for the heads of the group: GP*TN floats, one float4 per loader thread
-  const bool vv_loader = threadIdx.x < GP * (TN / 4);
-  const int vv_h = threadIdx.x / (TN / 4), vv_q = threadIdx.x % (TN / 4);
-  const float* vv_src = o.vv + (int64_t)(g * pb.G + min(vv_h, pb.G - 1)) * ldv + 4 * vv_q;
-  auto load_vv = [&](int kb) {
-    f32x4 x = {0.f, 0.f, 0.f, 0.f};
-    if (vv_loader && vv_h < pb.G && kb + 4 * vv_q < pb.P) x = *(const f32x4*)(vv_src + kb);
-    return x;
+  // vv copy of this wavefront: block wv % NVB (duplicates write identical bytes)
+  const int vb = wv % NVB;
+  const float* vv_g = o.vv + (int64_t)g * pb.G * ldv;                    // vv rows of this group
+  const uint32_t vv_row = (uint32_t)min(4 * vb + (l >> 4), pb.G - 1) * (uint32_t)ldv;
+  const uint32_t pitch = (uint32_t)pb.kv_st * 2u;
+  auto issue_tile = [&](int t) {
+    const int tt = min(t, t1 - 1);                  // past the end: harmless repeat into a free slot
+    const int kb = tt * TN;
+    Ring::template issue<NW>(kg, pitch, kb, pb.L, Ks[t % 3], wv, l);
+    Ring::template issue<NW>(vg, pitch, kb, pb.L, Vs[t % 3], wv, l);
+    dma_1k(vv_g, (vv_row + (uint32_t)min(kb + 4 * (l & 15), ldv - 4)) * 4u, &vvs[t & 3][4 * vb][0]);
   };
+  issue_tile(t0);          // ring indices run on the absolute tile number
+  issue_tile(t0 + 1);
 
-  TileRegs<D, NTHR> tk, tv;
-  tk.load(kg, pb.kv_st, t0 * TN, pb.L);
-  tv.load(vg, pb.kv_st, t0 * TN, pb.L);
-  f32x4 vvr = load_vv(t0 * TN);
-  tk.store(Ks[0], KST);
-  tv.store(Vs[0], KST);
-  if (vv_loader) *(f32x4*)&vvs[0][vv_h][4 * vv_q] = vvr;
-  __syncthreads();
+  // A operands: local row rr = position * GP + head
+  const float c2 = pb.scale * LOG2E;
+  const float Gf = (float)pb.G, invG = 1.f / Gf;
+  bf16x8 qf[KS], uhi[KS], ulo[KS];
+  int nslane = -1;                                   // champion key of local row rr (for the tile test)
+  {
+    const int head = rr & (GP - 1), i = wb * IW + (rr >> LG);
+    const bool valid = head < pb.G && i < pb.W;
+    const int h = g * pb.G + (valid ? head : 0);
+    const int row = h * pb.W + (valid ? i : 0);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 u = make_uint4(0, 0, 0, 0);
+      if (valid) u = *(const uint4*)(q + (int64_t)h * pb.q_sh + (int64_t)i * pb.q_st + 16 * ks + 8 * hf);
+      qf[ks] = as_bf16x8(u);
+      const float* up = o.rs_u + (int64_t)row * D + 16 * ks + 8 * hf;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float f = valid ? up[e] : 0.f;
+        const __bf16 hi = (__bf16)f;
+        uhi[ks][e] = hi;
+        ulo[ks][e] = (__bf16)(f - (float)hi);
+      }
+    }
+    // Start values of the two accumulators of this row, so that the MFMAs deliver
+    //   s + (-M - log2(G l)) / c2   and   u.v_n - zz/2   directly.
+    // An idle row starts at -inf (its q is zero): its exponential, hence its score, is exactly 0.
+    if (valid) nslane = o.rs_nstar[row];
+    if (hf == 0) {
+      rowc[wv][0][rr] = valid ? (-o.rs_m[row] - log2f(Gf * o.rs_l[row])) / c2 : -INFINITY;
+      rowc[wv][1][rr] = valid ? -0.5f * o.rs_zz[row] : 0.f;
+      rowc[wv][2][rr] = __int_as_float(nslane);
+      rowc[wv][3][rr] = valid ? o.rs_istar[row] * invG : 0.f;
+    }
+  }
+  const float* vvlane = &vvs[0][0][0] + rr;
+
+  wait_vm<NG>();           // own share of tile t0
+  wg_barrier();            // E_2t0
+  const bool late = wv >= NW / 2;
+  if (late) wg_barrier();
 
   for (int t = t0; t < t1; ++t) {
-    const int buf = (t - t0) & 1;
-    const int kb = t * TN;
-    {
-      const int kn = min(t + 1, t1 - 1) * TN;                 // unconditional: see pin_issue
-      tk.load(kg, pb.kv_st, kn, pb.L);
-      tv.load(vg, pb.kv_st, kn, pb.L);
-      vvr = load_vv(kn);
-      pin_issue();
-    }
+    issue_tile(t + 2);
+    // ---- matrix half-step ----
+    const uint16_t* kt = Ks[t % 3];
+    const uint16_t* vt = Vs[t % 3];
     f32x16 sacc[2], cacc[2];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int a = 0; a < 4; ++a) {
+      const f32x4 s0 = *(const f32x4*)&rowc[wv][0][8 * a + 4 * hf];
+      const f32x4 c0 = *(const f32x4*)&rowc[wv][1][8 * a + 4 * hf];
 #pragma unroll
-      for (int j = 0; j < 16; ++j) { sacc[mb][j] = 0.f; cacc[mb][j] = nhzz; }
+      for (int e = 0; e < 4; ++e) {
+        sacc[0][4 * a + e] = s0[e]; sacc[1][4 * a + e] = s0[e];
+        cacc[0][4 * a + e] = c0[e]; cacc[1][4 * a + e] = c0[e];
+      }
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb) {
-        const bf16x8 ak = as_bf16x8(*(const uint4*)&Ks[buf][(32 * mb + rr) * KST + 16 * ks + 8 * hf]);
-        sacc[mb] = MFMA(ak, qf[ks], sacc[mb]);
-        const bf16x8 av = as_bf16x8(*(const uint4*)&Vs[buf][(32 * mb + rr) * KST + 16 * ks + 8 * hf]);
-        cacc[mb] = MFMA(av, uhi[ks], cacc[mb]);
-        cacc[mb] = MFMA(av, ulo[ks], cacc[mb]);
+        const int ofs = Ring::off(32 * mb + rr, 2 * ks + hf);
+        const bf16x8 bk = as_bf16x8(*(const uint4*)&kt[ofs]);
+        sacc[mb] = MFMA(qf[ks], bk, sacc[mb]);
+        const bf16x8 bv = as_bf16x8(*(const uint4*)&vt[ofs]);
+        cacc[mb] = MFMA(uhi[ks], bv, cacc[mb]);
+        cacc[mb] = MFMA(ulo[ks], bv, cacc[mb]);
       }
-    // ---- epilogue: values in place of the logits ----
-    const float* vvrow = &vvs[buf][ri.hloc < GP ? ri.hloc : 0][0];
+    wait_vm<NG>();         // own share of tile t+1 (only the copies of tile t+2 are younger)
+    wg_barrier();
+    // ---- vector half-step ----
+    const int kb = t * TN;
+    const float* vvt = vvlane + (t & 3) * (GV * TN);
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < 2; ++mb) {
+      float vvh[ND];
 #pragma unroll
-      for (int jq = 0; jq < 4; ++jq) {
-        const f32x4 vv4 = *(const f32x4*)(vvrow + 32 * mb + 8 * jq + 4 * hf);
+      for (int jd = 0; jd < ND; ++jd)
+        vvh[jd] = vvt[((8 * (jd >> 2) + 4 * hf + (jd & 3)) & (GP - 1)) * TN + 32 * mb];
+      // stage by stage over 8 registers: eight independent chains in flight
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int j = 4 * jq + e;
-          const float ev = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nM2));
-          const float den = fmaf(-Gf, ev, lrow);
-          const float x = fmaxf(fmaf(-2.f, cacc[mb][j], vv4[e]), 1e-30f);
-          sacc[mb][j] = ev * x * __builtin_amdgcn_rsqf(x * den * den);
-        }
+      for (int b8 = 0; b8 < 16; b8 += 8) {
+        float a[8], x[8], den[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] = sacc[mb][b8 + e] * c2;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = fmaf(-2.f, cacc[mb][b8 + e], vvh[(b8 + e) % ND]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] = __builtin_amdgcn_exp2f(a[e]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = fmaxf(x[e], 1e-30f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) den[e] = fmaf(-Gf, a[e], 1.f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] *= x[e];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] *= den[e];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] *= den[e];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = __builtin_amdgcn_rsqf(x[e]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sacc[mb][b8 + e] = a[e] * x[e];
       }
-    if (__ballot(nstar >= kb && nstar < kb + TN) != 0ull) {     // a champion of this wavefront is here
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-          if (kb + 32 * mb + cidx(j, hf) == nstar) sacc[mb][j] = istar;
     }
-    // ---- mean over the group, store ----
-    const bool full = kb + TN <= pb.P;
+    if (__ballot(nslane >= kb && nslane < kb + TN) != 0ull) {   // a champion of this wavefront is here
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+      for (int j = 0; j < 16; ++j) {       // register j of lane half hf is local row 8 (j/4) + 4 hf + j%4
+        const int m_ = 8 * (j >> 2) + 4 * hf + (j & 3);
+        const int ns = __float_as_int(rowc[wv][2][m_]);
+        const float is = rowc[wv][3][m_];
 #pragma unroll
-      for (int jq = 0; jq < 4; ++jq) {
-        const int n0 = kb + 32 * mb + 8 * jq + 4 * hf;
-        f32x4 out;
+        for (int mb = 0; mb < 2; ++mb)
+          if (kb + 32 * mb + rr == ns) sacc[mb][j] = is;
+      }
+    }
+    // ---- mean over the group (in-lane, one half swap from GP = 8 on), store ----
 #pragma unroll
-        for (int e = 0; e < 4; ++e) out[e] = group_sum<GP>(sacc[mb][4 * jq + e]);
-        if (writer) {
-          if (full && vec_store) {
-            *(f32x4*)(orow + n0) = out;
-          } else {
+    for (int mb = 0; mb < 2; ++mb) {
+      const int n = kb + 32 * mb + rr;
+      auto put = [&](int pos, float val) {
+        const int i = wb * IW + pos;
+        if (i < pb.W && n < pb.P) score[((int64_t)g * pb.W + i) * pb.ld + n] = val;
+      };
+      if constexpr (GP <= 4) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (n0 + e < pb.P) orow[n0 + e] = out[e];
+        for (int a = 0; a < 16 / GP; ++a) {
+          float s = sacc[mb][GP * a];
+#pragma unroll
+          for (int e = 1; e < GP; ++e) s += sacc[mb][GP * a + e];
+          const int j0 = GP * a;
+          put((8 * (j0 >> 2) + 4 * hf + (j0 & 3)) >> LG, s);
+        }
+      } else {
+        constexpr int RPG = GP / 2;                 // registers per group inside one lane half
+        float s[16 / RPG];
+#pragma unroll
+        for (int a = 0; a < 16 / RPG; ++a) {
+          s[a] = sacc[mb][RPG * a];
+#pragma unroll
+          for (int e = 1; e < RPG; ++e) s[a] += sacc[mb][RPG * a + e];
+        }
+        if constexpr (16 / RPG >= 2) {
+#pragma unroll
+          for (int a = 0; a < 16 / RPG; a += 2) {
+            // lower half ends up with the total of position a, upper half with that of a + 1
+            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(s[a]), __float_as_uint(s[a + 1]),
+                                                            false, false);
+            put(a + hf, __uint_as_float(r[0]) + __uint_as_float(r[1]));
           }
+        } else {
+          const float tot = xhalf_sum(s[0]);
+          if (hf == 0) put(0, tot);
         }
       }
-    pin_issue();
-    tk.store(Ks[buf ^ 1], KST);
-    tv.store(Vs[buf ^ 1], KST);
-    if (vv_loader) *(f32x4*)&vvs[buf ^ 1][vv_h][4 * vv_q] = vvr;
-    __syncthreads();
+    }
+    wg_barrier();
   }
+  if (!late) wg_barrier();
+  wait_vm<0>();            // no copy may land in LDS after the workgroup has gone
 }
 
 template <int D, int NW>
@@ -623,19 +746,18 @@ void launch_attn(const Prob& pb, dim3 grid, hipStream_t st, const uint16_t* q, c
             log2iw, w);
 }
 
-template <int D, int NW>
-void launch_pass2(const Prob& pb, int gp, dim3 grid, hipStream_t st, const uint16_t* q, const uint16_t* k,
-                  const uint16_t* v, const ScorePtrs& w, int ldv, float* score, int tpw, int vec) {
-#define RK_CASE(GPV)                                                                              \
-  case GPV:                                                                                       \
-    RK_LAUNCH(ST_SCORE, st, (k_score_mfma<D, NW, GPV>), grid, dim3(NW * 64), 0, st, pb, q, k, v, w, \
-              ldv, score, tpw, vec);                                                              \
-    break;
-  switch (gp) {
-    RK_CASE(1) RK_CASE(2) RK_CASE(4) RK_CASE(8) RK_CASE(16) RK_CASE(32)
-    default: break;
+// compute units of the current device (queried once)
+int n_cu() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+    else
+      n = 256;
   }
-#undef RK_CASE
+  return n;
 }
 
 template <int D>
@@ -677,13 +799,22 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
     RK_LAUNCH(ST_VV, st, (k_vnorm2<D>), dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, vp,
               w.vv, lay.ldv);
   }
+  // score pass: one resident workgroup per compute unit, each walking a run of tiles
   const int NT = (pb.P + TN - 1) / TN;
-  int tpw = (int)(((int64_t)NT * gy * pb.Hkv + 2047) / 2048);
-  if (tpw < 1) tpw = 1;
-  const dim3 g2((NT + tpw - 1) / tpw, gy, pb.Hkv);
-  const int vec = ((pb.ld & 3) == 0 && ((uintptr_t)score & 15u) == 0) ? 1 : 0;
-  if (nw == 4) launch_pass2<D, 4>(pb, gp, g2, st, qq, kk, vp, w, lay.ldv, score, tpw, vec);
-  else launch_pass2<D, 8>(pb, gp, g2, st, qq, kk, vp, w, lay.ldv, score, tpw, vec);
+  const int gy2 = (nwr + 7) / 8;
+  int tpp = (int)(((int64_t)NT * gy2 * pb.Hkv + n_cu() - 1) / n_cu());
+  if (tpp < 1) tpp = 1;
+  const dim3 g2((NT + tpp - 1) / tpp, gy2, pb.Hkv);
+#define RK_CASE(GPV)                                                                          \
+  case GPV:                                                                                   \
+    RK_LAUNCH(ST_SCORE, st, (k_score_pipe<D, GPV>), g2, dim3(512), 0, st, pb, qq, kk, vp, w,  \
+              lay.ldv, score, tpp);                                                           \
+    break;
+  switch (gp) {
+    RK_CASE(1) RK_CASE(2) RK_CASE(4) RK_CASE(8) RK_CASE(16) RK_CASE(32)
+    default: break;
+  }
+#undef RK_CASE
   return hip_status();
 }
 
@@ -694,6 +825,9 @@ bool mfma_eligible(const Prob& pb, const void* q, const void* k, const void* v) 
   if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v) & 15u) != 0) return false;
   if ((pb.q_sh | pb.q_st | pb.kv_sh | pb.kv_st) & 7) return false;
   if (pb.G > 32) return false;
+  // 32-bit byte offsets inside one head's K/V matrix and inside one group's vv rows
+  if ((uint64_t)pb.L * (uint64_t)pb.kv_st * 2u >= (1ull << 32)) return false;
+  if ((uint64_t)pb.G * (uint64_t)((pb.P + 3) / 4 * 4) * 4u >= (1ull << 32)) return false;
   return true;
 }
 
