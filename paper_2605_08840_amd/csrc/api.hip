@@ -61,6 +61,16 @@ ScoreWs score_ws(const Prob& pb) {
   w.rs_istar = take(rows * 4);
   w.rs_u = take(rows * (size_t)pb.d * 4);
   w.vv = take((size_t)pb.Hq * w.ldv * 4);
+  // operand-ordered copies for the matrix-core path: 32-row blocks hold Gp (power of two >= G)
+  // heads of 32/Gp window positions
+  w.nwb = 0;
+  if (pb.G <= 32) {
+    int gp = 1;
+    while (gp < pb.G) gp <<= 1;
+    const int iw = 32 / gp;
+    w.nwb = (pb.W + iw - 1) / iw;
+  }
+  w.op = take((size_t)3 * pb.Hkv * w.nwb * 32 * pb.d * 2);
   w.bytes = off;
   return w;
 }

@@ -30,6 +30,8 @@ struct ScoreWs {
   size_t rs_m, rs_l, rs_zz, rs_nstar, rs_istar;   // [Hq*W]
   size_t rs_u;           // [Hq*W*d] f32   u = z M_h
   size_t vv;             // [Hq*ldv] f32   v_n M_h v_n^T
+  size_t op;             // [3, Hkv*nwb, d/16, 2, 32, 8] bf16: q, u_hi, u_lo in MFMA operand order
+  int nwb;               // blocks of 32 (padded) query rows per KV head in `op`; 0 if unused
   size_t bytes;
 };
 struct SmoothWs {

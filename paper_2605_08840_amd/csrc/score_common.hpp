@@ -10,6 +10,7 @@ struct ScorePtrs {
   float* part_m; float* part_mx; int* part_n; float* part_ref; float* part_l; float* part_z;
   float* rs_m; float* rs_l; float* rs_zz; int* rs_nstar; float* rs_istar; float* rs_u;
   float* vv;
+  uint16_t* op;
 };
 
 inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
@@ -21,6 +22,7 @@ inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
   p.rs_m = (float*)(ws + lay.rs_m); p.rs_l = (float*)(ws + lay.rs_l); p.rs_zz = (float*)(ws + lay.rs_zz);
   p.rs_nstar = (int*)(ws + lay.rs_nstar); p.rs_istar = (float*)(ws + lay.rs_istar);
   p.rs_u = (float*)(ws + lay.rs_u); p.vv = (float*)(ws + lay.vv);
+  p.op = (uint16_t*)(ws + lay.op);
   return p;
 }
 
@@ -64,7 +66,9 @@ __global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict
                                                     float* __restrict__ rs_m, float* __restrict__ rs_l,
                                                     float* __restrict__ rs_zz, int* __restrict__ rs_nstar,
                                                     float* __restrict__ rs_istar,
-                                                    float* __restrict__ rs_u) {
+                                                    float* __restrict__ rs_u,
+                                                    const T* __restrict__ q, uint16_t* __restrict__ op,
+                                                    int log2gp, int nwb) {
   __shared__ float zs[D];
   __shared__ float xs[D];
   __shared__ float red[4];
@@ -120,6 +124,28 @@ __global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict
   const float zz = block_sum(u * z, red, D);
   const float qx = block_sum(y * x, red, D);
   rs_u[(int64_t)row * D + c] = u;
+  if (op) {
+    // q, and u split into bf16 high and low parts, in the order the score pass feeds them to the
+    // matrix cores: [which][32-row block][d/16][lane half][local row][8], local row =
+    // position * Gp + head, so that a wavefront fetches each operand register as one 1 KiB run
+    const int i = row - h * pb.W, head = h - g * pb.G;
+    const int log2iw = 5 - log2gp;
+    const int wb = i >> log2iw, m_ = ((i & ((1 << log2iw) - 1)) << log2gp) + head;
+    const int64_t nb = (int64_t)pb.Hkv * nwb;
+    const int64_t inner = ((((int64_t)(g * nwb + wb) * (D / 16) + (c >> 4)) * 2 + ((c >> 3) & 1)) * 32 + m_) * 8 + (c & 7);
+    const int64_t plane = nb * (D / 16) * 2 * 32 * 8;
+    const uint32_t ub = __float_as_uint(u);
+    uint32_t hi = ub + 0x7FFFu + ((ub >> 16) & 1u);          // round to nearest even (u is finite)
+    hi &= 0xFFFF0000u;
+    const uint32_t lb = __float_as_uint(u - __uint_as_float(hi));
+    const uint32_t lo = (lb + 0x7FFFu + ((lb >> 16) & 1u)) >> 16;
+    const T qv = q[(int64_t)h * pb.q_sh + (int64_t)i * pb.q_st + c];
+    uint16_t qb;
+    __builtin_memcpy(&qb, &qv, 2);
+    op[inner] = qb;
+    op[plane + inner] = (uint16_t)(hi >> 16);
+    op[2 * plane + inner] = (uint16_t)lo;
+  }
   if (c == 0) {
     rs_m[row] = M;
     rs_l[row] = l;

@@ -538,7 +538,7 @@ template <int D, int GP>
 __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __restrict__ q,
                                                     const uint16_t* __restrict__ k,
                                                     const uint16_t* __restrict__ v, ScorePtrs o, int ldv,
-                                                    float* __restrict__ score, int tiles_per_wg) {
+                                                    float* __restrict__ score, int tiles_per_wg, int nwb) {
   constexpr int NW = 8, KS = D / 16, LG = ilog2(GP), IW = 32 / GP;
   constexpr int GV = GP < 4 ? 4 : GP;               // vv rows per ring slot (whole 1 KiB copies)
   constexpr int NVB = GV / 4;                       // 1 KiB copies per vv tile
@@ -586,19 +586,21 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
     const bool valid = head < pb.G && i < pb.W;
     const int h = g * pb.G + (valid ? head : 0);
     const int row = h * pb.W + (valid ? i : 0);
+    // operand-ordered copies left by the merge kernel: one 1 KiB run per wavefront and register
+    const int64_t plane = (int64_t)pb.Hkv * nwb * (KS * 2 * 32 * 8);
+    const uint16_t* ob = o.op + (((int64_t)(g * nwb + wb) * KS * 2 + hf) * 32 + rr) * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      uint4 u = make_uint4(0, 0, 0, 0);
-      if (valid) u = *(const uint4*)(q + (int64_t)h * pb.q_sh + (int64_t)i * pb.q_st + 16 * ks + 8 * hf);
-      qf[ks] = as_bf16x8(u);
-      const float* up = o.rs_u + (int64_t)row * D + 16 * ks + 8 * hf;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float f = valid ? up[e] : 0.f;
-        const __bf16 hi = (__bf16)f;
-        uhi[ks][e] = hi;
-        ulo[ks][e] = (__bf16)(f - (float)hi);
+      uint4 a = make_uint4(0, 0, 0, 0), b = a, c = a;
+      if (valid) {
+        const uint16_t* pk = ob + ks * (2 * 32 * 8);
+        a = *(const uint4*)pk;
+        b = *(const uint4*)(pk + plane);
+        c = *(const uint4*)(pk + 2 * plane);
       }
+      qf[ks] = as_bf16x8(a);
+      uhi[ks] = as_bf16x8(b);
+      ulo[ks] = as_bf16x8(c);
     }
     // Start values of the two accumulators of this row, so that the MFMAs deliver
     //   s + (-M - log2(G l)) / c2   and   u.v_n - zz/2   directly.
@@ -612,6 +614,19 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
     }
   }
   const float* vvlane = &vvs[0][0][0] + rr;
+  // Output a of a lane (after the group mean) belongs to window position i0 + out_pos0(a):
+  //   Gp <= 4: registers Gp a .. Gp a + Gp - 1, local row 8 (Gp a / 4) + 4 hf + (Gp a) % 4;
+  //   Gp 8, 16: position 2 a + hf after the half swap;   Gp 32: position 0 in both halves.
+  constexpr int NOUT = GP <= 4 ? 16 / GP : (GP == 8 ? 2 : 1);
+  constexpr int HS = GP <= 4 ? 4 / GP : (GP == 32 ? 0 : 1);   // position step between the lane halves
+  auto out_pos0 = [](int a) constexpr {
+    return GP <= 4 ? (8 * ((GP * a) >> 2) + ((GP * a) & 3)) >> LG : 2 * a;
+  };
+  const int i0 = wb * IW + hf * HS;
+  const bool rows_full = wb * IW + IW <= pb.W;       // wave-uniform: every position of the block exists
+  char* sbase = (char*)(score + (int64_t)g * pb.W * pb.ld);
+  const uint32_t ld4 = (uint32_t)pb.ld * 4u;
+  const uint32_t voff0 = (uint32_t)i0 * ld4 + (uint32_t)rr * 4u;   // 32-bit: checked on the host
 
   wait_vm<NG>();           // own share of tile t0
   wg_barrier();            // E_2t0
@@ -619,6 +634,10 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   if (late) wg_barrier();
 
   for (int t = t0; t < t1; ++t) {
+    // The wavefront in its matrix half-step issues few, long instructions: it goes first, the
+    // other wavefront of the SIMD fills the vector ALUs in between (without this the older
+    // wavefront wins every arbitration and the younger one's copies and MFMAs start late).
+    __builtin_amdgcn_s_setprio(2);
     issue_tile(t + 2);
     // ---- matrix half-step ----
     const uint16_t* kt = Ks[t % 3];
@@ -647,6 +666,7 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
       }
     wait_vm<NG>();         // own share of tile t+1 (only the copies of tile t+2 are younger)
     wg_barrier();
+    __builtin_amdgcn_s_setprio(0);
     // ---- vector half-step ----
     const int kb = t * TN;
     const float* vvt = vvlane + (t & 3) * (GV * TN);
@@ -667,15 +687,14 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
 #pragma unroll
         for (int e = 0; e < 8; ++e) a[e] = __builtin_amdgcn_exp2f(a[e]);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = fmaxf(x[e], 1e-30f);
-#pragma unroll
         for (int e = 0; e < 8; ++e) den[e] = fmaf(-Gf, a[e], 1.f);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) a[e] *= x[e];
+        for (int e = 0; e < 8; ++e) a[e] *= fabsf(x[e]);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] *= den[e];
+        for (int e = 0; e < 8; ++e) x[e] = fabsf(x[e]) * den[e];
+        // the tiny addend keeps rsq finite when x is exactly 0 (the score is then 0, not NaN)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] *= den[e];
+        for (int e = 0; e < 8; ++e) x[e] = fmaf(x[e], den[e], 1e-37f);
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = __builtin_amdgcn_rsqf(x[e]);
 #pragma unroll
@@ -694,21 +713,16 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
       }
     }
     // ---- mean over the group (in-lane, one half swap from GP = 8 on), store ----
+    float outv[2][NOUT];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
-      const int n = kb + 32 * mb + rr;
-      auto put = [&](int pos, float val) {
-        const int i = wb * IW + pos;
-        if (i < pb.W && n < pb.P) score[((int64_t)g * pb.W + i) * pb.ld + n] = val;
-      };
       if constexpr (GP <= 4) {
 #pragma unroll
-        for (int a = 0; a < 16 / GP; ++a) {
+        for (int a = 0; a < NOUT; ++a) {
           float s = sacc[mb][GP * a];
 #pragma unroll
           for (int e = 1; e < GP; ++e) s += sacc[mb][GP * a + e];
-          const int j0 = GP * a;
-          put((8 * (j0 >> 2) + 4 * hf + (j0 & 3)) >> LG, s);
+          outv[mb][a] = s;
         }
       } else {
         constexpr int RPG = GP / 2;                 // registers per group inside one lane half
@@ -725,13 +739,27 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
             // lower half ends up with the total of position a, upper half with that of a + 1
             const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(s[a]), __float_as_uint(s[a + 1]),
                                                             false, false);
-            put(a + hf, __uint_as_float(r[0]) + __uint_as_float(r[1]));
+            outv[mb][a / 2] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
           }
         } else {
-          const float tot = xhalf_sum(s[0]);
-          if (hf == 0) put(0, tot);
+          outv[mb][0] = xhalf_sum(s[0]);            // both halves hold (and store) the same total
         }
       }
+    }
+    const uint32_t toff = (uint32_t)kb * 4u;
+    if (rows_full && kb + TN <= pb.P) {             // wave-uniform: no lane needs a guard
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int a = 0; a < NOUT; ++a)
+          *(float*)(sbase + (voff0 + toff + (uint32_t)(128 * mb) + (uint32_t)out_pos0(a) * ld4)) = outv[mb][a];
+    } else {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int a = 0; a < NOUT; ++a)
+          if (i0 + out_pos0(a) < pb.W && kb + 32 * mb + rr < pb.P)
+            *(float*)(sbase + (voff0 + toff + (uint32_t)(128 * mb) + (uint32_t)out_pos0(a) * ld4)) = outv[mb][a];
     }
     wg_barrier();
   }
@@ -786,7 +814,7 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
   else launch_attn<D, 8>(pb, g1, st, qq, kk, vp, S, kps, log2iw, w);
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<bf16_t, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb,
             (const bf16_t*)v, S, gram, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
-            w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u);
+            w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, (const bf16_t*)q, w.op, ilog2(gp), lay.nwb);
   if (gram) {
     constexpr int HPW = D == 128 ? 2 : 4;
     const int NTv = (pb.P + TN - 1) / TN;
@@ -808,7 +836,7 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
 #define RK_CASE(GPV)                                                                          \
   case GPV:                                                                                   \
     RK_LAUNCH(ST_SCORE, st, (k_score_pipe<D, GPV>), g2, dim3(512), 0, st, pb, qq, kk, vp, w,  \
-              lay.ldv, score, tpp);                                                           \
+              lay.ldv, score, tpp, lay.nwb);                                                           \
     break;
   switch (gp) {
     RK_CASE(1) RK_CASE(2) RK_CASE(4) RK_CASE(8) RK_CASE(16) RK_CASE(32)
@@ -828,6 +856,7 @@ bool mfma_eligible(const Prob& pb, const void* q, const void* k, const void* v) 
   // 32-bit byte offsets inside one head's K/V matrix and inside one group's vv rows
   if ((uint64_t)pb.L * (uint64_t)pb.kv_st * 2u >= (1ull << 32)) return false;
   if ((uint64_t)pb.G * (uint64_t)((pb.P + 3) / 4 * 4) * 4u >= (1ull << 32)) return false;
+  if ((uint64_t)(pb.W + 32) * (uint64_t)pb.ld * 4u >= (1ull << 32)) return false;   // one head's score rows
   return true;
 }
 
