@@ -16,6 +16,7 @@
 // query heads of 32/Gp window positions; the mean over the group is then a reduction
 // across lanes of one wavefront.
 #include <limits.h>
+#include <stdlib.h>
 
 #include "score_common.hpp"
 
@@ -452,10 +453,10 @@ constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 //
 // A 64-key tile of a [tokens, D] bf16 matrix is copied global -> LDS by global_load_lds_dwordx4:
 // each wave-instruction moves 1 KiB (64 lanes x 16 B) to consecutive LDS bytes, while every
-// lane picks its own global source.  The 16-byte chunk c of tile row r is stored at chunk
-// position c ^ swz(r) of that row, swz(r) = (r >> log2(16 / chunks_per_row)) & (chunks_per_row-1),
-// so that the 16 lanes that fetch one MFMA operand column (16 rows, same chunk) hit 16 different
-// bank groups.  The copies are issued from inline asm and waited for with explicit s_waitcnt
+// lane picks its own global source.  Inside a tile row the 16-byte chunks are permuted by a
+// row-dependent XOR (see TileRing) so that the lanes of one LDS read instruction, which walk
+// down the rows at a fixed chunk, spread over all banks without padding between the rows.
+// The copies are issued from inline asm and waited for with explicit s_waitcnt
 // vmcnt(n): a wave's loads retire in order, and a later store can only make the count higher,
 // so "count <= number of loads issued after the group" implies that the group has landed.
 // One 1 KiB asynchronous copy: lane i moves the 16 bytes at base + voff_i to LDS bytes
@@ -470,15 +471,23 @@ __device__ __forceinline__ void dma_1k(const void* base, uint32_t voff, void* ld
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(ub), "s"(dst)
                : "memory", "m0");
 }
-template <int D>
+// KIND 0: tile read as MFMA operand columns (16 rows x one 16-byte chunk per instruction):
+//         chunk c of row r sits at chunk position c ^ key, key = (r >> log2(16/CH)) & (CH-1).
+// KIND 1: tile read through the transposing 8-byte LDS read (4 rows x 4 consecutive chunks per
+//         half wave): the GROUP of four chunks c>>2 sits at group position (c>>2) ^ key,
+//         key = r & 3 (D = 128) or (r >> 1) & 1 (D = 64).
+template <int D, int KIND = 0>
 struct TileRing {
   static constexpr int CH = D / 8;                 // 16-byte chunks per row
   static constexpr int RPI = 64 / CH;              // rows per wave-instruction
   static constexpr int NI = TN / RPI;              // wave-instructions per tile
-  static constexpr int SH = CH == 16 ? 0 : 1;      // swizzle shift (D = 128: 0, D = 64: 1)
-  __device__ static __forceinline__ int swz(int r) { return (r >> SH) & (CH - 1); }
+  static constexpr int SH = CH == 16 ? 0 : 1;      // D = 128: 0, D = 64: 1
+  __device__ static __forceinline__ int swz(int r, int c) {
+    if constexpr (KIND == 0) return c ^ ((r >> SH) & (CH - 1));
+    else return c ^ (((r >> SH) & (CH / 4 - 1)) << 2);
+  }
   // offset in uint16 units of chunk c of row r
-  __device__ static __forceinline__ int off(int r, int c) { return r * D + ((c ^ swz(r)) << 3); }
+  __device__ static __forceinline__ int off(int r, int c) { return r * D + (swz(r, c) << 3); }
   // wave wv of NW issues its share of one tile: rows [kb, kb+64) of the matrix at `base`
   // (wave-uniform pointer, row pitch `pitch` bytes), clamped to row L-1.  Byte offsets are 32-bit:
   // the host checks that the matrix of one head spans less than 4 GiB.
@@ -490,7 +499,7 @@ struct TileRing {
     for (int j = 0; j < NI / NW; ++j) {
       const int blk = wv * (NI / NW) + j;
       const int r = blk * RPI + lane / CH, cs = lane % CH;
-      const uint32_t voff = (uint32_t)min(kb + r, L - 1) * pitch + (uint32_t)((cs ^ swz(r)) * 16);
+      const uint32_t voff = (uint32_t)min(kb + r, L - 1) * pitch + (uint32_t)(swz(r, cs) * 16);
       dma_1k(base, voff, lds_tile + blk * 512);
     }
   }
@@ -498,10 +507,270 @@ struct TileRing {
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
-  static_assert(N == 0 || N == 3 || N == 5, "add the literal");
+  static_assert(N == 0 || N == 2 || N == 3 || N == 4 || N == 5 || N == 8, "add the literal");
   if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+  if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
   if constexpr (N == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
   if constexpr (N == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+}
+
+// ------------------------------------------------------------------------------------------
+// Attention pass, pipelined: per key split, champion-excluded online softmax statistics and
+// A.V sums (same arithmetic and outputs as k_attn_mfma).  grid (S, row blocks, Hkv), 512 threads.
+//
+// K tiles travel through a 4-deep, V tiles through a 5-deep asynchronous LDS ring.  A step t has a
+// matrix half (P.V of tile t-1, then Q.K of tile t: 48 MFMAs) and a vector half (softmax
+// bookkeeping of tile t), separated by workgroup barriers; wavefronts 4..7 run one half-step
+// behind wavefronts 0..3, so the two wavefronts of a SIMD alternate between the matrix cores and
+// the vector ALUs.  With barriers E_0, E_1, ...: the early half reads K tile t in (E_2t, E_2t+1)
+// and V tile t in (E_2t+2, E_2t+3), the late half one barrier later.  The copy of tile t+3 is
+// issued in the vector half of step t (after E_2t+1 / E_2t+2, where the wavefront has slack) into
+// the K slot of tile t-1 and the V slot of tile t-2, both last read before E_2t; every wavefront
+// waits for its share of tile t+1 (only tile t+2 is younger) before its mid-step barrier, which
+// precedes E_2t+2.
+template <int D>
+__global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __restrict__ q,
+                                                   const uint16_t* __restrict__ k,
+                                                   const uint16_t* __restrict__ v, int S, int kps,
+                                                   int log2iw, ScorePtrs o) {
+  constexpr int NW = 8, KS = D / 16, CB = D / 32;
+  using RingK = TileRing<D, 0>;
+  using RingV = TileRing<D, 1>;
+  constexpr int NG = 2 * (RingK::NI / NW);          // copies per wavefront and tile
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks[4][TN * D];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[5][TN * D];
+
+  const int s = blockIdx.x, g = blockIdx.z;
+  const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
+  const RowInfo ri = row_info(pb, g, blockIdx.y * NW + wv, l, log2iw);
+  const uint16_t* kg = k + (int64_t)g * pb.kv_sh;
+  const uint16_t* vg = v + (int64_t)g * pb.kv_sh;
+
+  const int kbeg = s * kps;
+  const int kend = min(pb.L, kbeg + kps);
+  const int ntiles = kend > kbeg ? (kend - kbeg + TN - 1) / TN : 0;
+  const uint32_t pitch = (uint32_t)pb.kv_st * 2u;
+  auto issue_tile = [&](int t) {
+    const int kb = kbeg + min(t, ntiles - 1) * TN;   // past the end: harmless repeat into a free slot
+    RingK::template issue<NW>(kg, pitch, kb, pb.L, Ks[t & 3], wv, l);
+    RingV::template issue<NW>(vg, pitch, kb, pb.L, Vs[t % 5], wv, l);
+  };
+  if (ntiles > 0) {
+    issue_tile(0);
+    issue_tile(1);
+    issue_tile(2);
+  }
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    uint4 u = make_uint4(0, 0, 0, 0);
+    if (ri.valid) u = *(const uint4*)(q + (int64_t)ri.h * pb.q_sh + (int64_t)ri.i * pb.q_st + 16 * ks + 8 * hf);
+    qf[ks] = as_bf16x8(u);
+  }
+  const int vis_last = (pb.causal && ri.valid) ? pb.P + ri.i : pb.L - 1;
+  const float c2 = pb.scale * LOG2E;
+
+  float mall = -INFINITY, mref = -INFINITY, mx = -INFINITY, lsum = 0.f;
+  int nx = -1;                       // key kept out of the sums, -1: none
+  f32x16 oacc[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) oacc[cb][j] = 0.f;
+  bf16x8 pv[2][2];
+
+  // lane-constant part of the transposing LDS read of the value tile: row and column of the
+  // 8 bytes this lane contributes to a 16 x 16 block
+  const int s16 = l & 15;
+  const int vrow = 4 * hf + (s16 >> 2), vcol = 16 * ((l >> 4) & 1) + 4 * (s16 & 3);
+
+  // P.V of one tile: O^T[c, row] += V^T P^T
+  auto accumulate = [&](const uint16_t* vt) {
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int kg2 = 0; kg2 < 2; ++kg2) {
+        const int r0 = 32 * mb + 16 * kg2 + vrow;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+          const int col = 32 * cb + vcol;
+          const uint16_t* base = vt + RingV::off(r0, col >> 3) + (col & 7);   // rows r0 and r0+8 share the XOR key
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(base));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(base + 8 * D));
+          union { s16x8 s; bf16x8 b; } a;
+          a.s = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[cb] = MFMA(a.b, pv[mb][kg2], oacc[cb]);
+        }
+      }
+  };
+
+  if (ntiles > 0) {
+    wait_vm<2 * NG>();       // own share of tile 0
+    wg_barrier();            // E_0
+    const bool late = wv >= NW / 2;
+    if (late) wg_barrier();
+
+    for (int t = 0; t < ntiles; ++t) {
+      const int kb = kbeg + t * TN;
+      __builtin_amdgcn_s_setprio(2);
+      // ---- matrix half-step: P.V of the previous tile, logits S^T[key, row] = K Q^T of this one ----
+      if (t > 0) accumulate(Vs[(t - 1) % 5]);
+      const uint16_t* kt = Ks[t & 3];
+      f32x16 sacc[2];
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) sacc[mb][j] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+          const bf16x8 a = as_bf16x8(*(const uint4*)&kt[RingK::off(32 * mb + rr, 2 * ks + hf)]);
+          sacc[mb] = MFMA(a, qf[ks], sacc[mb]);
+        }
+      wait_vm<NG>();         // own share of tile t+1 (only the copies of tile t+2 are younger)
+      wg_barrier();
+      __builtin_amdgcn_s_setprio(0);
+      // ---- vector half-step: first the copies of tile t+3, into slots last read before E_2t ----
+      issue_tile(t + 3);
+      const bool tile_mask = (kb + TN > kend) || (pb.causal && kb + TN - 1 > pb.P);
+      if (tile_mask) {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const int n = kb + 32 * mb + cidx(j, hf);
+            if (n >= kend || n > vis_last) sacc[mb][j] = -INFINITY;
+          }
+      }
+      // (only one wavefront of the SIMD is in its vector half: independent chains, not one long one)
+      float tq[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        tq[c] = fmaxf(fmaxf(sacc[0][c], sacc[0][4 + c]), sacc[0][8 + c]);
+        tq[c] = fmaxf(fmaxf(tq[c], sacc[0][12 + c]), sacc[1][c]);
+        tq[c] = fmaxf(fmaxf(tq[c], sacc[1][4 + c]), sacc[1][8 + c]);
+        tq[c] = fmaxf(tq[c], sacc[1][12 + c]);
+      }
+      float tm = xhalf_max(fmaxf(fmaxf(tq[0], tq[1]), fmaxf(tq[2], tq[3])));
+
+      // A key is kept out of the sums only if, on arrival, it is the largest so far AND would
+      // hold more than 1/9 of the mass seen so far; such keys are rare after the first tile, so
+      // the expensive part of the bookkeeping (index search, folding the previous kept-out key
+      // back in) almost never runs.  The reference of the exponentials follows the maximum lazily.
+      const bool newmax = tm > mall;
+      const bool resc = (tm - mref) * c2 > RESCALE_TH;
+      bool excl_here = false;
+      if (__ballot(newmax || resc) != 0ull) {
+        bool dominant = false;
+        if (newmax) {
+          const float pstar = __builtin_amdgcn_exp2f((tm - mref) * c2);      // inf on the first tile
+          float total = xhalf_sum(lsum);
+          if (nx >= 0) total += __builtin_amdgcn_exp2f((mx - mref) * c2);
+          dominant = pstar * 8.0f > total;
+        }
+        if (__ballot(dominant) != 0ull) {
+          int cand = INT_MAX;
+          if (dominant) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+              for (int j = 0; j < 16; ++j)
+                if (sacc[mb][j] == tm) cand = min(cand, kb + 32 * mb + cidx(j, hf));
+          }
+          cand = xhalf_min(cand);
+          if (dominant) {
+            if (nx >= 0) {             // the key kept out so far joins the running sums
+              const float w = __builtin_amdgcn_exp2f((mx - mref) * c2);
+              if (hf == 0) lsum += w;
+              const uint16_t* vr = vg + (int64_t)nx * pb.kv_st;
+#pragma unroll
+              for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int jq = 0; jq < 4; ++jq) {
+                  const uint2 u = *(const uint2*)(vr + 32 * cb + 8 * jq + 4 * hf);
+                  oacc[cb][4 * jq + 0] += w * __uint_as_float(u.x << 16);
+                  oacc[cb][4 * jq + 1] += w * __uint_as_float(u.x & 0xFFFF0000u);
+                  oacc[cb][4 * jq + 2] += w * __uint_as_float(u.y << 16);
+                  oacc[cb][4 * jq + 3] += w * __uint_as_float(u.y & 0xFFFF0000u);
+                }
+            }
+            mx = tm;
+            nx = cand;
+          }
+          excl_here = true;
+        }
+        if (resc) {
+          const float f = __builtin_amdgcn_exp2f((mref - tm) * c2);   // first tile: 2^-inf = 0
+          lsum *= f;
+#pragma unroll
+          for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) oacc[cb][j] *= f;
+          mref = tm;
+        }
+        mall = fmaxf(mall, tm);
+      }
+      // ---- weights relative to the reference ----
+      const float nm = -mref * c2;
+      if (excl_here) {                 // wave-uniform: this tile holds a key that is being kept out
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nm));
+            if ((kb + 32 * mb + cidx(j, hf)) == nx) p = 0.f;
+            lsum += p;
+            pv[mb][j >> 3][j & 7] = (__bf16)p;
+          }
+      } else {
+        float ls[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int b8 = 0; b8 < 16; b8 += 8) {
+            float pe[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pe[e] = fmaf(sacc[mb][b8 + e], c2, nm);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(pe[e]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ls[e & 3] += pe[e];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pv[mb][b8 >> 3][e] = (__bf16)pe[e];
+          }
+        lsum += (ls[0] + ls[1]) + (ls[2] + ls[3]);
+      }
+      wg_barrier();
+    }
+    accumulate(Vs[(ntiles - 1) % 5]);   // its slot is not a target of the copies still in flight
+    if (!late) wg_barrier();
+    wait_vm<0>();            // no copy may land in LDS after the workgroup has gone
+  }
+  const float ltot = xhalf_sum(lsum);
+  if (ri.valid) {
+    const int64_t po = (int64_t)ri.row * S + s;
+    if (hf == 0) {
+      o.part_m[po] = mall * c2;
+      o.part_mx[po] = mx * c2;
+      o.part_n[po] = nx;
+      o.part_ref[po] = ntiles > 0 ? mref * c2 : 0.f;
+      o.part_l[po] = ltot;
+    }
+    float* zp = o.part_z + po * D;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int jq = 0; jq < 4; ++jq) {
+        f32x4 x = {oacc[cb][4 * jq], oacc[cb][4 * jq + 1], oacc[cb][4 * jq + 2], oacc[cb][4 * jq + 3]};
+        *(f32x4*)(zp + 32 * cb + 8 * jq + 4 * hf) = x;
+      }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -799,19 +1068,20 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
   while (gp < pb.G) gp <<= 1;
   const int iw = 32 / gp, log2iw = ilog2(iw);
   const int nwr = (pb.W + iw - 1) / iw;            // wavefronts needed to cover the window
-  const int nw = nwr <= 4 ? 4 : 8;
-  const int gy = (nwr + nw - 1) / nw;
+  const int gy = (nwr + 7) / 8;                    // row blocks of 8 wavefronts
   // attention pass: about one workgroup per compute unit, whole tiles per split
-  int S = 256 / (pb.Hkv * gy);
+  int S = n_cu() / (pb.Hkv * gy);
   const int max_s = (pb.L + TN - 1) / TN;
   if (S > max_s) S = max_s;
   if (S > lay.S_max) S = lay.S_max;
   if (S < 1) S = 1;
   int kps = (pb.L + S - 1) / S;
   kps = (kps + TN - 1) / TN * TN;
-  const dim3 g1(S, gy, pb.Hkv);
-  if (nw == 4) launch_attn<D, 4>(pb, g1, st, qq, kk, vp, S, kps, log2iw, w);
-  else launch_attn<D, 8>(pb, g1, st, qq, kk, vp, S, kps, log2iw, w);
+  static const bool old_attn = getenv("RESTKV_OLD_ATTN") != nullptr;
+  if (old_attn) launch_attn<D, 8>(pb, dim3(S, gy, pb.Hkv), st, qq, kk, vp, S, kps, log2iw, w);
+  else
+  RK_LAUNCH(ST_ATTN, st, (k_attn_pipe<D>), dim3(S, gy, pb.Hkv), dim3(512), 0, st, pb, qq, kk, vp, S, kps,
+            log2iw, w);
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<bf16_t, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb,
             (const bf16_t*)v, S, gram, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
             w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, (const bf16_t*)q, w.op, ilog2(gp), lay.nwb);
@@ -829,7 +1099,7 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
   }
   // score pass: one resident workgroup per compute unit, each walking a run of tiles
   const int NT = (pb.P + TN - 1) / TN;
-  const int gy2 = (nwr + 7) / 8;
+  const int gy2 = gy;
   int tpp = (int)(((int64_t)NT * gy2 * pb.Hkv + n_cu() - 1) / n_cu());
   if (tpp < 1) tpp = 1;
   const dim3 g2((NT + tpp - 1) / tpp, gy2, pb.Hkv);
