@@ -16,6 +16,8 @@
 // query heads of 32/Gp window positions; the mean over the group is then a reduction
 // across lanes of one wavefront.
 #include <limits.h>
+
+#include <type_traits>
 #include <stdlib.h>
 
 #include "score_common.hpp"
@@ -507,13 +509,138 @@ struct TileRing {
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
-  static_assert(N == 0 || N == 2 || N == 3 || N == 4 || N == 5 || N == 8, "add the literal");
+  static_assert(N == 0 || N == 1 || N == 2 || N == 3 || N == 4 || N == 5 || N == 8, "add the literal");
+  if constexpr (N == 1) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
   if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
   if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
   if constexpr (N == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
   if constexpr (N == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+}
+
+// ------------------------------------------------------------------------------------------
+// vv[h, n] = v_n M_h v_n^T with the symmetric Gram matrix M_h, as  sum_i v_i (T v)_i  with the
+// upper triangular T = diag(M) + 2 triu(M, 1): only the 32 x 32 blocks on or above the diagonal
+// are multiplied (10 of 16 for D = 128).  Y^T = T V^T runs on the MFMA with T split into bf16
+// high and low parts that stay in registers for the whole kernel; row block rb needs the k-steps
+// from 2 rb on, so a wavefront takes the row blocks pr and D/32 - 1 - pr of one head: D/16 + 2
+// k-steps whatever pr.  The value tiles arrive through a 3-deep asynchronous LDS ring and are
+// the B operand shared by all wavefronts; the partial dots of a head's wavefronts meet in LDS.
+// grid (key chunks, ceil(G/HPW), Hkv), 512 threads; HPW = 4 heads per workgroup (8 for D = 64).
+template <int D>
+__global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __restrict__ v,
+                                                 const float* __restrict__ gram, float* __restrict__ vv,
+                                                 int ldv, int tiles_per_wg) {
+  constexpr int NW = 8, KS = D / 16, CB = D / 32, WPH = CB / 2, HPW = NW / WPH;
+  using Ring = TileRing<D, 0>;
+  constexpr int NG = Ring::NI / NW;                 // copies per wavefront and tile
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[3][TN * D];
+  __shared__ float part[2][HPW][WPH][TN];
+  const int g = blockIdx.z;
+  const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
+  const int hw = wv / WPH, pr = wv % WPH;           // head inside the workgroup, row block pair
+  const int hloc = blockIdx.y * HPW + hw;
+  const int h = g * pb.G + (hloc < pb.G ? hloc : 0);
+  const uint16_t* vg = v + (int64_t)g * pb.kv_sh;
+  const uint32_t pitch = (uint32_t)pb.kv_st * 2u;
+
+  const int NT = (pb.P + TN - 1) / TN;
+  const int t0 = blockIdx.x * tiles_per_wg;
+  const int t1 = min(NT, t0 + tiles_per_wg);
+  if (t0 >= t1) return;
+  auto issue_tile = [&](int t) { Ring::template issue<NW>(vg, pitch, min(t, t1 - 1) * TN, pb.L, Vs[t % 3], wv, l); };
+  issue_tile(t0);
+  issue_tile(t0 + 1);
+
+  auto body = [&](auto prc) {
+    constexpr int PR = decltype(prc)::value;
+    constexpr int RB0 = PR, RB1 = CB - 1 - PR;      // RB0 <= RB1
+    constexpr int N0 = KS - 2 * RB0, N1 = KS - 2 * RB1;
+    bf16x8 ahi0[N0], alo0[N0], ahi1[N1], alo1[N1];
+    auto load_frag = [&](int rb, int ks, bf16x8& hi8, bf16x8& lo8) {
+      const int i = 32 * rb + rr;                    // Gram row of this lane
+      const float* mrow = gram + ((int64_t)h * D + i) * D + 16 * ks + 8 * hf;
+      const f32x4 x0 = *(const f32x4*)mrow;
+      const f32x4 x1 = *(const f32x4*)(mrow + 4);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int j = 16 * ks + 8 * hf + e;
+        float f = e < 4 ? x0[e] : x1[e - 4];
+        f = j > i ? 2.f * f : (j == i ? f : 0.f);
+        const __bf16 hi = (__bf16)f;
+        hi8[e] = hi;
+        lo8[e] = (__bf16)(f - (float)hi);
+      }
+    };
+#pragma unroll
+    for (int a = 0; a < N0; ++a) load_frag(RB0, 2 * RB0 + a, ahi0[a], alo0[a]);
+#pragma unroll
+    for (int a = 0; a < N1; ++a) load_frag(RB1, 2 * RB1 + a, ahi1[a], alo1[a]);
+
+    wait_vm<NG>();           // own share of tile t0 (compiler-issued loads above are older or waited for)
+    wg_barrier();
+    for (int t = t0; t < t1; ++t) {
+      const int buf = (t - t0) & 1;
+      issue_tile(t + 2);     // into the slot of tile t-1, which every wavefront left before the last barrier
+      const uint16_t* vt = Vs[t % 3];
+      f32x16 y0[2], y1[2];
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) { y0[nb][j] = 0.f; y1[nb][j] = 0.f; }
+#pragma unroll
+      for (int ks = 2 * RB0; ks < KS; ++ks)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+          const bf16x8 b = as_bf16x8(*(const uint4*)&vt[Ring::off(32 * nb + rr, 2 * ks + hf)]);
+          y0[nb] = MFMA(ahi0[ks - 2 * RB0], b, y0[nb]);
+          if (ks >= 2 * RB1) y1[nb] = MFMA(ahi1[ks - 2 * RB1], b, y1[nb]);
+          y0[nb] = MFMA(alo0[ks - 2 * RB0], b, y0[nb]);
+          if (ks >= 2 * RB1) y1[nb] = MFMA(alo1[ks - 2 * RB1], b, y1[nb]);
+        }
+      // row dot with v_n: register j of a block is Gram row 32 rb + 8 (j/4) + 4 hf + j%4
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+        for (int jq = 0; jq < 4; ++jq) {
+          const uint2 u0 = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB0 + jq) + 4 * hf];
+          const uint2 u1 = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB1 + jq) + 4 * hf];
+          acc0 = fmaf(y0[nb][4 * jq + 0], __uint_as_float(u0.x << 16), acc0);
+          acc1 = fmaf(y1[nb][4 * jq + 0], __uint_as_float(u1.x << 16), acc1);
+          acc0 = fmaf(y0[nb][4 * jq + 1], __uint_as_float(u0.x & 0xFFFF0000u), acc0);
+          acc1 = fmaf(y1[nb][4 * jq + 1], __uint_as_float(u1.x & 0xFFFF0000u), acc1);
+          acc0 = fmaf(y0[nb][4 * jq + 2], __uint_as_float(u0.y << 16), acc0);
+          acc1 = fmaf(y1[nb][4 * jq + 2], __uint_as_float(u1.y << 16), acc1);
+          acc0 = fmaf(y0[nb][4 * jq + 3], __uint_as_float(u0.y & 0xFFFF0000u), acc0);
+          acc1 = fmaf(y1[nb][4 * jq + 3], __uint_as_float(u1.y & 0xFFFF0000u), acc1);
+        }
+        const float acc = xhalf_sum(acc0 + acc1);
+        if (hf == 0) part[buf][hw][PR][32 * nb + rr] = acc;
+      }
+      wait_vm<NG>();         // own share of tile t+1 (only the copy of tile t+2 is younger)
+      wg_barrier();
+      if (threadIdx.x < HPW * TN) {
+        const int hh = threadIdx.x / TN, key = threadIdx.x % TN;
+        const int n = t * TN + key;
+        const int hl2 = blockIdx.y * HPW + hh;
+        if (n < pb.P && hl2 < pb.G) {
+          float sum = 0.f;
+#pragma unroll
+          for (int m2 = 0; m2 < WPH; ++m2) sum += part[buf][hh][m2][key];
+          vv[(int64_t)(g * pb.G + hl2) * ldv + n] = sum;
+        }
+      }
+    }
+    wait_vm<0>();            // no copy may land in LDS after the workgroup has gone
+  };
+  if constexpr (WPH == 1) {
+    body(std::integral_constant<int, 0>{});
+  } else {
+    if (pr == 0) body(std::integral_constant<int, 0>{});
+    else body(std::integral_constant<int, 1>{});
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1086,13 +1213,13 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
             (const bf16_t*)v, S, gram, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
             w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, (const bf16_t*)q, w.op, ilog2(gp), lay.nwb);
   if (gram) {
-    constexpr int HPW = D == 128 ? 2 : 4;
+    constexpr int HPW = D == 128 ? 4 : 8;
     const int NTv = (pb.P + TN - 1) / TN;
     const int hg = (pb.G + HPW - 1) / HPW;
-    int tpv = (int)(((int64_t)NTv * hg * pb.Hkv + 1023) / 1024);
+    int tpv = (int)(((int64_t)NTv * hg * pb.Hkv + n_cu() - 1) / n_cu());
     if (tpv < 1) tpv = 1;
-    RK_LAUNCH(ST_VV, st, (k_vv_mfma<D, HPW>), dim3((NTv + tpv - 1) / tpv, hg, pb.Hkv),
-              dim3(HPW * (D / 32) * 64), 0, st, pb, vp, gram, w.vv, lay.ldv, tpv);
+    RK_LAUNCH(ST_VV, st, (k_vv_pipe<D>), dim3((NTv + tpv - 1) / tpv, hg, pb.Hkv), dim3(512), 0, st, pb, vp,
+              gram, w.vv, lay.ldv, tpv);
   } else {
     RK_LAUNCH(ST_VV, st, (k_vnorm2<D>), dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, vp,
               w.vv, lay.ldv);
