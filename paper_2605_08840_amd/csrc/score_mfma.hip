@@ -1,24 +1,25 @@
 // Reconstruction indicator on the matrix cores (bf16 inputs, FP32 accumulation), gfx950.
 //
-// Same four stages and scratch layout as the FP32 path.  Every contraction runs on
-// v_mfma_f32_32x32x16_bf16 in the "transposed" orientation: the 32 query rows of a
-// wavefront sit on the N side of the MFMA (lane % 32 = query row), the keys (or value
-// columns) on the M side.  A lane therefore owns ONE query row and 16 keys per 32x32
-// block, so the softmax statistics, the champion bookkeeping and the per-row
-// constants of the score are plain per-lane scalars.
+// Same four stages and scratch layout as the FP32 path: attention pass per key split, merge
+// (score_common.hpp), value Gram pass vv, score pass.  Every contraction runs on
+// v_mfma_f32_32x32x16_bf16:
 //
 //   C layout of a 32x32 block:  register j of lane l holds
 //       M index = 8*(j/4) + 4*(l/32) + (j%4),   N index = l % 32.
 //   A / B operands: lane l holds M (or N) index l % 32 and the 8 consecutive
 //       K indices 8*(l/32) .. 8*(l/32)+7 of each 16-wide K step.
 //
-// Query rows of one KV head are laid out so that a wavefront holds all (padded) Gp
-// query heads of 32/Gp window positions; the mean over the group is then a reduction
-// across lanes of one wavefront.
+// The attention pass puts the 32 query rows of a wavefront on the N side (lane % 32 = query
+// row, keys or value columns on the M side), so the softmax statistics and the champion
+// bookkeeping are per-lane scalars.  The score pass puts the query rows on the M side and the
+// keys on the N side, with the heads of a group in consecutive registers, so the mean over
+// the group is a few in-lane adds and a store writes 32 consecutive keys of one row.
+//
+// All three kernels are persistent (about one 8-wavefront workgroup per compute unit walking a
+// run of 64-key tiles) and stream their K/V tiles through asynchronous LDS rings (TileRing).
 #include <limits.h>
 
 #include <type_traits>
-#include <stdlib.h>
 
 #include "score_common.hpp"
 
@@ -75,355 +76,6 @@ __device__ __forceinline__ RowInfo row_info(const Prob& pb, int g, int wave_bloc
   r.h = g * pb.G + (r.valid ? r.hloc : 0);
   r.row = r.h * pb.W + (r.valid ? r.i : 0);
   return r;
-}
-
-// cooperative global -> register -> LDS copy of one 64-key tile of a [tokens, D] matrix
-template <int D, int NTHR>
-struct TileRegs {
-  static constexpr int CPT = TN * D / 8 / NTHR;     // 16-byte chunks per thread
-  uint4 r[CPT];
-  __device__ __forceinline__ void load(const uint16_t* __restrict__ base, int64_t stride, int kb, int L) {
-#pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      const int x = threadIdx.x + j * NTHR;
-      const int key = x / (D / 8), c8 = x % (D / 8);
-      // rows past the end are clamped, not skipped (their keys are masked, their weights zero):
-      // unconditional loads keep the prefetch free of branches
-      const int n = min(kb + key, L - 1);
-      r[j] = *(const uint4*)(base + (int64_t)n * stride + c8 * 8);
-    }
-  }
-  __device__ __forceinline__ void store(uint16_t* lds, int lds_stride) const {
-#pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      const int x = threadIdx.x + j * NTHR;
-      const int key = x / (D / 8), c8 = x % (D / 8);
-      *(uint4*)(lds + key * lds_stride + c8 * 8) = r[j];
-    }
-  }
-};
-
-// Compiler-only fence: memory operations are not moved across it.  Placed right after the global
-// loads of the next tile so that they are issued BEFORE the tile's matrix work instead of being
-// sunk down to the LDS stores that consume them (which would expose the full memory latency).
-__device__ __forceinline__ void pin_issue() { asm volatile("" ::: "memory"); }
-
-// ------------------------------------------------------------------------------------------
-// Attention pass: per key split, champion-excluded online softmax statistics and A.V sums.
-// grid (S, row blocks, Hkv), NW*64 threads.
-template <int D, int NW>
-__global__ __launch_bounds__(NW * 64) void k_attn_mfma(Prob pb, const uint16_t* __restrict__ q,
-                                                       const uint16_t* __restrict__ k,
-                                                       const uint16_t* __restrict__ v, int S, int kps,
-                                                       int log2iw, ScorePtrs o) {
-  constexpr int KS = D / 16, CB = D / 32, KST = D + 8, VST = D + 32, NTHR = NW * 64;
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][TN * KST];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[2][TN * VST];
-
-  const int s = blockIdx.x, g = blockIdx.z;
-  const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
-  const RowInfo ri = row_info(pb, g, blockIdx.y * NW + wv, l, log2iw);
-  const uint16_t* kg = k + (int64_t)g * pb.kv_sh;
-  const uint16_t* vg = v + (int64_t)g * pb.kv_sh;
-
-  bf16x8 qf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    uint4 u = make_uint4(0, 0, 0, 0);
-    if (ri.valid) u = *(const uint4*)(q + (int64_t)ri.h * pb.q_sh + (int64_t)ri.i * pb.q_st + 16 * ks + 8 * hf);
-    qf[ks] = as_bf16x8(u);
-  }
-  // Split s owns one contiguous key range (a sequential stream per workgroup measured faster
-  // than tiles interleaved across the splits).
-  const int kbeg = s * kps;
-  const int kend = min(pb.L, kbeg + kps);
-  const int ntiles = kend > kbeg ? (kend - kbeg + TN - 1) / TN : 0;
-  auto tile_key = [&](int t) { return kbeg + t * TN; };
-  const int vis_last = (pb.causal && ri.valid) ? pb.P + ri.i : pb.L - 1;
-  const float c2 = pb.scale * LOG2E;
-
-  float mall = -INFINITY, mref = -INFINITY, mx = -INFINITY, lsum = 0.f;
-  int nx = -1;                       // key kept out of the sums (see below), -1: none
-  f32x16 oacc[CB];
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) oacc[cb][j] = 0.f;
-
-  // lane-constant part of the transposing LDS read address of the value tile
-  const int s16 = l & 15;
-  const int voff = (4 * hf + (s16 >> 2)) * VST + 16 * ((l >> 4) & 1) + 4 * (s16 & 3);
-
-  TileRegs<D, NTHR> tk, tv;
-  if (ntiles > 0) {
-    tk.load(kg, pb.kv_st, tile_key(0), pb.L);
-    tv.load(vg, pb.kv_st, tile_key(0), pb.L);
-    tk.store(Ks[0], KST);
-    tv.store(Vs[0], VST);
-  }
-  __syncthreads();
-
-  for (int t = 0; t < ntiles; ++t) {
-    const int buf = t & 1;
-    const int kb = tile_key(t);
-    {
-      // the next tile travels through registers while this one is computed (the last iteration
-      // re-fetches its own tile: no branch around the loads, nothing reads that copy)
-      const int tn = min(t + 1, ntiles - 1);
-      tk.load(kg, pb.kv_st, tile_key(tn), pb.L);
-      tv.load(vg, pb.kv_st, tile_key(tn), pb.L);
-      pin_issue();
-    }
-    // ---- logits S^T[key, row] = K Q^T ----
-    f32x16 sacc[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) sacc[mb][j] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        const bf16x8 a = as_bf16x8(*(const uint4*)&Ks[buf][(32 * mb + rr) * KST + 16 * ks + 8 * hf]);
-        sacc[mb] = MFMA(a, qf[ks], sacc[mb]);
-      }
-    }
-    const bool tile_mask = (kb + TN > kend) || (pb.causal && kb + TN - 1 > pb.P);
-    if (tile_mask) {
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const int n = kb + 32 * mb + cidx(j, hf);
-          if (n >= kend || n > vis_last) sacc[mb][j] = -INFINITY;
-        }
-    }
-    float tm = sacc[0][0];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) tm = fmaxf(tm, sacc[mb][j]);
-    tm = xhalf_max(tm);
-
-    // A key is kept out of the sums only if, on arrival, it is the largest so far AND would
-    // hold more than 1/9 of the mass seen so far; such keys are rare after the first tile, so
-    // the expensive part of the bookkeeping (index search, folding the previous kept-out key
-    // back in) almost never runs.  The reference of the exponentials follows the maximum lazily.
-    const bool newmax = tm > mall;
-    const bool resc = (tm - mref) * c2 > RESCALE_TH;
-    bool excl_here = false;
-    if (__ballot(newmax || resc) != 0ull) {
-      bool dominant = false;
-      if (newmax) {
-        const float pstar = __builtin_amdgcn_exp2f((tm - mref) * c2);      // inf on the first tile
-        float total = xhalf_sum(lsum);
-        if (nx >= 0) total += __builtin_amdgcn_exp2f((mx - mref) * c2);
-        dominant = pstar * 8.0f > total;
-      }
-      if (__ballot(dominant) != 0ull) {
-        int cand = INT_MAX;
-        if (dominant) {
-#pragma unroll
-          for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int j = 0; j < 16; ++j)
-              if (sacc[mb][j] == tm) cand = min(cand, kb + 32 * mb + cidx(j, hf));
-        }
-        cand = xhalf_min(cand);
-        if (dominant) {
-          if (nx >= 0) {             // the key kept out so far joins the running sums
-            const float w = __builtin_amdgcn_exp2f((mx - mref) * c2);
-            if (hf == 0) lsum += w;
-            const uint16_t* vr = vg + (int64_t)nx * pb.kv_st;
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-              for (int jq = 0; jq < 4; ++jq) {
-                const uint2 u = *(const uint2*)(vr + 32 * cb + 8 * jq + 4 * hf);
-                oacc[cb][4 * jq + 0] += w * __uint_as_float(u.x << 16);
-                oacc[cb][4 * jq + 1] += w * __uint_as_float(u.x & 0xFFFF0000u);
-                oacc[cb][4 * jq + 2] += w * __uint_as_float(u.y << 16);
-                oacc[cb][4 * jq + 3] += w * __uint_as_float(u.y & 0xFFFF0000u);
-              }
-          }
-          mx = tm;
-          nx = cand;
-        }
-        excl_here = true;
-      }
-      if (resc) {
-        const float f = __builtin_amdgcn_exp2f((mref - tm) * c2);   // first tile: 2^-inf = 0
-        lsum *= f;
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) oacc[cb][j] *= f;
-        mref = tm;
-      }
-      mall = fmaxf(mall, tm);
-    }
-    // ---- weights relative to the reference ----
-    const float nm = -mref * c2;
-    bf16x8 pv[2][2];
-    if (excl_here) {                 // wave-uniform: this tile holds a key that is being kept out
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nm));
-          if ((kb + 32 * mb + cidx(j, hf)) == nx) p = 0.f;
-          lsum += p;
-          pv[mb][j >> 3][j & 7] = (__bf16)p;
-        }
-    } else {
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nm));
-          lsum += p;
-          pv[mb][j >> 3][j & 7] = (__bf16)p;
-        }
-    }
-    // ---- O^T[c, row] += V^T P^T ; value operand through the transposing LDS read ----
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int kg2 = 0; kg2 < 2; ++kg2) {
-        const int kb16 = 32 * mb + 16 * kg2;
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-          const uint16_t* base = &Vs[buf][kb16 * VST + 32 * cb + voff];
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(base));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(base + 8 * VST));
-          union { s16x8 s; bf16x8 b; } a;
-          a.s = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[cb] = MFMA(a.b, pv[mb][kg2], oacc[cb]);
-        }
-      }
-    pin_issue();                     // ... and their LDS stores stay behind the tile's work
-    tk.store(Ks[buf ^ 1], KST);
-    tv.store(Vs[buf ^ 1], VST);
-    __syncthreads();
-  }
-  const float ltot = xhalf_sum(lsum);
-  if (ri.valid) {
-    const int64_t po = (int64_t)ri.row * S + s;
-    if (hf == 0) {
-      o.part_m[po] = mall * c2;
-      o.part_mx[po] = mx * c2;
-      o.part_n[po] = nx;
-      o.part_ref[po] = ntiles > 0 ? mref * c2 : 0.f;
-      o.part_l[po] = ltot;
-    }
-    float* zp = o.part_z + po * D;
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-      for (int jq = 0; jq < 4; ++jq) {
-        f32x4 x = {oacc[cb][4 * jq], oacc[cb][4 * jq + 1], oacc[cb][4 * jq + 2], oacc[cb][4 * jq + 3]};
-        *(f32x4*)(zp + 32 * cb + 8 * jq + 4 * hf) = x;
-      }
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// vv[h, n] = v_n M_h v_n^T :  Y^T = M_h V^T on the MFMA, then a row dot with v_n.
-// A wavefront owns 32 rows of one head's Gram matrix (hi + lo bf16 parts, resident in
-// registers for the whole kernel); the value tile in LDS is the B operand shared by all
-// wavefronts of the workgroup (HPW heads x D/32 row blocks).  Partial row dots of the D/32
-// wavefronts of a head meet in LDS.
-// grid (key chunks, ceil(G/HPW), Hkv), HPW*(D/32)*64 threads.
-template <int D, int HPW>
-__global__ __launch_bounds__(HPW * (D / 32) * 64) void k_vv_mfma(Prob pb, const uint16_t* __restrict__ v,
-                                                                 const float* __restrict__ gram,
-                                                                 float* __restrict__ vv, int ldv,
-                                                                 int tiles_per_wg) {
-  constexpr int KS = D / 16, CB = D / 32, KST = D + 8, NW = HPW * CB, NTHR = NW * 64;
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[2][TN * KST];
-  __shared__ float part[2][HPW][CB][TN];
-  const int g = blockIdx.z;
-  const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
-  const int hw = wv / CB, mb = wv % CB;               // head inside the workgroup, Gram row block
-  const int hloc = blockIdx.y * HPW + hw;
-  const bool head_ok = hloc < pb.G;
-  const int h = g * pb.G + (head_ok ? hloc : 0);
-  const uint16_t* vg = v + (int64_t)g * pb.kv_sh;
-
-  bf16x8 ahi[KS], alo[KS];
-  {
-    const float* mrow = gram + ((int64_t)h * D + 32 * mb + rr) * D;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const f32x4 x0 = *(const f32x4*)(mrow + 16 * ks + 8 * hf);
-      const f32x4 x1 = *(const f32x4*)(mrow + 16 * ks + 8 * hf + 4);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float f = e < 4 ? x0[e] : x1[e - 4];
-        const __bf16 hi = (__bf16)f;
-        ahi[ks][e] = hi;
-        alo[ks][e] = (__bf16)(f - (float)hi);
-      }
-    }
-  }
-  const int NT = (pb.P + TN - 1) / TN;
-  const int t0 = blockIdx.x * tiles_per_wg;
-  const int t1 = min(NT, t0 + tiles_per_wg);
-  if (t0 >= t1) return;
-
-  TileRegs<D, NTHR> tv;
-  tv.load(vg, pb.kv_st, t0 * TN, pb.L);
-  tv.store(Vs[0], KST);
-  __syncthreads();
-
-  for (int t = t0; t < t1; ++t) {
-    const int buf = (t - t0) & 1;
-    tv.load(vg, pb.kv_st, min(t + 1, t1 - 1) * TN, pb.L);     // unconditional: see pin_issue
-    pin_issue();
-    f32x16 y[2];
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) y[nb][j] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        const bf16x8 b = as_bf16x8(*(const uint4*)&Vs[buf][(32 * nb + rr) * KST + 16 * ks + 8 * hf]);
-        y[nb] = MFMA(ahi[ks], b, y[nb]);
-        y[nb] = MFMA(alo[ks], b, y[nb]);
-      }
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      float acc = 0.f;
-#pragma unroll
-      for (int jq = 0; jq < 4; ++jq) {
-        const uint2 u = *(const uint2*)&Vs[buf][(32 * nb + rr) * KST + 32 * mb + 8 * jq + 4 * hf];
-        acc = fmaf(y[nb][4 * jq + 0], __uint_as_float(u.x << 16), acc);
-        acc = fmaf(y[nb][4 * jq + 1], __uint_as_float(u.x & 0xFFFF0000u), acc);
-        acc = fmaf(y[nb][4 * jq + 2], __uint_as_float(u.y << 16), acc);
-        acc = fmaf(y[nb][4 * jq + 3], __uint_as_float(u.y & 0xFFFF0000u), acc);
-      }
-      acc = xhalf_sum(acc);
-      if (hf == 0) part[buf][hw][mb][32 * nb + rr] = acc;
-    }
-    pin_issue();
-    tv.store(Vs[buf ^ 1], KST);
-    __syncthreads();
-    if (threadIdx.x < HPW * TN) {
-      const int hh = threadIdx.x / TN, key = threadIdx.x % TN;
-      const int n = t * TN + key;
-      const int hl2 = blockIdx.y * HPW + hh;
-      if (n < pb.P && hl2 < pb.G) {
-        float sum = 0.f;
-#pragma unroll
-        for (int m2 = 0; m2 < CB; ++m2) sum += part[buf][hh][m2][key];
-        vv[(int64_t)(g * pb.G + hl2) * ldv + n] = sum;
-      }
-    }
-  }
 }
 
 // vv without a projection: squared norm of the value row.  grid (ceil(P/256), Hkv)
@@ -589,16 +241,24 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
       for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
         for (int j = 0; j < 16; ++j) { y0[nb][j] = 0.f; y1[nb][j] = 0.f; }
+      // consecutive MFMAs never touch the same accumulator
 #pragma unroll
-      for (int ks = 2 * RB0; ks < KS; ++ks)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-          const bf16x8 b = as_bf16x8(*(const uint4*)&vt[Ring::off(32 * nb + rr, 2 * ks + hf)]);
-          y0[nb] = MFMA(ahi0[ks - 2 * RB0], b, y0[nb]);
-          if (ks >= 2 * RB1) y1[nb] = MFMA(ahi1[ks - 2 * RB1], b, y1[nb]);
-          y0[nb] = MFMA(alo0[ks - 2 * RB0], b, y0[nb]);
-          if (ks >= 2 * RB1) y1[nb] = MFMA(alo1[ks - 2 * RB1], b, y1[nb]);
+      for (int ks = 2 * RB0; ks < KS; ++ks) {
+        const bf16x8 b0 = as_bf16x8(*(const uint4*)&vt[Ring::off(rr, 2 * ks + hf)]);
+        const bf16x8 b1 = as_bf16x8(*(const uint4*)&vt[Ring::off(32 + rr, 2 * ks + hf)]);
+        y0[0] = MFMA(ahi0[ks - 2 * RB0], b0, y0[0]);
+        y0[1] = MFMA(ahi0[ks - 2 * RB0], b1, y0[1]);
+        if (ks >= 2 * RB1) {
+          y1[0] = MFMA(ahi1[ks - 2 * RB1], b0, y1[0]);
+          y1[1] = MFMA(ahi1[ks - 2 * RB1], b1, y1[1]);
         }
+        y0[0] = MFMA(alo0[ks - 2 * RB0], b0, y0[0]);
+        y0[1] = MFMA(alo0[ks - 2 * RB0], b1, y0[1]);
+        if (ks >= 2 * RB1) {
+          y1[0] = MFMA(alo1[ks - 2 * RB1], b0, y1[0]);
+          y1[1] = MFMA(alo1[ks - 2 * RB1], b1, y1[1]);
+        }
+      }
       // row dot with v_n: register j of a block is Gram row 32 rb + 8 (j/4) + 4 hf + j%4
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
@@ -1049,17 +709,21 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
         cacc[0][4 * a + e] = c0[e]; cacc[1][4 * a + e] = c0[e];
       }
     }
+    // consecutive MFMAs never touch the same accumulator
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        const int ofs = Ring::off(32 * mb + rr, 2 * ks + hf);
-        const bf16x8 bk = as_bf16x8(*(const uint4*)&kt[ofs]);
-        sacc[mb] = MFMA(qf[ks], bk, sacc[mb]);
-        const bf16x8 bv = as_bf16x8(*(const uint4*)&vt[ofs]);
-        cacc[mb] = MFMA(uhi[ks], bv, cacc[mb]);
-        cacc[mb] = MFMA(ulo[ks], bv, cacc[mb]);
-      }
+    for (int ks = 0; ks < KS; ++ks) {
+      const int of0 = Ring::off(rr, 2 * ks + hf), of1 = Ring::off(32 + rr, 2 * ks + hf);
+      const bf16x8 bk0 = as_bf16x8(*(const uint4*)&kt[of0]);
+      const bf16x8 bv0 = as_bf16x8(*(const uint4*)&vt[of0]);
+      const bf16x8 bk1 = as_bf16x8(*(const uint4*)&kt[of1]);
+      const bf16x8 bv1 = as_bf16x8(*(const uint4*)&vt[of1]);
+      sacc[0] = MFMA(qf[ks], bk0, sacc[0]);
+      cacc[0] = MFMA(uhi[ks], bv0, cacc[0]);
+      sacc[1] = MFMA(qf[ks], bk1, sacc[1]);
+      cacc[1] = MFMA(uhi[ks], bv1, cacc[1]);
+      cacc[0] = MFMA(ulo[ks], bv0, cacc[0]);
+      cacc[1] = MFMA(ulo[ks], bv1, cacc[1]);
+    }
     wait_vm<NG>();         // own share of tile t+1 (only the copies of tile t+2 are younger)
     wg_barrier();
     __builtin_amdgcn_s_setprio(0);
@@ -1163,13 +827,6 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   wait_vm<0>();            // no copy may land in LDS after the workgroup has gone
 }
 
-template <int D, int NW>
-void launch_attn(const Prob& pb, dim3 grid, hipStream_t st, const uint16_t* q, const uint16_t* k,
-                 const uint16_t* v, int S, int kps, int log2iw, const ScorePtrs& w) {
-  RK_LAUNCH(ST_ATTN, st, (k_attn_mfma<D, NW>), grid, dim3(NW * 64), 0, st, pb, q, k, v, S, kps,
-            log2iw, w);
-}
-
 // compute units of the current device (queried once)
 int n_cu() {
   static int n = 0;
@@ -1204,9 +861,6 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
   if (S < 1) S = 1;
   int kps = (pb.L + S - 1) / S;
   kps = (kps + TN - 1) / TN * TN;
-  static const bool old_attn = getenv("RESTKV_OLD_ATTN") != nullptr;
-  if (old_attn) launch_attn<D, 8>(pb, dim3(S, gy, pb.Hkv), st, qq, kk, vp, S, kps, log2iw, w);
-  else
   RK_LAUNCH(ST_ATTN, st, (k_attn_pipe<D>), dim3(S, gy, pb.Hkv), dim3(512), 0, st, pb, qq, kk, vp, S, kps,
             log2iw, w);
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<bf16_t, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb,
