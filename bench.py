@@ -24,29 +24,51 @@ PEAK_HBM = 8.0e12            # HBM3E, B/s
 
 
 def stage_work(w, stage: str):
-    """(bound, algorithmic work per launch) of each kernel: flops for the contractions,
-    bytes for the streaming passes.  Recomputed logits of the scoring pass are not counted."""
+    """Algorithmic work of one layer pass of each stage as (flops, bytes): the flops of its
+    contractions (the logits recomputed by the scoring pass are not counted) and the bytes it
+    must move to and from HBM once (inputs read once, outputs written once; split partials and
+    other scratch of the implementation are not counted)."""
     Hq, Hkv, d, L, W, P, B = w.n_q_heads, w.n_kv_heads, w.head_dim, w.seq_len, w.window, w.prefix, w.budget
     esz = 4 if w.dtype == "f32" else 2
-    if stage == "attn_partial":      # q K^T and A V over all L keys
-        return "mfma", 2 * (2.0 * Hq * W * L * d)
-    if stage == "score":             # cross term u V^T (the logits are a recompute)
-        return "mfma", 2.0 * Hq * W * P * d
+    if stage == "attn_partial":      # q K^T and A V over all L keys; K and V read once
+        return 2 * (2.0 * Hq * W * L * d), 2.0 * Hkv * L * d * esz + Hq * W * d * (esz + 4.0)
+    if stage == "score":             # cross term u V^T; K, V prefix and vv read, raw score written
+        return 2.0 * Hq * W * P * d, 2.0 * Hkv * P * d * esz + 4.0 * Hq * P + 4.0 * Hkv * W * P
     if stage == "vv":                # V M_h for every query head
-        return "mfma", 2.0 * Hq * P * d * d
-    if stage == "ema":
-        return "hbm", 4.0 * Hkv * W * P + 4.0 * Hkv * P
-    if stage == "row_topk":          # one read of the raw score
-        return "hbm", 4.0 * Hkv * W * P
+        return 2.0 * Hq * P * d * d, 1.0 * Hkv * P * d * esz + 4.0 * Hq * P
+    if stage == "ema":               # one read of the raw score, EMA written
+        return 0.0, 4.0 * Hkv * W * P + 4.0 * Hkv * P
+    if stage == "row_topk":          # threshold search on samples and candidates of the raw score
+        return 0.0, 0.0
     if stage == "box":
-        return "hbm", 8.0 * Hkv * P
+        return 0.0, 8.0 * Hkv * P
     if stage == "select":
-        return "hbm", 4.0 * Hkv * P + 4.0 * Hkv * B
+        return 0.0, 4.0 * Hkv * P + 4.0 * Hkv * B
     if stage == "compact":           # read and write of the kept K and V rows
-        return "hbm", 2.0 * 2.0 * Hkv * B * d * esz
-    if stage == "attn_combine":
-        return "hbm", 0.0
-    return "hbm", 0.0
+        return 0.0, 2.0 * 2.0 * Hkv * B * d * esz
+    return 0.0, 0.0
+
+
+# kernel behind each timed stage whose HBM traffic was measured with rocprofv3 --pmc
+STAGE_KERNEL = {"attn_partial": "k_attn_pipe", "vv": "k_vv_pipe", "score": "k_score_pipe", "ema": "k_ema_scan",
+                "compact": "k_compact", "box": "k_box"}
+
+
+def measured_traffic(workload: str, stage: str):
+    """HBM bytes per launch of the stage's kernel from the committed counter summary
+    (profiles/hbm_traffic_<workload>.md, column 'HBM bytes'), or None."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.md")
+    kern = STAGE_KERNEL.get(stage)
+    if kern is None or not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 6 and cells[0].strip("`") == kern:
+            try:
+                return float(cells[5])
+            except ValueError:
+                return None
+    return None
 
 
 def cpu_baseline(w, q, k, v, wo, budget_s=20.0):
@@ -144,26 +166,28 @@ def main():
     tokens = w.n_layers * w.n_kv_heads * w.seq_len           # KV-head-tokens scored and evicted
     value = tokens / (ms_per_step * 1e-3)
 
-    # ---- roofline of the dominant kernel ------------------------------------------------------
+    # ---- roofline: every stage against the bound that binds it, the dominant one reported -------
+    passes = args.steps * w.n_layers
+    peak_mfma = PEAK_FP32 if w.dtype == "f32" else PEAK_MFMA_BF16
     per = {}
     for name, (ms, n) in stages.items():
         if n:
-            bound, work = stage_work(w, name)
-            avg = ms / n
-            peak = PEAK_MFMA_BF16 if bound == "mfma" else PEAK_HBM
-            if bound == "mfma" and w.dtype == "f32":
-                peak = PEAK_FP32
-            per[name] = {"avg_ms": avg, "launches": n, "bound": bound, "work": work,
-                         "achieved": work / (avg * 1e-3) if avg > 0 else 0.0, "peak": peak}
+            flops, nbytes = stage_work(w, name)
+            t = ms / passes                          # ms of this stage per layer pass
+            t_mfma, t_hbm = flops / peak_mfma, nbytes / PEAK_HBM
+            bound = "mfma" if t_mfma > t_hbm else "hbm"
+            work, peak = (flops, peak_mfma) if bound == "mfma" else (nbytes, PEAK_HBM)
+            per[name] = {"ms": t, "launches": n / passes, "bound": bound, "work": work,
+                         "achieved": work / (t * 1e-3) if t > 0 else 0.0, "peak": peak}
     roof = None
     if per:
-        dom = max((n for n in per if per[n]["work"] > 0), key=lambda n: per[n]["avg_ms"])
+        dom = max((n for n in per if per[n]["work"] > 0), key=lambda n: per[n]["ms"])
         s = per[dom]
         unit = "TFLOP/s" if s["bound"] == "mfma" else "GB/s"
         div = 1e12 if s["bound"] == "mfma" else 1e9
         roof = {"kernel": dom, "bound": s["bound"], "achieved": s["achieved"] / div, "peak": s["peak"] / div,
-                "unit": unit, "frac": s["achieved"] / s["peak"], "traffic": None,
-                "avg_ms": s["avg_ms"]}
+                "unit": unit, "frac": s["achieved"] / s["peak"], "traffic": measured_traffic(w.name, dom),
+                "avg_ms": s["ms"]}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -180,7 +204,7 @@ def main():
                    "window": w.window, "budget": w.budget, "layer_tokens_per_s": w.n_layers * w.seq_len / (ms_per_step * 1e-3)},
         "roofline": roof,
         "cpu_baseline": cpu,
-        "stages": {n: {"avg_ms": round(s["avg_ms"], 5), "launches": s["launches"], "bound": s["bound"],
+        "stages": {n: {"ms_per_layer": round(s["ms"], 5), "launches_per_layer": s["launches"], "bound": s["bound"],
                        "frac": (s["achieved"] / s["peak"]) if s["work"] else None} for n, s in per.items()},
     }
     print(json.dumps(out))

@@ -87,7 +87,8 @@ size_t restkv_workspace_bytes(const restkv_params* p);
  *   w_o   [Hq*d, d_model] float32, row-major, "z @ W_O" orientation: rows
  *         h*d .. (h+1)*d-1 belong to query head h (a framework weight stored
  *         [out,in] must be passed transposed).
- *   gram  [Hq, d, d] float32 out.
+ *   gram  [Hq, d, d] float32 out; symmetric by construction (restkv_score relies
+ *         on M_h[i][j] == M_h[j][i] and reads the upper triangle only).
  * Weight-only: run once per layer, not per request.  Accumulates in float64.
  */
 int restkv_prepare_wo(const restkv_params* p, const float* w_o, int64_t d_model,
@@ -103,7 +104,8 @@ int restkv_prepare_wo(const restkv_params* p, const float* w_o, int64_t d_model,
  * Output is the mean over the G query heads of each KV head:
  *     score[g,i,n] = (1/G) sum_{h in g} I[h,i,n]          [Hkv, W, ld_score] float32
  *   q     [Hq, W, d]  (strides q_stride_*),  k, v  [Hkv, L, d] (strides kv_stride_*)
- *   gram  [Hq, d, d] from restkv_prepare_wo, or NULL for W_O W_O^T = identity.
+ *   gram  [Hq, d, d] from restkv_prepare_wo (any symmetric matrices), or NULL for
+ *         W_O W_O^T = identity.
  * Columns n >= P of `score` are not written.
  */
 int restkv_score(const restkv_params* p, const void* q, const void* k, const void* v,
@@ -133,6 +135,9 @@ int restkv_smooth(const restkv_params* p, const float* score, float* ema, float*
  * largest final[g, 0..P) (equal values: lower index wins), written in ascending
  * position order and followed by the window tokens P .. L-1.
  *   final [Hkv, ld] in;  idx [Hkv, B] int32 out.
+ * Uses the workspace (samples, per-chunk counters, candidates); like every call
+ * here it allocates nothing and returns RESTKV_EWORKSPACE if the workspace is
+ * NULL, misaligned or smaller than restkv_workspace_bytes().
  */
 int restkv_select(const restkv_params* p, const float* final_score, int32_t* idx,
                   void* workspace, size_t workspace_bytes, restkv_stream_t stream);
