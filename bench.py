@@ -153,41 +153,68 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    rk.restkv_timing_enable(not args.no_kernel_events)
+    # One more untimed step with every kernel bracketed by HIP events shows which stage dominates.
+    dom = None
+    if not args.no_kernel_events:
+        rk.restkv_timing_enable(True)
+        step()
+        torch.cuda.synchronize()
+        probe = rk.restkv_timing_read()
+        dom = max((s for s in probe if s != "gram" and stage_work(w, s) != (0.0, 0.0)), key=lambda s: probe[s][0])
+
+    # Timed region: exactly `steps` steps.  Only the dominant stage keeps its events (two per
+    # layer); bracketing all seventeen kernels of a layer costs about a tenth of the step time.
+    rk.restkv_timing_enable([dom] if dom else False)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    stages = rk.restkv_timing_read() if not args.no_kernel_events else {}
-    rk.restkv_timing_enable(False)
+    timed = rk.restkv_timing_read() if dom else {}
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens = w.n_layers * w.n_kv_heads * w.seq_len           # KV-head-tokens scored and evicted
     value = tokens / (ms_per_step * 1e-3)
 
-    # ---- roofline: every stage against the bound that binds it, the dominant one reported -------
+    # ---- roofline: every stage against the bound that binds it --------------------------------
     passes = args.steps * w.n_layers
     peak_mfma = PEAK_FP32 if w.dtype == "f32" else PEAK_MFMA_BF16
-    per = {}
-    for name, (ms, n) in stages.items():
-        if n:
-            flops, nbytes = stage_work(w, name)
-            t = ms / passes                          # ms of this stage per layer pass
-            t_mfma, t_hbm = flops / peak_mfma, nbytes / PEAK_HBM
-            bound = "mfma" if t_mfma > t_hbm else "hbm"
-            work, peak = (flops, peak_mfma) if bound == "mfma" else (nbytes, PEAK_HBM)
-            per[name] = {"ms": t, "launches": n / passes, "bound": bound, "work": work,
-                         "achieved": work / (t * 1e-3) if t > 0 else 0.0, "peak": peak}
+
+    def price(name, ms, n):
+        flops, nbytes = stage_work(w, name)
+        t = ms / passes                              # ms of this stage per layer pass
+        t_mfma, t_hbm = flops / peak_mfma, nbytes / PEAK_HBM
+        bound = "mfma" if t_mfma > t_hbm else "hbm"
+        work, peak = (flops, peak_mfma) if bound == "mfma" else (nbytes, PEAK_HBM)
+        return {"ms": t, "launches": n / passes, "bound": bound, "work": work,
+                "achieved": work / (t * 1e-3) if t > 0 else 0.0, "peak": peak}
+
     roof = None
-    if per:
-        dom = max((n for n in per if per[n]["work"] > 0), key=lambda n: per[n]["ms"])
-        s = per[dom]
+    if dom and timed[dom][1]:
+        s = price(dom, *timed[dom])                  # durations from the timed region itself
         unit = "TFLOP/s" if s["bound"] == "mfma" else "GB/s"
         div = 1e12 if s["bound"] == "mfma" else 1e9
-        roof = {"kernel": dom, "bound": s["bound"], "achieved": s["achieved"] / div, "peak": s["peak"] / div,
+        roof = {"kernel": STAGE_KERNEL.get(dom, dom), "stage": dom, "bound": s["bound"],
+                "achieved": s["achieved"] / div, "peak": s["peak"] / div,
                 "unit": unit, "frac": s["achieved"] / s["peak"], "traffic": measured_traffic(w.name, dom),
-                "avg_ms": s["ms"]}
+                "avg_ms": s["ms"] / s["launches"]}
+
+    # Stage breakdown: the same steps once more, untimed, with every kernel bracketed.
+    per = {}
+    ms_all_events = None
+    if not args.no_kernel_events:
+        rk.restkv_timing_enable(True)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        ms_all_events = (time.perf_counter() - t2) * 1e3 / args.steps
+        for name, (ms, n) in rk.restkv_timing_read().items():
+            if n:
+                per[name] = price(name, ms, n)
+    rk.restkv_timing_enable(False)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -204,6 +231,7 @@ def main():
                    "window": w.window, "budget": w.budget, "layer_tokens_per_s": w.n_layers * w.seq_len / (ms_per_step * 1e-3)},
         "roofline": roof,
         "cpu_baseline": cpu,
+        "ms_per_step_all_kernels_bracketed": ms_all_events,
         "stages": {n: {"ms_per_layer": round(s["ms"], 5), "launches_per_layer": s["launches"], "bound": s["bound"],
                        "frac": (s["achieved"] / s["peak"]) if s["work"] else None} for n, s in per.items()},
     }

@@ -151,8 +151,11 @@ int restkv_compact(const restkv_params* p, const void* k, const void* v, const i
                    void* k_out, void* v_out, restkv_stream_t stream);
 
 /*
- * Profiling aid (not part of the method): when enabled, every kernel the library
- * launches is bracketed by two HIP events on the caller's stream.
+ * Profiling aid (not part of the method): every kernel launch of a selected stage
+ * is bracketed by two HIP events on the caller's stream.  stage_mask: bit s selects
+ * stage s (see restkv_stage_name), -1 selects all, 0 turns timing off.  A bracket
+ * costs a few microseconds of idle GPU, so timing all stages slows a layer by
+ * about a tenth; timing one stage is nearly free.
  * restkv_timing_read() blocks until those events have completed, adds the elapsed
  * milliseconds and the number of launches per stage into ms[] / launches[] (host
  * arrays of n_stages >= RESTKV_N_STAGES entries) and forgets them.  Disabled by
@@ -160,7 +163,7 @@ int restkv_compact(const restkv_params* p, const void* k, const void* v, const i
  * against concurrent launches on other host threads beyond a mutex on the records.
  */
 #define RESTKV_N_STAGES 10
-int restkv_timing_enable(int on);
+int restkv_timing_enable(int stage_mask);
 int restkv_timing_read(double* ms, int64_t* launches, int n_stages);
 const char* restkv_stage_name(int stage);   /* "gram", "attn_partial", ... */
 

@@ -150,8 +150,16 @@ def restkv_compact(p, k, v, idx, k_out, v_out, stream=None):
 N_STAGES = 10
 
 
-def restkv_timing_enable(on: bool):
-    _chk(lib().restkv_timing_enable(int(bool(on))), "restkv_timing_enable")
+def restkv_timing_enable(on):
+    """True / False, or a collection of stage names to time only those (see restkv_timing_read)."""
+    if isinstance(on, (bool, int)):
+        mask = -1 if on else 0
+    else:
+        names = [lib().restkv_stage_name(s).decode() for s in range(N_STAGES)]
+        mask = 0
+        for name in on:
+            mask |= 1 << names.index(name)
+    _chk(lib().restkv_timing_enable(mask), "restkv_timing_enable")
 
 
 def restkv_timing_read():

@@ -1,6 +1,7 @@
 // Optional per-kernel timing with HIP events on the caller's stream (off by default).
-// When enabled, every kernel launch of the library is bracketed by two events taken
-// from a pool; restkv_timing_read() waits for them and returns the time per stage.
+// Every kernel launch of a selected stage is bracketed by two events taken from a pool;
+// restkv_timing_read() waits for them and returns the time per stage.  Each bracket costs a
+// few microseconds of idle GPU between kernels, which is why stages can be selected one by one.
 #include <mutex>
 #include <vector>
 
@@ -11,13 +12,13 @@ namespace restkv {
 namespace {
 struct Rec { hipEvent_t a, b; int stage; };
 std::mutex g_mu;
-bool g_on = false;
+unsigned g_mask = 0;      // bit s: launches of stage s are timed
 std::vector<Rec> g_pool;     // events are created once and reused
 size_t g_used = 0;
 }  // namespace
 
 StageTimer::StageTimer(int stage, hipStream_t st) : st_(st), slot_(-1) {
-  if (!g_on) return;
+  if (!((g_mask >> stage) & 1u)) return;
   std::lock_guard<std::mutex> lk(g_mu);
   if (g_used == g_pool.size()) {
     Rec r;
@@ -42,9 +43,9 @@ using namespace restkv;
 
 extern "C" {
 
-int restkv_timing_enable(int on) {
+int restkv_timing_enable(int stage_mask) {
   std::lock_guard<std::mutex> lk(g_mu);
-  g_on = on != 0;
+  g_mask = (unsigned)stage_mask;
   g_used = 0;
   return RESTKV_OK;
 }
