@@ -40,62 +40,98 @@ inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
 //   l = 1 + l_rest, z = (v* + z_rest)/l, u = z M_h, zz = u.z, and the champion's indicator
 //   in its leave-one-out form I* = A* ||(z_rest/l_rest - v*) W_O||  (Eq. ori with Eq. relation;
 //   equals Eq. rec_ei).  Without one, l and z are the plain softmax sums relative to the maximum.
-__device__ __forceinline__ float block_sum(float x, float* red, int nthreads) {
-  // wavefront reduce, then across wavefronts through LDS
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-  const int w = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[w] = x;
-  __syncthreads();
-  float tot = 0.f;
-  for (int j = 0; j < (nthreads + 63) / 64; ++j) tot += red[j];
-  return tot;
-}
+constexpr int CMB_RQ = 4;    // query rows of one head per workgroup of the merge kernel
 
-// one block of D threads per query row (global row = h*W + i)
+// Merge of the key splits and the per-row quantities of the score pass.
+// grid (ceil(W / CMB_RQ), Hq), CMB_RQ * D threads: thread = (row r of the group, column c).
+// The head's Gram matrix is staged in LDS once per workgroup; the per-split scalars of a row are
+// fetched by one thread each and shared through LDS.
 template <typename T, int D>
-__global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict__ v, int S,
-                                                    const float* __restrict__ gram,
-                                                    const float* __restrict__ part_m,
-                                                    const float* __restrict__ part_mx,
-                                                    const int* __restrict__ part_n,
-                                                    const float* __restrict__ part_ref,
-                                                    const float* __restrict__ part_l,
-                                                    const float* __restrict__ part_z,
-                                                    float* __restrict__ rs_m, float* __restrict__ rs_l,
-                                                    float* __restrict__ rs_zz, int* __restrict__ rs_nstar,
-                                                    float* __restrict__ rs_istar,
-                                                    float* __restrict__ rs_u,
-                                                    const T* __restrict__ q, uint16_t* __restrict__ op,
-                                                    int log2gp, int nwb) {
-  __shared__ float zs[D];
-  __shared__ float xs[D];
-  __shared__ float red[4];
-  const int row = blockIdx.x;               // h*W + i  ==  g*R + r
-  const int h = row / pb.W, g = h / pb.G;
-  const int c = threadIdx.x;
+__global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* __restrict__ v, int S,
+                                                             const float* __restrict__ gram,
+                                                             const float* __restrict__ part_m,
+                                                             const float* __restrict__ part_mx,
+                                                             const int* __restrict__ part_n,
+                                                             const float* __restrict__ part_ref,
+                                                             const float* __restrict__ part_l,
+                                                             const float* __restrict__ part_z,
+                                                             float* __restrict__ rs_m, float* __restrict__ rs_l,
+                                                             float* __restrict__ rs_zz, int* __restrict__ rs_nstar,
+                                                             float* __restrict__ rs_istar,
+                                                             float* __restrict__ rs_u,
+                                                             const T* __restrict__ q, uint16_t* __restrict__ op,
+                                                             int log2gp, int nwb) {
+  constexpr int NWV = D / 64, SMAX = 64;     // wavefronts per row; capacity of the split dimension
+  __shared__ float Mh_s[D * D];              // the head's Gram matrix (unused when gram == NULL)
+  __shared__ float zq[CMB_RQ][D], xq[CMB_RQ][D];
+  __shared__ float red[CMB_RQ][NWV][2];
+  __shared__ float s_m[CMB_RQ][SMAX], s_mx[CMB_RQ][SMAX], s_ref[CMB_RQ][SMAX], s_l[CMB_RQ][SMAX];
+  __shared__ int s_n[CMB_RQ][SMAX];
+  __shared__ float s_w[CMB_RQ][SMAX];
+  const int h = blockIdx.y, g = h / pb.G;
+  const int r = threadIdx.x / D, c = threadIdx.x % D;
+  const int i = blockIdx.x * CMB_RQ + r;
+  const bool live = i < pb.W;
+  const int row = h * pb.W + (live ? i : 0);
   const T* vg = v + (int64_t)g * pb.kv_sh;
   const int64_t o = (int64_t)row * S;
+  if (c < S) {                               // S <= SMAX <= D
+    s_m[r][c] = part_m[o + c];
+    s_mx[r][c] = part_mx[o + c];
+    s_n[r][c] = part_n[o + c];
+    s_ref[r][c] = part_ref[o + c];
+    s_l[r][c] = part_l[o + c];
+  }
+  if (gram) {
+    const float* Mh = gram + (int64_t)h * D * D;
+    for (int x = threadIdx.x; x < D * D; x += CMB_RQ * D) Mh_s[x] = Mh[x];
+  }
+  __syncthreads();
 
   float M = -INFINITY;
-  for (int s = 0; s < S; ++s) M = fmaxf(M, part_m[o + s]);
+  for (int s = 0; s < S; ++s) M = fmaxf(M, s_m[r][s]);
   int sstar = -1;                            // split whose kept-out key is the overall maximum
   for (int s = 0; s < S; ++s)
-    if (sstar < 0 && part_n[o + s] >= 0 && part_mx[o + s] == M) sstar = s;   // earliest split = lowest key
-  const int nstar = sstar >= 0 ? part_n[o + sstar] : -1;
+    if (sstar < 0 && s_n[r][s] >= 0 && s_mx[r][s] == M) sstar = s;   // earliest split = lowest key
+  const int nstar = sstar >= 0 ? s_n[r][sstar] : -1;
+  // weight of every split's sums (they are relative to the split's reference); 0 for an empty split
+  if (c < S) s_w[r][c] = s_m[r][c] == -INFINITY ? 0.f : exp2f(s_ref[r][c] - M);
+  __syncthreads();
   float lrest = 0.f, zr = 0.f;
-  for (int s = 0; s < S; ++s) {
-    const float ms = part_m[o + s];
-    if (ms == -INFINITY) continue;
-    const float wr = exp2f(part_ref[o + s] - M);   // the split's sums are relative to its reference
-    lrest += wr * part_l[o + s];
-    zr += wr * part_z[(o + s) * D + c];
-    if (s != sstar && part_n[o + s] >= 0) {        // a kept-out key that is not the maximum joins the rest
-      const float w = exp2f(part_mx[o + s] - M);
-      lrest += w;
-      zr += w * to_float(vg[(int64_t)part_n[o + s] * pb.kv_st + c]);
+  const float* pz = part_z + o * D + c;
+  int s = 0;
+  for (; s + 8 <= S; s += 8) {               // eight independent loads in flight
+    float t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t[k] = pz[(int64_t)(s + k) * D];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {            // an empty split's sums may hold anything, NaN included
+      const float wk = s_w[r][s + k];
+      zr = fmaf(wk, wk != 0.f ? t[k] : 0.f, zr);
+      lrest = fmaf(wk, wk != 0.f ? s_l[r][s + k] : 0.f, lrest);
     }
+  }
+  for (; s < S; ++s) {
+    const float wk = s_w[r][s];
+    zr = fmaf(wk, wk != 0.f ? pz[(int64_t)s * D] : 0.f, zr);
+    lrest = fmaf(wk, wk != 0.f ? s_l[r][s] : 0.f, lrest);
+  }
+  __syncthreads();                           // s_w is reused
+  // kept-out keys that are not the maximum join the rest: weight 2^(logit - M), 0 otherwise.
+  // Their value rows are fetched unconditionally (row 0 when there is none) so that the loads of
+  // a batch are independent instead of one round trip per split.
+  if (c < S) s_w[r][c] = (c != sstar && s_n[r][c] >= 0 && s_m[r][c] != -INFINITY) ? exp2f(s_mx[r][c] - M) : 0.f;
+  __syncthreads();
+  for (s = 0; s < S; s += 8) {
+    float t[8], wk[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int sk = min(s + k, S - 1);
+      wk[k] = s + k < S ? s_w[r][sk] : 0.f;
+      t[k] = to_float(vg[(int64_t)(wk[k] != 0.f ? s_n[r][sk] : 0) * pb.kv_st + c]);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { zr = fmaf(wk[k], t[k], zr); lrest += wk[k]; }
   }
   float l, z, x;
   if (nstar >= 0) {
@@ -108,27 +144,35 @@ __global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict
     z = zr / l;
     x = 0.f;
   }
-  zs[c] = z;
-  xs[c] = x;
+  zq[r][c] = z;
+  xq[r][c] = x;
   __syncthreads();
   float u = z, y = x;
   if (gram) {
-    const float* Mh = gram + (int64_t)h * D * D;
     u = 0.f; y = 0.f;
+#pragma unroll 8
     for (int a = 0; a < D; ++a) {
-      const float mv = Mh[a * D + c];
-      u = fmaf(zs[a], mv, u);
-      y = fmaf(xs[a], mv, y);
+      const float mv = Mh_s[a * D + c];
+      u = fmaf(zq[r][a], mv, u);
+      y = fmaf(xq[r][a], mv, y);
     }
   }
-  const float zz = block_sum(u * z, red, D);
-  const float qx = block_sum(y * x, red, D);
+  // zz = u.z and |x|_M^2 = y.x of the row: wavefront sums, then across the row's wavefronts
+  float s0 = u * z, s1 = y * x;
+#pragma unroll
+  for (int sh = 32; sh >= 1; sh >>= 1) { s0 += __shfl_xor(s0, sh, 64); s1 += __shfl_xor(s1, sh, 64); }
+  if ((c & 63) == 0) { red[r][c >> 6][0] = s0; red[r][c >> 6][1] = s1; }
+  __syncthreads();
+  if (!live) return;
+  float zz = 0.f, qx = 0.f;
+#pragma unroll
+  for (int wv = 0; wv < NWV; ++wv) { zz += red[r][wv][0]; qx += red[r][wv][1]; }
   rs_u[(int64_t)row * D + c] = u;
   if (op) {
     // q, and u split into bf16 high and low parts, in the order the score pass feeds them to the
     // matrix cores: [which][32-row block][d/16][lane half][local row][8], local row =
     // position * Gp + head, so that a wavefront fetches each operand register as one 1 KiB run
-    const int i = row - h * pb.W, head = h - g * pb.G;
+    const int head = h - g * pb.G;
     const int log2iw = 5 - log2gp;
     const int wb = i >> log2iw, m_ = ((i & ((1 << log2iw) - 1)) << log2gp) + head;
     const int64_t nb = (int64_t)pb.Hkv * nwb;
@@ -155,5 +199,9 @@ __global__ __launch_bounds__(D) void k_attn_combine(Prob pb, const T* __restrict
   }
 }
 
+// launch configuration of k_attn_combine
+inline dim3 combine_grid(const Prob& pb) { return dim3((pb.W + CMB_RQ - 1) / CMB_RQ, pb.Hq); }
+template <int D>
+inline dim3 combine_block() { return dim3(CMB_RQ * D); }
 
 }  // namespace restkv

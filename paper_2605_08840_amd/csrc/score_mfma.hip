@@ -863,7 +863,7 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
   kps = (kps + TN - 1) / TN * TN;
   RK_LAUNCH(ST_ATTN, st, (k_attn_pipe<D>), dim3(S, gy, pb.Hkv), dim3(512), 0, st, pb, qq, kk, vp, S, kps,
             log2iw, w);
-  RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<bf16_t, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb,
+  RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<bf16_t, D>), combine_grid(pb), combine_block<D>(), 0, st, pb,
             (const bf16_t*)v, S, gram, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
             w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, (const bf16_t*)q, w.op, ilog2(gp), lay.nwb);
   if (gram) {

@@ -288,7 +288,7 @@ int run(const Prob& pb, const void* q, const void* k, const void* v, const float
   const int S = lay.S_simple;
   RK_LAUNCH(ST_ATTN, st, (k_attn_partial<T, D>), dim3(S, (pb.R + RB - 1) / RB, pb.Hkv), dim3(256), 0, st,
                      pb, qq, kk, vp, S, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z);
-  RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<T, D>), dim3(pb.Hq * pb.W), dim3(D), 0, st, pb, vp, S, gram,
+  RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<T, D>), combine_grid(pb), combine_block<D>(), 0, st, pb, vp, S, gram,
             w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m, w.rs_l, w.rs_zz, w.rs_nstar,
             w.rs_istar, w.rs_u, (const T*)nullptr, (uint16_t*)nullptr, 0, 0);
   RK_LAUNCH(ST_VV, st, (k_vv<T, D>), dim3((pb.P + 63) / 64, pb.Hq), dim3(256), 0, st, pb, vp, gram, w.vv, lay.ldv);
