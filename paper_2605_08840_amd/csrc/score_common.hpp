@@ -62,11 +62,11 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
                                                              const T* __restrict__ q, uint16_t* __restrict__ op,
                                                              int log2gp, int nwb) {
   constexpr int NWV = D / 64, SMAX = 64;     // wavefronts per row; capacity of the split dimension
-  __shared__ float Mh_s[D * D];              // the head's Gram matrix (unused when gram == NULL)
+  __shared__ __attribute__((aligned(16))) float Mh_s[D * D];   // the head's Gram matrix (unused when gram == NULL)
   __shared__ float zq[CMB_RQ][D], xq[CMB_RQ][D];
   __shared__ float red[CMB_RQ][NWV][2];
-  __shared__ float s_m[CMB_RQ][SMAX], s_mx[CMB_RQ][SMAX], s_ref[CMB_RQ][SMAX], s_l[CMB_RQ][SMAX];
-  __shared__ int s_n[CMB_RQ][SMAX];
+  __shared__ float s_m[CMB_RQ][1], s_mx[CMB_RQ][SMAX], s_l[CMB_RQ][SMAX];
+  __shared__ int s_n[CMB_RQ][SMAX + 1];      // [SMAX]: the split that holds the champion, or -1
   __shared__ float s_w[CMB_RQ][SMAX];
   const int h = blockIdx.y, g = h / pb.G;
   const int r = threadIdx.x / D, c = threadIdx.x % D;
@@ -75,63 +75,67 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
   const int row = h * pb.W + (live ? i : 0);
   const T* vg = v + (int64_t)g * pb.kv_sh;
   const int64_t o = (int64_t)row * S;
-  if (c < S) {                               // S <= SMAX <= D
-    s_m[r][c] = part_m[o + c];
-    s_mx[r][c] = part_mx[o + c];
-    s_n[r][c] = part_n[o + c];
-    s_ref[r][c] = part_ref[o + c];
-    s_l[r][c] = part_l[o + c];
-  }
+  // The Gram matrix travels through registers while the splits are merged (written to LDS just
+  // before the matrix-vector product): its latency hides behind the merge.
+  constexpr int GQ = D * D / 4 / (CMB_RQ * D);     // float4 per thread
+  float4 gq[GQ];
   if (gram) {
-    const float* Mh = gram + (int64_t)h * D * D;
-    for (int x = threadIdx.x; x < D * D; x += CMB_RQ * D) Mh_s[x] = Mh[x];
+    const float4* Mh4 = (const float4*)(gram + (int64_t)h * D * D);
+#pragma unroll
+    for (int k = 0; k < GQ; ++k) gq[k] = Mh4[threadIdx.x + k * (CMB_RQ * D)];
+  }
+  // Per-split scalars: thread c < S of the row's first wavefront owns split c (S <= 64).
+  float pm = -INFINITY, pmx = 0.f, pref = 0.f, pl = 0.f;
+  int pn = -1;
+  if (c < S) {
+    pm = part_m[o + c];
+    pmx = part_mx[o + c];
+    pn = part_n[o + c];
+    pref = part_ref[o + c];
+    pl = part_l[o + c];
+  }
+  if (c < 64) {
+    float M0 = pm;
+#pragma unroll
+    for (int sh = 32; sh >= 1; sh >>= 1) M0 = fmaxf(M0, __shfl_xor(M0, sh, 64));
+    // split whose kept-out key is the overall maximum: the earliest one (= lowest key)
+    const unsigned long long cand = __ballot(pn >= 0 && pmx == M0);
+    const int ss = cand ? __builtin_ctzll(cand) : -1;
+    const bool empty = pm == -INFINITY;
+    // weight of the split's sums (relative to its reference); weight of its kept-out key if that
+    // key joins the rest (it does unless it is the overall maximum); 0 for an empty split
+    s_w[r][c] = empty ? 0.f : exp2f(pref - M0);
+    s_l[r][c] = empty ? 0.f : pl;                  // an empty split's sums may hold anything
+    s_mx[r][c] = (!empty && pn >= 0 && c != ss) ? exp2f(pmx - M0) : 0.f;
+    s_n[r][c] = pn;
+    if (c == 0) { s_m[r][0] = M0; s_n[r][SMAX] = ss; }
   }
   __syncthreads();
-
-  float M = -INFINITY;
-  for (int s = 0; s < S; ++s) M = fmaxf(M, s_m[r][s]);
-  int sstar = -1;                            // split whose kept-out key is the overall maximum
-  for (int s = 0; s < S; ++s)
-    if (sstar < 0 && s_n[r][s] >= 0 && s_mx[r][s] == M) sstar = s;   // earliest split = lowest key
+  const float M = s_m[r][0];
+  const int sstar = s_n[r][SMAX];
   const int nstar = sstar >= 0 ? s_n[r][sstar] : -1;
-  // weight of every split's sums (they are relative to the split's reference); 0 for an empty split
-  if (c < S) s_w[r][c] = s_m[r][c] == -INFINITY ? 0.f : exp2f(s_ref[r][c] - M);
-  __syncthreads();
+
   float lrest = 0.f, zr = 0.f;
   const float* pz = part_z + o * D + c;
-  int s = 0;
-  for (; s + 8 <= S; s += 8) {               // eight independent loads in flight
-    float t[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) t[k] = pz[(int64_t)(s + k) * D];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {            // an empty split's sums may hold anything, NaN included
-      const float wk = s_w[r][s + k];
-      zr = fmaf(wk, wk != 0.f ? t[k] : 0.f, zr);
-      lrest = fmaf(wk, wk != 0.f ? s_l[r][s + k] : 0.f, lrest);
-    }
-  }
-  for (; s < S; ++s) {
-    const float wk = s_w[r][s];
-    zr = fmaf(wk, wk != 0.f ? pz[(int64_t)s * D] : 0.f, zr);
-    lrest = fmaf(wk, wk != 0.f ? s_l[r][s] : 0.f, lrest);
-  }
-  __syncthreads();                           // s_w is reused
-  // kept-out keys that are not the maximum join the rest: weight 2^(logit - M), 0 otherwise.
-  // Their value rows are fetched unconditionally (row 0 when there is none) so that the loads of
-  // a batch are independent instead of one round trip per split.
-  if (c < S) s_w[r][c] = (c != sstar && s_n[r][c] >= 0 && s_m[r][c] != -INFINITY) ? exp2f(s_mx[r][c] - M) : 0.f;
-  __syncthreads();
-  for (s = 0; s < S; s += 8) {
-    float t[8], wk[8];
+  for (int s = 0; s < S; s += 8) {           // sixteen independent loads in flight
+    float t[8], tv[8], wk[8], wv[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const int sk = min(s + k, S - 1);
-      wk[k] = s + k < S ? s_w[r][sk] : 0.f;
-      t[k] = to_float(vg[(int64_t)(wk[k] != 0.f ? s_n[r][sk] : 0) * pb.kv_st + c]);
+      const bool in = s + k < S;
+      wk[k] = in ? s_w[r][sk] : 0.f;
+      wv[k] = in ? s_mx[r][sk] : 0.f;
+      t[k] = pz[(int64_t)sk * D];
+      // value row of the kept-out key, fetched unconditionally (row 0 when there is none)
+      tv[k] = to_float(vg[(int64_t)(wv[k] != 0.f ? s_n[r][sk] : 0) * pb.kv_st + c]);
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) { zr = fmaf(wk[k], t[k], zr); lrest += wk[k]; }
+    for (int k = 0; k < 8; ++k) {
+      zr = fmaf(wk[k], wk[k] != 0.f ? t[k] : 0.f, zr);
+      lrest = fmaf(wk[k], s + k < S ? s_l[r][min(s + k, S - 1)] : 0.f, lrest);
+      zr = fmaf(wv[k], tv[k], zr);
+      lrest += wv[k];
+    }
   }
   float l, z, x;
   if (nstar >= 0) {
@@ -146,6 +150,10 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
   }
   zq[r][c] = z;
   xq[r][c] = x;
+  if (gram) {
+#pragma unroll
+    for (int k = 0; k < GQ; ++k) ((float4*)Mh_s)[threadIdx.x + k * (CMB_RQ * D)] = gq[k];
+  }
   __syncthreads();
   float u = z, y = x;
   if (gram) {
