@@ -101,6 +101,7 @@ def cpu_baseline(w, q, k, v, wo, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--streams", type=int, default=1, help="HIP streams the layers are spread over")
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="drift_128k")
@@ -144,11 +145,16 @@ def main():
         del wo
         layers.append((q, k, v, gram))
     torch.cuda.synchronize()
-    buf = rk.alloc_layer_buffers(p, dt, dev)
+    # Layers are independent: with --streams N > 1 they are spread round-robin over N streams
+    # (each with its own outputs and scratch) so that the short latency-bound kernels of one layer
+    # overlap the long ones of another.
+    n_str = max(1, args.streams)
+    bufs = [rk.alloc_layer_buffers(p, dt, dev) for _ in range(n_str)]
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(n_str - 1)]
 
     def step():
-        for (q, k, v, gram) in layers:
-            rk.evict_layer(p, q, k, v, gram, buf)
+        for j, (q, k, v, gram) in enumerate(layers):
+            rk.evict_layer(p, q, k, v, gram, bufs[j % n_str], stream=streams[j % n_str])
 
     for _ in range(args.warmup):
         step()

@@ -52,19 +52,16 @@ __global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __
 // Fused single read of the raw score: EMA over the window queries (the recursion of Sec. 3.3:
 // first query as is, every later one enters with weight alpha) and, per (head, query) row,
 // the count / position sum of the entries above the bracket and the list of entries inside it.
-// A workgroup owns NPB prefix positions of one head for all W queries.  Entries above the
-// bracket go straight into per-row LDS counters; entries inside it are staged in an LDS list
-// that is flushed (one global atomic per row) at the end; an entry that finds the list full is
-// appended to its row directly.  grid (ceil(P/NPB), Hkv), 256 threads, 4 positions per thread.
-// sum of the positions of the set bits of a 64-bit lane mask (scalar work)
-__device__ __forceinline__ unsigned long long bit_position_sum(unsigned long long m) {
-  return (unsigned long long)(__popcll(m & 0xAAAAAAAAAAAAAAAAull) + 2 * __popcll(m & 0xCCCCCCCCCCCCCCCCull) +
-                              4 * __popcll(m & 0xF0F0F0F0F0F0F0F0ull) + 8 * __popcll(m & 0xFF00FF00FF00FF00ull) +
-                              16 * __popcll(m & 0xFFFF0000FFFF0000ull) + 32 * __popcll(m & 0xFFFFFFFF00000000ull));
-}
-
-constexpr int LIST_CAP = 6144;      // staged candidates per workgroup
-constexpr int ROWS_BLK = 256;       // rows between forced flushes (bounds the LDS counters)
+// A workgroup owns NPB prefix positions of one head for all W queries; a thread owns 4 of them.
+// While streaming, a thread only packs what it saw into two LDS words per group of RG rows
+// (per row: 3-bit count and 3-bit element-offset sum of the entries above the bracket, 4-bit
+// mask of the entries inside it): no cross-lane work and no scalar-ALU ballots in the stream.
+// After every ROWS_BLK rows the workgroup turns around: thread j = (row, quarter of the
+// workgroup's threads) adds up its 64 packed words, the four quarters of a row meet through
+// lane shuffles, and one thread per row issues the row's global atomics; the candidates are
+// then written from the packed masks (their values are re-read: cache hits).
+// grid (ceil(P/NPB), Hkv), 256 threads.
+constexpr int ROWS_BLK = 64;        // rows per turn-around of the fused pass
 
 __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restrict__ score,
                                                   float* __restrict__ ema, const float2* __restrict__ thr,
@@ -73,48 +70,75 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
                                                   uint32_t* __restrict__ ncand,
                                                   float* __restrict__ cand_val, int* __restrict__ cand_idx,
                                                   int vec) {
-  __shared__ uint32_t list[LIST_CAP];     // position in the workgroup (10 bits) | row since flush << 10
-  __shared__ uint32_t lcnt, ccnt[ROWS_BLK], hcnt[ROWS_BLK], base[ROWS_BLK];
-  __shared__ unsigned long long hsum[ROWS_BLK];
+  __shared__ uint32_t pk0[ROWS_BLK / RG][256];   // per thread and row group: RG x (count:3 | offset sum:3)
+  __shared__ uint32_t pk1[ROWS_BLK / RG][256];   // RG x 4-bit masks of the entries inside the bracket
   const int g = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
-  const unsigned long long lane_lt = (1ull << lane) - 1ull;
   const int nb0 = blockIdx.x * NPB, n0 = nb0 + tid * 4;
   const float* s = score + (int64_t)g * pb.W * pb.ld;
   const float a = pb.alpha, b = 1.0f - pb.alpha;
   const bool scan = pb.adaptive != 0;
-  if (tid == 0) lcnt = 0;
-  for (int x = tid; x < ROWS_BLK; x += 256) { ccnt[x] = 0; hcnt[x] = 0; hsum[x] = 0ull; }
-  __syncthreads();
 
-  // rows [rb0, rb1) have been scanned since the last flush
-  auto flush = [&](int rb0, int rb1) {
+  // rows [rb0, rb0 + nrows) of the head have been streamed and packed
+  auto turn_around = [&](int rb0, int nrows) {
     __syncthreads();
-    const uint32_t E = min(lcnt, (uint32_t)LIST_CAP);
-    for (uint32_t x = tid; x < E; x += 256) {
-      const uint32_t rl = (list[x] >> 10) & 255u;
-      list[x] |= atomicAdd(&ccnt[rl], 1u) << 18;
-    }
-    __syncthreads();
-    for (int x = tid; x < rb1 - rb0; x += 256) {
-      const int row = g * pb.W + rb0 + x;
-      if (ccnt[x]) base[x] = atomicAdd(&ncand[row], ccnt[x]);
-      if (hcnt[x]) { atomicAdd(&cnt_hi[row], hcnt[x]); atomicAdd(&sum_hi[row], hsum[x]); }
-    }
-    __syncthreads();
-    for (uint32_t x = tid; x < E; x += 256) {
-      const uint32_t en = list[x];
-      const uint32_t rl = (en >> 10) & 255u;
-      const uint32_t pos = base[rl] + (en >> 18);
-      if (pos < (uint32_t)CAND_CAP) {
-        const int n = nb0 + (int)(en & 1023u);
-        const int64_t o = (int64_t)(g * pb.W + rb0 + (int)rl) * CAND_CAP + pos;
-        cand_val[o] = s[(int64_t)(rb0 + (int)rl) * pb.ld + n];     // value read back (cache hit)
-        cand_idx[o] = n;
+    const int rl = tid >> 2, qd = tid & 3;
+    // the 16 (row group, quarter) pairs of a wavefront start their walk 4 words apart: no two
+    // of them meet in an LDS bank
+    const int rot = 4 * (((lane >> 4) << 2) | (lane & 3));
+    const int itr = rl / RG, sh0 = 6 * (rl % RG), sh1 = 4 * (rl % RG);
+    uint32_t cnt = 0, els = 0, wsum = 0, nc = 0;
+    if (rl < nrows) {
+      for (int tt = 0; tt < 64; ++tt) {
+        const int t = (tt + rot) & 63;
+        const uint32_t a0 = (pk0[itr][64 * qd + t] >> sh0) & 63u;
+        const uint32_t c = a0 & 7u;
+        cnt += c;
+        els += a0 >> 3;
+        wsum += c * (uint32_t)t;
+        nc += (uint32_t)__popc((pk1[itr][64 * qd + t] >> sh1) & 15u);
       }
     }
-    __syncthreads();
-    if (tid == 0) lcnt = 0;
-    for (int x = tid; x < ROWS_BLK; x += 256) { ccnt[x] = 0; hcnt[x] = 0; hsum[x] = 0ull; }
+    // positions above the bracket seen by this quarter: thread t of it owns nb0 + 4 (64 qd + t) + el
+    const unsigned long long hs_own = (unsigned long long)cnt * (unsigned long long)(nb0 + 256 * qd) +
+                                      4ull * wsum + (unsigned long long)els;
+    unsigned long long hs = hs_own;
+    // the four quarters of a row sit in four adjacent lanes
+    uint32_t nc_below = 0, nc_tot = nc, cnt_tot = cnt;
+#pragma unroll
+    for (int d = 1; d < 4; ++d) {
+      const int src = (lane & ~3) | ((lane + d) & 3);
+      const uint32_t onc = (uint32_t)__shfl((int)nc, src, 64);
+      cnt_tot += (uint32_t)__shfl((int)cnt, src, 64);
+      hs += ((unsigned long long)(uint32_t)__shfl((int)(hs_own >> 32), src, 64) << 32) |
+            (unsigned long long)(uint32_t)__shfl((int)(uint32_t)hs_own, src, 64);
+      nc_tot += onc;
+      if (((lane + d) & 3) < qd) nc_below += onc;
+    }
+    const int row = g * pb.W + rb0 + rl;
+    uint32_t base = 0;
+    if (qd == 0 && rl < nrows) {
+      if (cnt_tot) { atomicAdd(&cnt_hi[row], cnt_tot); atomicAdd(&sum_hi[row], hs); }
+      if (nc_tot) base = atomicAdd(&ncand[row], nc_tot);
+    }
+    base = (uint32_t)__shfl((int)base, lane & ~3, 64);
+    if (rl < nrows && nc) {
+      uint32_t pos = base + nc_below;
+      const float* srow = s + (int64_t)(rb0 + rl) * pb.ld;
+      for (int tt = 0; tt < 64; ++tt) {
+        const int t = (tt + rot) & 63;
+        uint32_t mk = (pk1[itr][64 * qd + t] >> sh1) & 15u;
+        while (mk) {
+          const int el = __builtin_ctz(mk);
+          mk &= mk - 1;
+          if (pos < (uint32_t)CAND_CAP) {
+            const int n = nb0 + 4 * (64 * qd + t) + el;
+            cand_val[(int64_t)row * CAND_CAP + pos] = srow[n];     // value read back (cache hit)
+            cand_idx[(int64_t)row * CAND_CAP + pos] = n;
+          }
+          ++pos;
+        }
+      }
+    }
     __syncthreads();
   };
 
@@ -140,7 +164,7 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
     }
   };
   fetch(0);
-  int rb0 = 0;                       // first row since the last flush
+  int rb0 = 0;                       // first row since the last turn-around
   for (int i0 = 0; i0 < pb.W; i0 += RG) {
     float xc[RG][4];
     float2 thc[RG];
@@ -151,62 +175,36 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
       for (int el = 0; el < 4; ++el) xc[r][el] = xs[r][el];
     }
     if (i0 + RG < pb.W) fetch(i0 + RG);
-    if (scan && i0 + RG - rb0 > ROWS_BLK) {        // block-uniform: bounds the LDS row counters
-      flush(rb0, i0);
-      rb0 = i0;
-    }
+    uint32_t w0 = 0, w1 = 0;
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
       const int i = i0 + r;
       if (i >= pb.W) break;
       const float* x = xc[r];
       const float2 th = thc[r];
-      const uint32_t rl = (uint32_t)(i - rb0);
-      const bool has_hi = th.y < INFINITY;        // wave-uniform (same row for every lane)
-      // hits are found with wave-wide ballots: one LDS atomic per wavefront and row
-      unsigned long long mh[4], mc[4];
-      uint32_t nh = 0, nc = 0;
+      uint32_t cnt = 0, els = 0, cm = 0;
 #pragma unroll
       for (int el = 0; el < 4; ++el) {
         e[el] = i == 0 ? x[el] : a * x[el] + b * e[el];
-        mh[el] = has_hi ? __ballot(x[el] > th.y) : 0ull;
-        mc[el] = __ballot(x[el] > th.x) & ~mh[el];
-        nh += (uint32_t)__popcll(mh[el]);
-        nc += (uint32_t)__popcll(mc[el]);
+        const bool hi = x[el] > th.y;              // th.y = +inf: the bracket has no upper bound
+        const bool in = x[el] > th.x && !hi;
+        cnt += hi ? 1u : 0u;
+        els += hi ? (uint32_t)el : 0u;
+        cm |= in ? (1u << el) : 0u;
       }
-      if (nh) {                                   // wave-uniform
-        unsigned long long ps = 0;
-#pragma unroll
-        for (int el = 0; el < 4; ++el)
-          ps += 4ull * bit_position_sum(mh[el]) +
-                (unsigned long long)__popcll(mh[el]) * (unsigned long long)(nb0 + (tid & ~63) * 4 + el);
-        if (lane == 0) { atomicAdd(&hcnt[rl], nh); atomicAdd(&hsum[rl], ps); }
-      }
-      if (nc) {                                   // wave-uniform
-        uint32_t slot0 = 0;
-        if (lane == 0) slot0 = atomicAdd(&lcnt, nc);
-        slot0 = __builtin_amdgcn_readfirstlane(slot0);
-#pragma unroll
-        for (int el = 0; el < 4; ++el) {
-          if ((mc[el] >> lane) & 1ull) {
-            const uint32_t slot = slot0 + (uint32_t)__popcll(mc[el] & lane_lt);
-            if (slot < (uint32_t)LIST_CAP) {
-              list[slot] = (uint32_t)(tid * 4 + el) | (rl << 10);
-            } else {                 // staging list full (a dense cluster of hits): append directly
-              const int row = g * pb.W + i;
-              const uint32_t pos = atomicAdd(&ncand[row], 1u);
-              if (pos < (uint32_t)CAND_CAP) {
-                cand_val[(int64_t)row * CAND_CAP + pos] = x[el];
-                cand_idx[(int64_t)row * CAND_CAP + pos] = n0 + el;
-              }
-            }
-          }
-          slot0 += (uint32_t)__popcll(mc[el]);
-        }
+      w0 |= (cnt | (els << 3)) << (6 * r);
+      w1 |= cm << (4 * r);
+    }
+    if (scan) {
+      const int it = (i0 - rb0) / RG;
+      pk0[it][tid] = w0;
+      pk1[it][tid] = w1;
+      if (i0 + RG - rb0 >= ROWS_BLK || i0 + RG >= pb.W) {      // block-uniform
+        turn_around(rb0, min(i0 + RG, pb.W) - rb0);
+        rb0 = i0 + RG;
       }
     }
   }
-  if (scan) flush(rb0, pb.W);
 #pragma unroll
   for (int el = 0; el < 4; ++el)
     if (n0 + el < pb.P) ema[(int64_t)g * pb.ld + n0 + el] = e[el];
