@@ -53,15 +53,19 @@ __global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __
 // first query as is, every later one enters with weight alpha) and, per (head, query) row,
 // the count / position sum of the entries above the bracket and the list of entries inside it.
 // A workgroup owns NPB prefix positions of one head for all W queries; a thread owns 4 of them.
-// While streaming, a thread only packs what it saw into two LDS words per group of RG rows
-// (per row: 3-bit count and 3-bit element-offset sum of the entries above the bracket, 4-bit
-// mask of the entries inside it): no cross-lane work and no scalar-ALU ballots in the stream.
-// After every ROWS_BLK rows the workgroup turns around: thread j = (row, quarter of the
-// workgroup's threads) adds up its 64 packed words, the four quarters of a row meet through
-// lane shuffles, and one thread per row issues the row's global atomics; the candidates are
-// then written from the packed masks (their values are re-read: cache hits).
+// While streaming, a thread works alone (no cross-lane work, no scalar-ALU ballots): per group
+// of RG rows it packs two LDS words (per row: 3-bit count and 3-bit element-offset sum of its
+// entries above the bracket; 4-bit mask of its entries inside it) and keeps the values of the
+// latter in a private LDS list.  After every ROWS_BLK rows the workgroup turns around:
+//   * thread j = (row, quarter of the workgroup's threads) walks the 64 packed words of its
+//     quarter: it adds up the statistics and leaves every thread's running candidate offset;
+//     the four quarters of a row meet through lane shuffles and one thread per row issues the
+//     row's global atomics (statistics, space in the row's candidate list);
+//   * every thread then writes its own candidates to their final places.  A wavefront whose
+//     private lists did not suffice (a dense cluster of candidates) re-reads its rows instead.
 // grid (ceil(P/NPB), Hkv), 256 threads.
-constexpr int ROWS_BLK = 64;        // rows per turn-around of the fused pass
+constexpr int ROWS_BLK = 32;        // rows per turn-around of the fused pass
+constexpr int CAPT = 12;            // private candidate values per thread between turn-arounds
 
 __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restrict__ score,
                                                   float* __restrict__ ema, const float2* __restrict__ thr,
@@ -70,75 +74,107 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
                                                   uint32_t* __restrict__ ncand,
                                                   float* __restrict__ cand_val, int* __restrict__ cand_idx,
                                                   int vec) {
-  __shared__ uint32_t pk0[ROWS_BLK / RG][256];   // per thread and row group: RG x (count:3 | offset sum:3)
-  __shared__ uint32_t pk1[ROWS_BLK / RG][256];   // RG x 4-bit masks of the entries inside the bracket
+  constexpr int NGRP = ROWS_BLK / RG;
+  __shared__ uint32_t pk0[NGRP][256];            // per thread and row group: RG x (count:3 | offset sum:3)
+  __shared__ uint32_t pk1[NGRP][256];            // RG x 4-bit masks of the entries inside the bracket
+  __shared__ uint8_t pk2[NGRP][256][RG];         // candidates of the row in earlier threads of the quarter
+  __shared__ float pval[CAPT][256];              // private lists of candidate values, in stream order
+  __shared__ uint32_t rbase[ROWS_BLK][4];        // first list position of each (row, quarter)
   const int g = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
   const int nb0 = blockIdx.x * NPB, n0 = nb0 + tid * 4;
   const float* s = score + (int64_t)g * pb.W * pb.ld;
   const float a = pb.alpha, b = 1.0f - pb.alpha;
   const bool scan = pb.adaptive != 0;
+  int kp = 0;                        // candidates of this thread since the last turn-around
 
-  // rows [rb0, rb0 + nrows) of the head have been streamed and packed
+  // rows [rb0, rb0 + nrows) of the head have been streamed
   auto turn_around = [&](int rb0, int nrows) {
     __syncthreads();
-    const int rl = tid >> 2, qd = tid & 3;
-    // the 16 (row group, quarter) pairs of a wavefront start their walk 4 words apart: no two
-    // of them meet in an LDS bank
-    const int rot = 4 * (((lane >> 4) << 2) | (lane & 3));
-    const int itr = rl / RG, sh0 = 6 * (rl % RG), sh1 = 4 * (rl % RG);
-    uint32_t cnt = 0, els = 0, wsum = 0, nc = 0;
-    if (rl < nrows) {
-      for (int tt = 0; tt < 64; ++tt) {
-        const int t = (tt + rot) & 63;
-        const uint32_t a0 = (pk0[itr][64 * qd + t] >> sh0) & 63u;
-        const uint32_t c = a0 & 7u;
-        cnt += c;
-        els += a0 >> 3;
-        wsum += c * (uint32_t)t;
-        nc += (uint32_t)__popc((pk1[itr][64 * qd + t] >> sh1) & 15u);
+    {
+      const int rl = tid >> 2, qd = tid & 3;
+      const int itr = rl / RG, rr = rl % RG, sh0 = 6 * rr, sh1 = 4 * rr;
+      uint32_t cnt = 0, els = 0, wsum = 0, nc = 0;
+      if (rl < nrows) {
+        // (lanes with the same row group and quarter read the same word; the others are 64 or
+        // 256 words apart, so the walk starts at a different word for each of them)
+        const int rot = 4 * (((lane >> 4) << 2) | (lane & 3));
+        for (int tt = 0; tt < 64; ++tt) {
+          const int t = (tt + rot) & 63, src = 64 * qd + t;
+          const uint32_t a0 = (pk0[itr][src] >> sh0) & 63u;
+          const uint32_t c = a0 & 7u;
+          cnt += c;
+          els += a0 >> 3;
+          wsum += c * (uint32_t)t;
+          pk2[itr][src][rr] = (uint8_t)nc;       // at most 252: a quarter holds 256 positions
+          nc += (uint32_t)__popc((pk1[itr][src] >> sh1) & 15u);
+        }
       }
-    }
-    // positions above the bracket seen by this quarter: thread t of it owns nb0 + 4 (64 qd + t) + el
-    const unsigned long long hs_own = (unsigned long long)cnt * (unsigned long long)(nb0 + 256 * qd) +
-                                      4ull * wsum + (unsigned long long)els;
-    unsigned long long hs = hs_own;
-    // the four quarters of a row sit in four adjacent lanes
-    uint32_t nc_below = 0, nc_tot = nc, cnt_tot = cnt;
+      // positions above the bracket seen by this quarter: thread t of it owns nb0 + 4 (64 qd + t) + el
+      const unsigned long long hs_own = (unsigned long long)cnt * (unsigned long long)(nb0 + 256 * qd) +
+                                        4ull * wsum + (unsigned long long)els;
+      unsigned long long hs = hs_own;
+      uint32_t cnt_tot = cnt, nc_tot = nc, nc_below = 0;
+      // the four quarters of a row sit in four adjacent lanes
 #pragma unroll
-    for (int d = 1; d < 4; ++d) {
-      const int src = (lane & ~3) | ((lane + d) & 3);
-      const uint32_t onc = (uint32_t)__shfl((int)nc, src, 64);
-      cnt_tot += (uint32_t)__shfl((int)cnt, src, 64);
-      hs += ((unsigned long long)(uint32_t)__shfl((int)(hs_own >> 32), src, 64) << 32) |
-            (unsigned long long)(uint32_t)__shfl((int)(uint32_t)hs_own, src, 64);
-      nc_tot += onc;
-      if (((lane + d) & 3) < qd) nc_below += onc;
+      for (int d = 1; d < 4; ++d) {
+        const int src = (lane & ~3) | ((lane + d) & 3);
+        const uint32_t onc = (uint32_t)__shfl((int)nc, src, 64);
+        cnt_tot += (uint32_t)__shfl((int)cnt, src, 64);
+        hs += ((unsigned long long)(uint32_t)__shfl((int)(hs_own >> 32), src, 64) << 32) |
+              (unsigned long long)(uint32_t)__shfl((int)(uint32_t)hs_own, src, 64);
+        nc_tot += onc;
+        if (((lane + d) & 3) < qd) nc_below += onc;
+      }
+      uint32_t base = 0;
+      if (qd == 0 && rl < nrows) {
+        const int row = g * pb.W + rb0 + rl;
+        if (cnt_tot) { atomicAdd(&cnt_hi[row], cnt_tot); atomicAdd(&sum_hi[row], hs); }
+        if (nc_tot) base = atomicAdd(&ncand[row], nc_tot);
+      }
+      base = (uint32_t)__shfl((int)base, lane & ~3, 64);
+      if (rl < nrows) rbase[rl][qd] = base + nc_below;
     }
-    const int row = g * pb.W + rb0 + rl;
-    uint32_t base = 0;
-    if (qd == 0 && rl < nrows) {
-      if (cnt_tot) { atomicAdd(&cnt_hi[row], cnt_tot); atomicAdd(&sum_hi[row], hs); }
-      if (nc_tot) base = atomicAdd(&ncand[row], nc_tot);
-    }
-    base = (uint32_t)__shfl((int)base, lane & ~3, 64);
-    if (rl < nrows && nc) {
-      uint32_t pos = base + nc_below;
-      const float* srow = s + (int64_t)(rb0 + rl) * pb.ld;
-      for (int tt = 0; tt < 64; ++tt) {
-        const int t = (tt + rot) & 63;
-        uint32_t mk = (pk1[itr][64 * qd + t] >> sh1) & 15u;
-        while (mk) {
-          const int el = __builtin_ctz(mk);
-          mk &= mk - 1;
-          if (pos < (uint32_t)CAND_CAP) {
-            const int n = nb0 + 4 * (64 * qd + t) + el;
-            cand_val[(int64_t)row * CAND_CAP + pos] = srow[n];     // value read back (cache hit)
-            cand_idx[(int64_t)row * CAND_CAP + pos] = n;
+    __syncthreads();
+    // every thread places its own candidates: rows in stream order, elements in order.  The walk
+    // above visited this thread's quarter starting at its rotation, which only permutes the
+    // order inside the list.
+    if (__ballot(kp > 0) != 0ull) {
+      const bool reread = __ballot(kp > CAPT) != 0ull;     // wave-uniform: private lists overflowed
+      const int qd = tid >> 6;
+      int k = 0;
+      for (int itr = 0; itr * RG < nrows; ++itr) {
+        const uint32_t w1 = pk1[itr][tid];
+        if (__ballot(w1 != 0u) == 0ull) continue;
+#pragma unroll
+        for (int rr = 0; rr < RG; ++rr) {
+          const int rl = itr * RG + rr;
+          uint32_t mk = (w1 >> (4 * rr)) & 15u;
+          if (__ballot(mk != 0u) == 0ull) continue;
+          float x4[4] = {0.f, 0.f, 0.f, 0.f};
+          if (reread) {                                     // coalesced: the whole wavefront's row piece
+            const float* rp = s + (int64_t)(rb0 + rl) * pb.ld + n0;
+#pragma unroll
+            for (int el = 0; el < 4; ++el) x4[el] = n0 + el < pb.P ? rp[el] : 0.f;
           }
-          ++pos;
+          if (mk) {
+            const int row = g * pb.W + rb0 + rl;
+            uint32_t pos = rbase[rl][qd] + pk2[itr][tid][rr];
+#pragma unroll
+            for (int el = 0; el < 4; ++el) {
+              if ((mk >> el) & 1u) {
+                if (pos < (uint32_t)CAND_CAP) {
+                  cand_val[(int64_t)row * CAND_CAP + pos] = reread ? x4[el] : pval[min(k, CAPT - 1)][tid];
+                  cand_idx[(int64_t)row * CAND_CAP + pos] = n0 + el;
+                }
+                ++pos;
+                ++k;
+              }
+            }
+          }
         }
       }
     }
+    kp = 0;
     __syncthreads();
   };
 
@@ -187,18 +223,20 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
       for (int el = 0; el < 4; ++el) {
         e[el] = i == 0 ? x[el] : a * x[el] + b * e[el];
         const bool hi = x[el] > th.y;              // th.y = +inf: the bracket has no upper bound
-        const bool in = x[el] > th.x && !hi;
         cnt += hi ? 1u : 0u;
         els += hi ? (uint32_t)el : 0u;
-        cm |= in ? (1u << el) : 0u;
+        if (x[el] > th.x && !hi) {                 // inside the bracket: rare
+          if (kp < CAPT) pval[kp][tid] = x[el];
+          ++kp;
+          cm |= 1u << el;
+        }
       }
       w0 |= (cnt | (els << 3)) << (6 * r);
       w1 |= cm << (4 * r);
     }
     if (scan) {
-      const int it = (i0 - rb0) / RG;
-      pk0[it][tid] = w0;
-      pk1[it][tid] = w1;
+      pk0[(i0 - rb0) / RG][tid] = w0;
+      pk1[(i0 - rb0) / RG][tid] = w1;
       if (i0 + RG - rb0 >= ROWS_BLK || i0 + RG >= pb.W) {      // block-uniform
         turn_around(rb0, min(i0 + RG, pb.W) - rb0);
         rb0 = i0 + RG;
