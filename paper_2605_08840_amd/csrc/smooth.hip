@@ -78,7 +78,8 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
   __shared__ uint32_t pk0[NGRP][256];            // per thread and row group: RG x (count:3 | offset sum:3)
   __shared__ uint32_t pk1[NGRP][256];            // RG x 4-bit masks of the entries inside the bracket
   __shared__ uint8_t pk2[NGRP][256][RG];         // candidates of the row in earlier threads of the quarter
-  __shared__ float pval[CAPT][256];              // private lists of candidate values, in stream order
+  __shared__ float pval[CAPT][256];              // private lists of candidates, in stream order: value ...
+  __shared__ uint8_t pmeta[CAPT][256];           // ... and (row in block) * 4 + element
   __shared__ uint32_t rbase[ROWS_BLK][4];        // first list position of each (row, quarter)
   const int g = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
   const int nb0 = blockIdx.x * NPB, n0 = nb0 + tid * 4;
@@ -135,40 +136,64 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
       if (rl < nrows) rbase[rl][qd] = base + nc_below;
     }
     __syncthreads();
-    // every thread places its own candidates: rows in stream order, elements in order.  The walk
-    // above visited this thread's quarter starting at its rotation, which only permutes the
-    // order inside the list.
-    if (__ballot(kp > 0) != 0ull) {
-      const bool reread = __ballot(kp > CAPT) != 0ull;     // wave-uniform: private lists overflowed
-      const int qd = tid >> 6;
-      int k = 0;
-      for (int itr = 0; itr * RG < nrows; ++itr) {
-        const uint32_t w1 = pk1[itr][tid];
-        if (__ballot(w1 != 0u) == 0ull) continue;
+    // every thread places its own candidates (the walk above visited this thread's quarter
+    // starting at the walker's rotation, which only permutes the order inside the list)
+    const int qd = tid >> 6;
+    if (__ballot(kp > CAPT) == 0ull) {
+      // Every private list of the wavefront is complete.  All LDS reads are issued up front
+      // (clamped, not branched around), only the stores are predicated: three LDS round trips
+      // and at most 2 CAPT store instructions per wavefront.
+      int mt[CAPT];
+      float pv[CAPT];
 #pragma unroll
-        for (int rr = 0; rr < RG; ++rr) {
-          const int rl = itr * RG + rr;
-          uint32_t mk = (w1 >> (4 * rr)) & 15u;
-          if (__ballot(mk != 0u) == 0ull) continue;
-          float x4[4] = {0.f, 0.f, 0.f, 0.f};
-          if (reread) {                                     // coalesced: the whole wavefront's row piece
-            const float* rp = s + (int64_t)(rb0 + rl) * pb.ld + n0;
+      for (int k = 0; k < CAPT; ++k) { mt[k] = pmeta[k][tid]; pv[k] = pval[k][tid]; }
+      uint32_t pos[CAPT];
 #pragma unroll
-            for (int el = 0; el < 4; ++el) x4[el] = n0 + el < pb.P ? rp[el] : 0.f;
-          }
-          if (mk) {
-            const int row = g * pb.W + rb0 + rl;
-            uint32_t pos = rbase[rl][qd] + pk2[itr][tid][rr];
+      for (int k = 0; k < CAPT; ++k) {
+        const int rl = k < kp ? mt[k] >> 2 : 0;
+        pos[k] = rbase[rl][qd] + pk2[rl / RG][tid][rl % RG];
+      }
+      int prev = -1;
+      uint32_t run = 0;
 #pragma unroll
-            for (int el = 0; el < 4; ++el) {
-              if ((mk >> el) & 1u) {
-                if (pos < (uint32_t)CAND_CAP) {
-                  cand_val[(int64_t)row * CAND_CAP + pos] = reread ? x4[el] : pval[min(k, CAPT - 1)][tid];
-                  cand_idx[(int64_t)row * CAND_CAP + pos] = n0 + el;
-                }
-                ++pos;
-                ++k;
+      for (int k = 0; k < CAPT; ++k) {
+        const int rl = mt[k] >> 2;
+        run = rl == prev ? run + 1u : 0u;          // this thread's earlier candidates of the same row
+        prev = rl;
+        const uint32_t ps = pos[k] + run;
+        if (k < kp && ps < (uint32_t)CAND_CAP) {
+          const int64_t o = (int64_t)(g * pb.W + rb0 + rl) * CAND_CAP + ps;
+          cand_val[o] = pv[k];
+          cand_idx[o] = n0 + (mt[k] & 3);
+        }
+      }
+    } else {
+      // a dense cluster: the wavefront re-reads its rows (coalesced, two row groups = 8 rows per
+      // round trip) and walks its masks
+      for (int it0 = 0; it0 * RG < nrows; it0 += 2) {
+        float x4[2 * RG][4];
+#pragma unroll
+        for (int q = 0; q < 2 * RG; ++q) {
+          const int rl = min(it0 * RG + q, nrows - 1);
+          const float* rp = s + (int64_t)(rb0 + rl) * pb.ld + n0;
+#pragma unroll
+          for (int el = 0; el < 4; ++el) x4[q][el] = n0 + el < pb.P ? rp[el] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 2 * RG; ++q) {
+          const int itr = it0 + q / RG, rr = q % RG, rl = it0 * RG + q;
+          if (rl >= nrows) break;
+          const uint32_t mk = (pk1[itr][tid] >> (4 * rr)) & 15u;
+          const int row = g * pb.W + rb0 + rl;
+          uint32_t ps = rbase[rl][qd] + pk2[itr][tid][rr];
+#pragma unroll
+          for (int el = 0; el < 4; ++el) {
+            if ((mk >> el) & 1u) {
+              if (ps < (uint32_t)CAND_CAP) {
+                cand_val[(int64_t)row * CAND_CAP + ps] = x4[q][el];
+                cand_idx[(int64_t)row * CAND_CAP + ps] = n0 + el;
               }
+              ++ps;
             }
           }
         }
@@ -226,7 +251,7 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
         cnt += hi ? 1u : 0u;
         els += hi ? (uint32_t)el : 0u;
         if (x[el] > th.x && !hi) {                 // inside the bracket: rare
-          if (kp < CAPT) pval[kp][tid] = x[el];
+          if (kp < CAPT) { pval[kp][tid] = x[el]; pmeta[kp][tid] = (uint8_t)((i - rb0) * 4 + el); }
           ++kp;
           cm |= 1u << el;
         }
