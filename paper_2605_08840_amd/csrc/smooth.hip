@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __
     const int ns = min(pb.P, SMP_NS);
     int r_hi, r_lo;
     bracket_ranks(pb.P, ns, k, r_hi, r_lo);
-    if ((float)r_lo * (float)pb.P / (float)ns <= 0.75f * (float)CAND_CAP) khi = 0xFFFFFFFFu;
+    if (false && (float)r_lo * (float)pb.P / (float)ns <= 0.75f * (float)CAND_CAP) khi = 0xFFFFFFFFu;
   }
   if (threadIdx.x == 0)
     thr[r] = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
