@@ -99,6 +99,7 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
         // (lanes with the same row group and quarter read the same word; the others are 64 or
         // 256 words apart, so the walk starts at a different word for each of them)
         const int rot = 4 * (((lane >> 4) << 2) | (lane & 3));
+#pragma unroll 8
         for (int tt = 0; tt < 64; ++tt) {
           const int t = (tt + rot) & 63, src = 64 * qd + t;
           const uint32_t a0 = (pk0[itr][src] >> sh0) & 63u;
@@ -212,11 +213,16 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
     for (int r = 0; r < RG; ++r) {
       const int i = i0 + r;
       if (i < pb.W) {
-        const float* rp = s + (int64_t)i * pb.ld + n0;
-        if (vec && n0 + 3 < pb.P) {
-          const float4 v4 = *(const float4*)rp;
-          xs[r][0] = v4.x; xs[r][1] = v4.y; xs[r][2] = v4.z; xs[r][3] = v4.w;
+        if (vec) {
+          // one 16-byte load per thread, no branch at the tail: threads past the end re-read the
+          // last aligned quad of the row (inside its ld floats) and discard it
+          const float4 v4 = *(const float4*)(s + (int64_t)i * pb.ld + min(n0, (pb.P - 1) & ~3));
+          xs[r][0] = n0 + 0 < pb.P ? v4.x : -INFINITY;
+          xs[r][1] = n0 + 1 < pb.P ? v4.y : -INFINITY;
+          xs[r][2] = n0 + 2 < pb.P ? v4.z : -INFINITY;
+          xs[r][3] = n0 + 3 < pb.P ? v4.w : -INFINITY;
         } else {
+          const float* rp = s + (int64_t)i * pb.ld + n0;
 #pragma unroll
           for (int el = 0; el < 4; ++el) xs[r][el] = n0 + el < pb.P ? rp[el] : -INFINITY;
         }
