@@ -13,7 +13,7 @@ namespace {
 
 constexpr int CAND_CAP = 4096;      // candidates kept per (head, query) row
 constexpr int SMP_NS = 8192;        // samples per row for the bracket
-constexpr int RG = 4;               // rows per flush group of the fused pass
+constexpr int RG = 4;               // rows in flight per thread of the fused pass (multiple of 4)
 constexpr int NPB = 1024;           // prefix positions per workgroup of the fused pass
 
 // Bracket of the top-min(B,P) threshold of one (head, query) row from a sample of the row.
@@ -37,14 +37,6 @@ __global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __
   int it = 0;
   uint32_t klo, khi;
   block_bracket<SMP_NS / 256, 16>(row, pb.P, k, cs, it, klo, khi);
-  {
-    // when everything above the lower bound is expected to fit the candidate list, no upper
-    // bound is used (the fused pass then has a single test per entry)
-    const int ns = min(pb.P, SMP_NS);
-    int r_hi, r_lo;
-    bracket_ranks(pb.P, ns, k, r_hi, r_lo);
-    if (false && (float)r_lo * (float)pb.P / (float)ns <= 0.75f * (float)CAND_CAP) khi = 0xFFFFFFFFu;
-  }
   if (threadIdx.x == 0)
     thr[r] = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
 }
@@ -74,10 +66,11 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
                                                   uint32_t* __restrict__ ncand,
                                                   float* __restrict__ cand_val, int* __restrict__ cand_idx,
                                                   int vec) {
-  constexpr int NGRP = ROWS_BLK / RG;
+  constexpr int PG = 4;                          // rows per packed LDS word
+  constexpr int NGRP = ROWS_BLK / PG;
   __shared__ uint32_t pk0[NGRP][256];            // per thread and row group: RG x (count:3 | offset sum:3)
   __shared__ uint32_t pk1[NGRP][256];            // RG x 4-bit masks of the entries inside the bracket
-  __shared__ uint8_t pk2[NGRP][256][RG];         // candidates of the row in earlier threads of the quarter
+  __shared__ uint8_t pk2[NGRP][256][PG];         // candidates of the row in earlier threads of the quarter
   __shared__ float pval[CAPT][256];              // private lists of candidates, in stream order: value ...
   __shared__ uint8_t pmeta[CAPT][256];           // ... and (row in block) * 4 + element
   __shared__ uint32_t rbase[ROWS_BLK][4];        // first list position of each (row, quarter)
@@ -93,7 +86,7 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
     __syncthreads();
     {
       const int rl = tid >> 2, qd = tid & 3;
-      const int itr = rl / RG, rr = rl % RG, sh0 = 6 * rr, sh1 = 4 * rr;
+      const int itr = rl / PG, rr = rl % PG, sh0 = 6 * rr, sh1 = 4 * rr;
       uint32_t cnt = 0, els = 0, wsum = 0, nc = 0;
       if (rl < nrows) {
         // (lanes with the same row group and quarter read the same word; the others are 64 or
@@ -152,7 +145,7 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
 #pragma unroll
       for (int k = 0; k < CAPT; ++k) {
         const int rl = k < kp ? mt[k] >> 2 : 0;
-        pos[k] = rbase[rl][qd] + pk2[rl / RG][tid][rl % RG];
+        pos[k] = rbase[rl][qd] + pk2[rl / PG][tid][rl % PG];
       }
       int prev = -1;
       uint32_t run = 0;
@@ -171,18 +164,18 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
     } else {
       // a dense cluster: the wavefront re-reads its rows (coalesced, two row groups = 8 rows per
       // round trip) and walks its masks
-      for (int it0 = 0; it0 * RG < nrows; it0 += 2) {
-        float x4[2 * RG][4];
+      for (int it0 = 0; it0 * PG < nrows; it0 += 2) {
+        float x4[2 * PG][4];
 #pragma unroll
-        for (int q = 0; q < 2 * RG; ++q) {
-          const int rl = min(it0 * RG + q, nrows - 1);
+        for (int q = 0; q < 2 * PG; ++q) {
+          const int rl = min(it0 * PG + q, nrows - 1);
           const float* rp = s + (int64_t)(rb0 + rl) * pb.ld + n0;
 #pragma unroll
           for (int el = 0; el < 4; ++el) x4[q][el] = n0 + el < pb.P ? rp[el] : 0.f;
         }
 #pragma unroll
-        for (int q = 0; q < 2 * RG; ++q) {
-          const int itr = it0 + q / RG, rr = q % RG, rl = it0 * RG + q;
+        for (int q = 0; q < 2 * PG; ++q) {
+          const int itr = it0 + q / PG, rr = q % PG, rl = it0 * PG + q;
           if (rl >= nrows) break;
           const uint32_t mk = (pk1[itr][tid] >> (4 * rr)) & 15u;
           const int row = g * pb.W + rb0 + rl;
@@ -242,7 +235,9 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
       for (int el = 0; el < 4; ++el) xc[r][el] = xs[r][el];
     }
     if (i0 + RG < pb.W) fetch(i0 + RG);
-    uint32_t w0 = 0, w1 = 0;
+    uint32_t w0[RG / PG], w1[RG / PG];
+#pragma unroll
+    for (int q = 0; q < RG / PG; ++q) { w0[q] = 0; w1[q] = 0; }
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
       const int i = i0 + r;
@@ -262,12 +257,15 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
           cm |= 1u << el;
         }
       }
-      w0 |= (cnt | (els << 3)) << (6 * r);
-      w1 |= cm << (4 * r);
+      w0[r / PG] |= (cnt | (els << 3)) << (6 * (r % PG));
+      w1[r / PG] |= cm << (4 * (r % PG));
     }
     if (scan) {
-      pk0[(i0 - rb0) / RG][tid] = w0;
-      pk1[(i0 - rb0) / RG][tid] = w1;
+#pragma unroll
+      for (int q = 0; q < RG / PG; ++q) {
+        pk0[(i0 - rb0) / PG + q][tid] = w0[q];
+        pk1[(i0 - rb0) / PG + q][tid] = w1[q];
+      }
       if (i0 + RG - rb0 >= ROWS_BLK || i0 + RG >= pb.W) {      // block-uniform
         turn_around(rb0, min(i0 + RG, pb.W) - rb0);
         rb0 = i0 + RG;
