@@ -177,8 +177,12 @@ __device__ __forceinline__ void wait_vm() {
 // are multiplied (10 of 16 for D = 128).  Y^T = T V^T runs on the MFMA with T split into bf16
 // high and low parts that stay in registers for the whole kernel; row block rb needs the k-steps
 // from 2 rb on, so a wavefront takes the row blocks pr and D/32 - 1 - pr of one head: D/16 + 2
-// k-steps whatever pr.  The value tiles arrive through a 3-deep asynchronous LDS ring and are
+// k-steps whatever pr.  The value tiles arrive through a 4-deep asynchronous LDS ring and are
 // the B operand shared by all wavefronts; the partial dots of a head's wavefronts meet in LDS.
+// A tile has a matrix half-step (the MFMAs) and a vector half-step (row dots), and wavefronts
+// 4..7 run one half-step behind wavefronts 0..3 as in k_score_pipe; a tile is read in both
+// halves, i.e. until E_2t+3 by the late wavefronts, and the copy of tile t+2 goes to the slot
+// of tile t-2.  The two wavefronts of a head are in the same half.
 // grid (key chunks, ceil(G/HPW), Hkv), 512 threads; HPW = 4 heads per workgroup (8 for D = 64).
 template <int D>
 __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __restrict__ v,
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
   constexpr int NW = 8, KS = D / 16, CB = D / 32, WPH = CB / 2, HPW = NW / WPH;
   using Ring = TileRing<D, 0>;
   constexpr int NG = Ring::NI / NW;                 // copies per wavefront and tile
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs[3][TN * D];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[4][TN * D];
   __shared__ float part[2][HPW][WPH][TN];
   const int g = blockIdx.z;
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
@@ -201,7 +205,7 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
   const int t0 = blockIdx.x * tiles_per_wg;
   const int t1 = min(NT, t0 + tiles_per_wg);
   if (t0 >= t1) return;
-  auto issue_tile = [&](int t) { Ring::template issue<NW>(vg, pitch, min(t, t1 - 1) * TN, pb.L, Vs[t % 3], wv, l); };
+  auto issue_tile = [&](int t) { Ring::template issue<NW>(vg, pitch, min(t, t1 - 1) * TN, pb.L, Vs[t & 3], wv, l); };
   issue_tile(t0);
   issue_tile(t0 + 1);
 
@@ -230,12 +234,30 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
 #pragma unroll
     for (int a = 0; a < N1; ++a) load_frag(RB1, 2 * RB1 + a, ahi1[a], alo1[a]);
 
+    // vv of one tile of this wavefront's head: the partial dots of the head's wavefronts meet here
+    auto head_sum = [&](int t) {
+      if (PR == 0) {
+        const int n = t * TN + l;
+        if (n < pb.P && hloc < pb.G) {
+          float sum = 0.f;
+#pragma unroll
+          for (int m2 = 0; m2 < WPH; ++m2) sum += part[(t - t0) & 1][hw][m2][l];
+          vv[(int64_t)h * ldv + n] = sum;
+        }
+      }
+    };
+
     wait_vm<NG>();           // own share of tile t0 (compiler-issued loads above are older or waited for)
-    wg_barrier();
+    wg_barrier();            // E_2t0
+    const bool late = wv >= NW / 2;
+    if (late) wg_barrier();
     for (int t = t0; t < t1; ++t) {
       const int buf = (t - t0) & 1;
-      issue_tile(t + 2);     // into the slot of tile t-1, which every wavefront left before the last barrier
-      const uint16_t* vt = Vs[t % 3];
+      // ---- matrix half-step (raised priority: see k_score_pipe) ----
+      __builtin_amdgcn_s_setprio(2);
+      issue_tile(t + 2);     // into the slot of tile t-2
+      if (t > t0) head_sum(t - 1);
+      const uint16_t* vt = Vs[t & 3];
       f32x16 y0[2], y1[2];
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
@@ -259,6 +281,10 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
           y1[1] = MFMA(alo1[ks - 2 * RB1], b1, y1[1]);
         }
       }
+      wait_vm<NG>();         // own share of tile t+1 (only the copy of tile t+2 is younger)
+      wg_barrier();
+      __builtin_amdgcn_s_setprio(0);
+      // ---- vector half-step ----
       // row dot with v_n: register j of a block is Gram row 32 rb + 8 (j/4) + 4 hf + j%4
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
@@ -279,20 +305,10 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
         const float acc = xhalf_sum(acc0 + acc1);
         if (hf == 0) part[buf][hw][PR][32 * nb + rr] = acc;
       }
-      wait_vm<NG>();         // own share of tile t+1 (only the copy of tile t+2 is younger)
       wg_barrier();
-      if (threadIdx.x < HPW * TN) {
-        const int hh = threadIdx.x / TN, key = threadIdx.x % TN;
-        const int n = t * TN + key;
-        const int hl2 = blockIdx.y * HPW + hh;
-        if (n < pb.P && hl2 < pb.G) {
-          float sum = 0.f;
-#pragma unroll
-          for (int m2 = 0; m2 < WPH; ++m2) sum += part[buf][hh][m2][key];
-          vv[(int64_t)(g * pb.G + hl2) * ldv + n] = sum;
-        }
-      }
     }
+    head_sum(t1 - 1);
+    if (!late) wg_barrier();
     wait_vm<0>();            // no copy may land in LDS after the workgroup has gone
   };
   if constexpr (WPH == 1) {
