@@ -147,14 +147,21 @@ def main():
     torch.cuda.synchronize()
     # Layers are independent: with --streams N > 1 they are spread round-robin over N streams
     # (each with its own outputs and scratch) so that the short latency-bound kernels of one layer
-    # overlap the long ones of another.
+    # overlap the long ones of another.  The headline figure uses one stream unless asked.
     n_str = max(1, args.streams)
-    bufs = [rk.alloc_layer_buffers(p, dt, dev) for _ in range(n_str)]
-    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(n_str - 1)]
+    n_alt = 2 if n_str == 1 else n_str           # also measured, reported under "overlap"
+    bufs = [rk.alloc_layer_buffers(p, dt, dev) for _ in range(max(n_str, n_alt))]
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(max(n_str, n_alt) - 1)]
 
-    def step():
+    def step(ns=n_str):
+        if ns > 1:                                  # the side streams start after the work queued so far
+            for st in streams[1:ns]:
+                st.wait_stream(streams[0])
         for j, (q, k, v, gram) in enumerate(layers):
-            rk.evict_layer(p, q, k, v, gram, bufs[j % n_str], stream=streams[j % n_str])
+            rk.evict_layer(p, q, k, v, gram, bufs[j % ns], stream=streams[j % ns])
+        if ns > 1:
+            for st in streams[1:ns]:
+                streams[0].wait_stream(st)
 
     for _ in range(args.warmup):
         step()
@@ -206,6 +213,19 @@ def main():
                 "unit": unit, "frac": s["achieved"] / s["peak"], "traffic": measured_traffic(w.name, dom),
                 "avg_ms": s["ms"] / s["launches"]}
 
+    # The same steps with the layers spread over two streams (no kernel is bracketed).
+    overlap = None
+    if n_str == 1 and w.n_layers > 1:
+        rk.restkv_timing_enable(False)
+        step(n_alt)
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(args.steps):
+            step(n_alt)
+        torch.cuda.synchronize()
+        ms_alt = (time.perf_counter() - t3) * 1e3 / args.steps
+        overlap = {"streams": n_alt, "ms_per_step": ms_alt, "value": tokens / (ms_alt * 1e-3)}
+
     # Stage breakdown: the same steps once more, untimed, with every kernel bracketed.
     per = {}
     ms_all_events = None
@@ -237,6 +257,7 @@ def main():
                    "window": w.window, "budget": w.budget, "layer_tokens_per_s": w.n_layers * w.seq_len / (ms_per_step * 1e-3)},
         "roofline": roof,
         "cpu_baseline": cpu,
+        "overlap": overlap,
         "ms_per_step_all_kernels_bracketed": ms_all_events,
         "stages": {n: {"ms_per_layer": round(s["ms"], 5), "launches_per_layer": s["launches"], "bound": s["bound"],
                        "frac": (s["achieved"] / s["peak"]) if s["work"] else None} for n, s in per.items()},
