@@ -107,6 +107,7 @@ def main():
     ap.add_argument("--workload", default="drift_128k")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="skip the extra two-stream measurement")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with events in the timed region")
     args = ap.parse_args()
@@ -215,7 +216,7 @@ def main():
 
     # The same steps with the layers spread over two streams (no kernel is bracketed).
     overlap = None
-    if n_str == 1 and w.n_layers > 1:
+    if n_str == 1 and w.n_layers > 1 and not args.no_overlap:
         rk.restkv_timing_enable(False)
         step(n_alt)
         torch.cuda.synchronize()

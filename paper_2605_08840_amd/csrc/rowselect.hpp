@@ -98,57 +98,89 @@ constexpr int SEL_NS = 4096;     // samples / candidate capacity of the brackete
 
 // Block-wide counting on keys held in registers (NPT per thread; empty slots hold key 0, which
 // no pivot >= 1 counts).  One barrier per call; `it` alternates the two reduction buffers.
-struct CountSmem { uint32_t red[2][2][SEL_NW]; };
+struct CountSmem { uint32_t red[2][3][SEL_NW]; };
+
+// counts of keys >= piv[0..NP) (NP <= 6): per-lane counts on the vector ALU, two 16-bit counts per
+// register through the wave reduction (NPT * 64 < 65536), one LDS word per pair and wavefront
+template <int NPT, int NP>
+__device__ __forceinline__ void block_count_geN(const uint32_t (&k)[NPT], const uint32_t (&piv)[NP],
+                                                CountSmem& cs, int& it, uint32_t (&cnt)[NP]) {
+  static_assert(NP >= 1 && NP <= 6, "three packed registers");
+  constexpr int NR = (NP + 1) / 2;
+  uint32_t c[NP];
+#pragma unroll
+  for (int q = 0; q < NP; ++q) c[q] = 0;
+#pragma unroll
+  for (int j = 0; j < NPT; ++j)
+#pragma unroll
+    for (int q = 0; q < NP; ++q) c[q] += k[j] >= piv[q] ? 1u : 0u;
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6, p = it & 1;
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const uint32_t packed = wave_sum(c[2 * r] | ((2 * r + 1 < NP ? c[2 * r + 1] : 0u) << 16));
+    if ((threadIdx.x & 63) == 0) cs.red[p][r][w] = packed;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < NP; ++q) cnt[q] = 0;
+  for (int j = 0; j < nw; ++j)
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      const uint32_t x = cs.red[p][r][j];
+      cnt[2 * r] += x & 0xFFFFu;
+      if (2 * r + 1 < NP) cnt[2 * r + 1] += x >> 16;
+    }
+  ++it;
+}
 
 template <int NPT>
 __device__ __forceinline__ void block_count_ge2(const uint32_t (&k)[NPT], uint32_t va, uint32_t vb,
                                                 CountSmem& cs, int& it, uint32_t& ca, uint32_t& cb) {
-  uint32_t a = 0, b = 0;            // per-lane counts (vector ALU), reduced across the wave below
-#pragma unroll
-  for (int j = 0; j < NPT; ++j) {
-    a += k[j] >= va ? 1u : 0u;
-    b += k[j] >= vb ? 1u : 0u;
-  }
-  const uint32_t ab = wave_sum(a | (b << 16));   // NPT * 64 < 65536: both counts in one register
-  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6, p = it & 1;
-  if ((threadIdx.x & 63) == 0) cs.red[p][0][w] = ab;
-  __syncthreads();
-  a = 0; b = 0;
-  for (int j = 0; j < nw; ++j) { const uint32_t x = cs.red[p][0][j]; a += x & 0xFFFFu; b += x >> 16; }
-  ca = a; cb = b;
-  ++it;
+  const uint32_t piv[2] = {va, vb};
+  uint32_t cnt[2];
+  block_count_geN<NPT, 2>(k, piv, cs, it, cnt);
+  ca = cnt[0]; cb = cnt[1];
 }
 
-template <int NPT>
-__device__ __forceinline__ uint32_t block_count_ge(const uint32_t (&k)[NPT], uint32_t v, CountSmem& cs,
-                                                   int& it) {
-  uint32_t a = 0;
-#pragma unroll
-  for (int j = 0; j < NPT; ++j) a += k[j] >= v ? 1u : 0u;
-  a = wave_sum(a);
-  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6, p = it & 1;
-  if ((threadIdx.x & 63) == 0) cs.red[p][0][w] = a;
-  __syncthreads();
-  a = 0;
-  for (int j = 0; j < nw; ++j) a += cs.red[p][0][j];
-  ++it;
+// One bisection step on `nb` (1 or 2) bits starting at `bit`: a becomes the largest of
+// a | (x << (bit - nb + 1)), x in [0, 2^nb), whose count is >= kk, given the counts of x = 1..3.
+__device__ __forceinline__ uint32_t bisect_pick(uint32_t a, int sh, uint32_t kk, uint32_t c1, uint32_t c2,
+                                                uint32_t c3) {
+  if (c3 >= kk) return a | (3u << sh);
+  if (c2 >= kk) return a | (2u << sh);
+  if (c1 >= kk) return a | (1u << sh);
   return a;
 }
 
-// k-th largest key of the block (largest t with count(key >= t) >= k), bit by bit.
+// k-th largest key of the block (largest t with count(key >= t) >= k).  Bits above `top_bit` are
+// known (`prefix`, e.g. the common leading bits of a bracket that holds every key); the others
+// are resolved two per barrier (three pivots at a time).
 template <int NPT>
-__device__ inline uint32_t block_kth(const uint32_t (&k)[NPT], uint32_t kk, CountSmem& cs, int& it) {
-  uint32_t a = 0;
-  for (int bit = 31; bit >= 0; --bit) {
-    const uint32_t pa = a | (1u << bit);
-    if (block_count_ge<NPT>(k, pa, cs, it) >= kk) a = pa;
+__device__ inline uint32_t block_kth(const uint32_t (&k)[NPT], uint32_t kk, CountSmem& cs, int& it,
+                                     int top_bit = 31, uint32_t prefix = 0u) {
+  uint32_t a = prefix;
+  int bit = top_bit;
+  if ((bit & 1) == 0) {                 // odd number of bits: one single-bit step first
+    const uint32_t piv[1] = {a | (1u << bit)};
+    uint32_t c[1];
+    block_count_geN<NPT, 1>(k, piv, cs, it, c);
+    if (c[0] >= kk) a = piv[0];
+    --bit;
+  }
+  for (; bit >= 1; bit -= 2) {
+    const int sh = bit - 1;
+    const uint32_t piv[3] = {a | (1u << sh), a | (2u << sh), a | (3u << sh)};
+    uint32_t c[3];
+    block_count_geN<NPT, 3>(k, piv, cs, it, c);
+    a = bisect_pick(a, sh, kk, c[0], c[1], c[2]);
   }
   return a;
 }
 
 // Largest values ta, tb with count(key >= ta) >= ka and count(key >= tb) >= kb, i.e. the
-// ka-th and kb-th largest keys of the block (0 if fewer keys than that), bit by bit.
-// With low_bit > 0 only the bits above it are resolved (ta, tb are then lower bounds with the
+// ka-th and kb-th largest keys of the block (0 if fewer keys than that), bit by bit (with many
+// keys per thread the counting, not the barrier, is what a step costs).
+// With low_bit > 0 only the bits from it up are resolved (ta, tb are then lower bounds with the
 // unresolved bits zero).
 template <int NPT>
 __device__ inline void block_kth2(const uint32_t (&k)[NPT], uint32_t ka, uint32_t kb, CountSmem& cs,
@@ -162,6 +194,14 @@ __device__ inline void block_kth2(const uint32_t (&k)[NPT], uint32_t ka, uint32_
     if (cb >= kb) b = pb;
   }
   ta = a; tb = b;
+}
+
+// Highest bit in which two keys differ (-1 if equal) and their common bits above it: every key
+// between them shares that prefix.
+__device__ __forceinline__ void common_prefix(uint32_t klo, uint32_t khi, int& top_bit, uint32_t& prefix) {
+  const uint32_t x = klo ^ khi;
+  top_bit = x ? 31 - __builtin_clz(x) : -1;
+  prefix = top_bit >= 31 ? 0u : (khi & ~((2u << max(top_bit, 0)) - 1u)) | (top_bit < 0 ? khi : 0u);
 }
 
 // Sample ranks that bracket the k-th largest of a population of n from a sample of ns
@@ -188,11 +228,12 @@ __device__ inline int block_sample_regs(const float* __restrict__ row, int n, ui
     return n;
   }
   const int nch = cap / RUN;
+  const double step = (double)(n - RUN) / (double)(nch - 1);     // no integer division per sample
 #pragma unroll
   for (int j = 0; j < NPT; ++j) {
     const int x = threadIdx.x + j * blockDim.x;
     const int c = x / RUN, e = x % RUN;
-    const int start = (int)(((long long)c * (n - RUN)) / (nch - 1));
+    const int start = min((int)((double)c * step), n - RUN);
     k[j] = float_key(row[start + e]);
   }
   return cap;

@@ -108,8 +108,13 @@ __global__ __launch_bounds__(256) void k_sel_finish(Prob pb, SelPtrs w) {
     ck[j] = x < nc ? float_key(w.cand_val[(int64_t)g * SCAP + x]) : 0u;
     ci[j] = x < nc ? (uint32_t)w.cand_idx[(int64_t)g * SCAP + x] : 0u;
   }
-  int it = 0;
-  const uint32_t t = block_kth<NPT>(ck, need, cs, it);
+  int it = 0, top_bit;
+  uint32_t prefix;
+  {                                     // every candidate lies inside the bracket: its leading bits are known
+    const float2 th = w.thr[g];
+    common_prefix(float_key(th.x), float_key(th.y), top_bit, prefix);
+  }
+  const uint32_t t = block_kth<NPT>(ck, need, cs, it, top_bit, prefix);
   uint32_t cge, cgt;
   block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);
   const uint32_t k_eq = need - cgt;

@@ -289,6 +289,7 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __r
                                                     const uint32_t* __restrict__ ncand,
                                                     const float* __restrict__ cand_val,
                                                     const int* __restrict__ cand_idx,
+                                                    const float2* __restrict__ thr,
                                                     unsigned long long* __restrict__ rowsum) {
   constexpr int NPT = CAND_CAP / 256;
   __shared__ CountSmem cs;
@@ -314,9 +315,13 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __r
     ck[j] = x < nc ? float_key(cand_val[o]) : 0u;
     ci[j] = x < nc ? (uint32_t)cand_idx[o] : 0u;
   }
-  int it = 0;
-  uint32_t cge, cgt;
-  const uint32_t t = block_kth<NPT>(ck, need, cs, it);
+  int it = 0, top_bit;
+  uint32_t prefix, cge, cgt;
+  {                                              // every candidate lies inside the bracket: its leading bits are known
+    const float2 th = thr[r];
+    common_prefix(float_key(th.x), float_key(th.y), top_bit, prefix);
+  }
+  const uint32_t t = block_kth<NPT>(ck, need, cs, it, top_bit, prefix);
   block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);
   const uint32_t k_eq = need - cgt;              // ties at t to take, lowest positions first
   uint32_t pos_cut = 0xFFFFFFFFu;                // take tied entries with position <= pos_cut
@@ -435,7 +440,7 @@ int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, in
             thr, cnt_hi, sum_hi, ncand, cand_val, cand_idx, vec);
   if (pb.adaptive) {
     RK_LAUNCH(ST_ROWTOPK, st, k_row_finish, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, cnt_hi, sum_hi,
-              ncand, cand_val, cand_idx, rowsum);
+              ncand, cand_val, cand_idx, thr, rowsum);
     RK_LAUNCH(ST_ROWTOPK, st, k_row_fallback, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
   }
   RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, e, rowsum, fin,
