@@ -108,6 +108,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="skip the extra two-stream measurement")
+    ap.add_argument("--no-fold", action="store_true", help="skip the extra measurement with all layers as one call")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with events in the timed region")
     args = ap.parse_args()
@@ -134,17 +135,27 @@ def main():
     dt = workloads.torch_dtype(w)
 
     # ---- resident inputs: every layer's q, k, v and Gram matrices -----------------------------
+    # One tensor per kind, layers stacked along the head dimension; a layer is a slice of it.
+    Lyr, Hq, Hkv, d = w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim
+    Q = torch.empty((Lyr * Hq, w.window, d), dtype=dt, device=dev)
+    K = torch.empty((Lyr * Hkv, w.seq_len, d), dtype=dt, device=dev)
+    V = torch.empty((Lyr * Hkv, w.seq_len, d), dtype=dt, device=dev)
+    GR = torch.empty((Lyr * Hq, d, d), dtype=torch.float32, device=dev)
     layers = []
     wo0 = None
-    for l in range(w.n_layers):
+    for l in range(Lyr):
         q, k, v = workloads.make_qkv(w, l, dev)
+        Q[l * Hq:(l + 1) * Hq].copy_(q)
+        K[l * Hkv:(l + 1) * Hkv].copy_(k)
+        V[l * Hkv:(l + 1) * Hkv].copy_(v)
+        del q, k, v
         wo = workloads.make_wo(w, l, dev)
-        gram = torch.empty((w.n_q_heads, w.head_dim, w.head_dim), dtype=torch.float32, device=dev)
-        rk.restkv_prepare_wo(p, wo, gram)
+        rk.restkv_prepare_wo(p, wo, GR[l * Hq:(l + 1) * Hq])
         if l == 0:
             wo0 = wo.cpu()
         del wo
-        layers.append((q, k, v, gram))
+        layers.append((Q[l * Hq:(l + 1) * Hq], K[l * Hkv:(l + 1) * Hkv], V[l * Hkv:(l + 1) * Hkv],
+                       GR[l * Hq:(l + 1) * Hq]))
     torch.cuda.synchronize()
     # Layers are independent: with --streams N > 1 they are spread round-robin over N streams
     # (each with its own outputs and scratch) so that the short latency-bound kernels of one layer
@@ -227,6 +238,46 @@ def main():
         ms_alt = (time.perf_counter() - t3) * 1e3 / args.steps
         overlap = {"streams": n_alt, "ms_per_step": ms_alt, "value": tokens / (ms_alt * 1e-3)}
 
+    # The same work as ONE call per stage: the layers folded into the head dimension.
+    folded = None
+    if not args.no_fold and w.n_layers > 1:
+        pF = rk.make_params(n_q_heads=Lyr * Hq, n_kv_heads=Lyr * Hkv, head_dim=d, seq_len=w.seq_len,
+                            window=w.window, budget=w.budget, dtype=w.dtype, ema_alpha=w.alpha,
+                            base_window=w.base_window, beta=w.beta)
+        bufF = rk.alloc_layer_buffers(pF, dt, dev)
+        rk.restkv_timing_enable(False)
+
+        def timed(fn):
+            fn()
+            torch.cuda.synchronize()
+            t4 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t4) * 1e3 / args.steps
+
+        def hybrid():          # score layer by layer, smoothing / selection / compaction folded
+            for l, (q, k, v, gram) in enumerate(layers):
+                rk.restkv_score(p, q, k, v, gram, bufF.score[l * Hkv:(l + 1) * Hkv], bufs[0].workspace)
+            rk.restkv_smooth(pF, bufF.score, bufF.ema, bufF.final, bufF.aws_info, bufF.aws_d, bufF.workspace)
+            rk.restkv_select(pF, bufF.final, bufF.idx, bufF.workspace)
+            rk.restkv_compact(pF, K, V, bufF.idx, bufF.k_out, bufF.v_out)
+
+        ms_h = timed(hybrid)
+        idx_h = bufF.idx.clone()
+        ms_f = timed(lambda: rk.evict_layer(pF, Q, K, V, GR, bufF))
+        rk.evict_layer(p, *layers[-1], bufs[0])
+        torch.cuda.synchronize()
+        folded = {"ms_per_step": ms_f, "value": tokens / (ms_f * 1e-3),
+                  "hybrid_ms_per_step": ms_h, "hybrid_value": tokens / (ms_h * 1e-3),
+                  "last_layer_idx_equal": bool(torch.equal(bufF.idx[(Lyr - 1) * Hkv:], bufs[0].idx)),
+                  "hybrid_idx_equal": bool(torch.equal(idx_h, bufF.idx))}
+        rk.restkv_timing_enable(True)
+        rk.evict_layer(pF, Q, K, V, GR, bufF)
+        torch.cuda.synchronize()
+        folded["stages_ms_per_layer"] = {n: round(ms / Lyr, 5) for n, (ms, c) in rk.restkv_timing_read().items() if c}
+        del bufF
+
     # Stage breakdown: the same steps once more, untimed, with every kernel bracketed.
     per = {}
     ms_all_events = None
@@ -259,6 +310,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "overlap": overlap,
+        "folded": folded,
         "ms_per_step_all_kernels_bracketed": ms_all_events,
         "stages": {n: {"ms_per_layer": round(s["ms"], 5), "launches_per_layer": s["launches"], "bound": s["bound"],
                        "frac": (s["achieved"] / s["peak"]) if s["work"] else None} for n, s in per.items()},

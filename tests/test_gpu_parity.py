@@ -137,6 +137,8 @@ def _smooth_select_inputs(seed, Hkv, W, P, kind):
     ("drifting", 16, 20000, 512, 5, 100.0, 0.3),
     ("drifting", 6, 4000, 5000, 21, 37.0, 1.0),     # budget above the prefix length
     ("lognormal", 1, 900, 50, 5, 2000.0, 0.3),      # single query: no adaptive window
+    ("drifting", 40, 20001, 700, 5, 100.0, 0.3),    # two row blocks (32 + 8), dense candidate runs, odd row length
+    ("lognormal", 70, 6000, 400, 5, 500.0, 0.2),    # three row blocks (32 + 32 + 6)
 ])
 def test_smooth_select_compact_stage_exact(rk, oracle_mod, kind, W, P, B, k, beta, alpha):
     """Same FP32 scores into both sides: index sums, W_s, gamma and the selection are exact."""
@@ -314,3 +316,32 @@ def test_gqa8_128k_full_size_one_head(rk, oracle_mod):
 def test_lowrank_32k_budgets(rk, oracle_mod, budget):
     """BASELINE config 3 (rank-16 key/query structure, L 32768, W 64) at its three budgets."""
     _full_size_head_check(rk, oracle_mod, workloads.WORKLOADS["lowrank_32k"], layer=9, g=budget % 7, budget=budget)
+@pytest.mark.gpu
+def test_layers_folded_into_heads(rk, oracle_mod):
+    """A batch (here: three layers) folds into the head dimension: one call over 3*Hkv KV heads
+    gives, head by head, what the oracle gives for that layer, and selects what the per-layer
+    call selects."""
+    w = workloads.WORKLOADS["tiny"].with_(dtype="bf16", head_dim=128, seq_len=2500, window=24, budget=200)
+    Lyr, Hq, Hkv, d = 3, w.n_q_heads, w.n_kv_heads, w.head_dim
+    per = [(workloads.make_qkv(w, l, "cpu"), workloads.make_wo(w, l, "cpu")) for l in range(Lyr)]
+    wf = w.with_(n_q_heads=Lyr * Hq, n_kv_heads=Lyr * Hkv)
+    q = torch.cat([x[0][0] for x in per]); k = torch.cat([x[0][1] for x in per]); v = torch.cat([x[0][2] for x in per])
+    pf = params_for(rk, wf)
+    gram = torch.empty((Lyr * Hq, d, d), dtype=torch.float32, device="cuda")
+    for l in range(Lyr):
+        rk.restkv_prepare_wo(params_for(rk, w), per[l][1].cuda(), gram[l * Hq:(l + 1) * Hq])
+    buf = rk.alloc_layer_buffers(pf, q.dtype, "cuda")
+    rk.evict_layer(pf, q.cuda(), k.cuda(), v.cuda(), gram, buf)
+    torch.cuda.synchronize()
+    P = w.prefix
+    for l in range(Lyr):
+        (ql, kl, vl), wol = per[l]
+        one = run_gpu_layer(rk, w, ql, kl, vl, wol)
+        ref = oracle_score(oracle_mod, w, ql, kl, vl, wol)
+        for g in range(Hkv):
+            Ig, tol = ref[g]
+            assert_score_close(buf.score[l * Hkv + g, :, :P].cpu().numpy(), Ig, tol, f"folded layer {l} head {g}")
+        np.testing.assert_array_equal(buf.aws_info[l * Hkv:(l + 1) * Hkv].cpu().numpy(), one["aws_info"])
+        np.testing.assert_array_equal(buf.idx[l * Hkv:(l + 1) * Hkv].cpu().numpy(), one["idx"])
+
+
