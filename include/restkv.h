@@ -131,6 +131,22 @@ int restkv_smooth(const restkv_params* p, const float* score, float* ema, float*
                   restkv_stream_t stream);
 
 /*
+ * restkv_score followed by restkv_smooth as ONE call, with the same outputs (score
+ * included).  Where the shape allows it (bf16 inputs on the matrix-core path, G padded
+ * to a power of two in {4, 8}, G * W <= 256, adaptive window on, P >= 32768) the score
+ * pass itself accumulates the EMA (as the weighted sum that the recursion of Sec. 3.3
+ * unrolls to) and the per-query top-B statistics of the adaptive window, from brackets
+ * that a short pass over 8192 sampled keys provides, so that the raw score is written
+ * once and not read again; otherwise the two calls run one after the other.  A query
+ * whose bracket fails is redone exactly from `score`.  Workspace as reported by
+ * restkv_workspace_bytes (it covers this call).
+ */
+int restkv_score_smooth(const restkv_params* p, const void* q, const void* k, const void* v,
+                        const float* gram, float* score, float* ema, float* final_score,
+                        int32_t* aws_info, double* aws_d, void* workspace, size_t workspace_bytes,
+                        restkv_stream_t stream);
+
+/*
  * Per-head selection (Sec. 3.3, Eq. topk): the B - W prefix tokens with the
  * largest final[g, 0..P) (equal values: lower index wins), written in ascending
  * position order and followed by the window tokens P .. L-1.

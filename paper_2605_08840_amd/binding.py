@@ -57,6 +57,7 @@ def lib() -> ctypes.CDLL:
         L.restkv_prepare_wo.argtypes = [P, vp, i64, vp, vp]
         L.restkv_score.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
         L.restkv_smooth.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.restkv_score_smooth.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.restkv_select.argtypes = [P, vp, vp, vp, sz, vp]
         L.restkv_compact.argtypes = [P, vp, vp, vp, vp, vp, vp]
         L.restkv_strerror.restype = ctypes.c_char_p
@@ -66,7 +67,7 @@ def lib() -> ctypes.CDLL:
         L.restkv_stage_name.restype = ctypes.c_char_p
         L.restkv_stage_name.argtypes = [ctypes.c_int]
         for f in ("restkv_timing_enable", "restkv_timing_read", "restkv_prepare_wo", "restkv_score", "restkv_smooth", "restkv_select",
-                  "restkv_compact", "restkv_version"):
+                  "restkv_compact", "restkv_version", "restkv_score_smooth"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -136,6 +137,13 @@ def restkv_smooth(p, score, ema, final, aws_info, aws_d, workspace, stream=None)
                              _ptr(aws_d), wp, wn, _stream(stream)), "restkv_smooth")
 
 
+def restkv_score_smooth(p, q, k, v, gram, score, ema, final, aws_info, aws_d, workspace, stream=None):
+    wp, wn = _ws(workspace)
+    _chk(lib().restkv_score_smooth(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(gram), _ptr(score),
+                                   _ptr(ema), _ptr(final), _ptr(aws_info), _ptr(aws_d), wp, wn,
+                                   _stream(stream)), "restkv_score_smooth")
+
+
 def restkv_select(p, final, idx, workspace, stream=None):
     wp, wn = _ws(workspace)
     _chk(lib().restkv_select(ctypes.byref(p), _ptr(final), _ptr(idx), wp, wn, _stream(stream)),
@@ -203,9 +211,14 @@ def alloc_layer_buffers(p: RestkvParams, dtype: torch.dtype, device="cuda") -> L
         workspace=alloc_workspace(p, device))
 
 
-def evict_layer(p: RestkvParams, q, k, v, gram, buf: LayerBuffers, stream=None):
-    """The four calls of one layer, back to back on one stream (no host synchronisation)."""
-    restkv_score(p, q, k, v, gram, buf.score, buf.workspace, stream)
-    restkv_smooth(p, buf.score, buf.ema, buf.final, buf.aws_info, buf.aws_d, buf.workspace, stream)
+def evict_layer(p: RestkvParams, q, k, v, gram, buf: LayerBuffers, stream=None, fused=False):
+    """The calls of one layer, back to back on one stream (no host synchronisation); with
+    fused=True the score and the smoothing run as the one fused call."""
+    if fused:
+        restkv_score_smooth(p, q, k, v, gram, buf.score, buf.ema, buf.final, buf.aws_info, buf.aws_d,
+                            buf.workspace, stream)
+    else:
+        restkv_score(p, q, k, v, gram, buf.score, buf.workspace, stream)
+        restkv_smooth(p, buf.score, buf.ema, buf.final, buf.aws_info, buf.aws_d, buf.workspace, stream)
     restkv_select(p, buf.final, buf.idx, buf.workspace, stream)
     restkv_compact(p, k, v, buf.idx, buf.k_out, buf.v_out, stream)

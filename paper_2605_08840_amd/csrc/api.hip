@@ -92,6 +92,26 @@ SmoothWs smooth_ws(const Prob& pb) {
   return w;
 }
 
+FuseWs fuse_ws(const Prob& pb) {
+  FuseWs w;
+  w.ns = 8192;
+  w.nchunks = pb.G <= 32 ? score_pass_chunks(pb) : 1;
+  // a row's candidates (at most 4096 are usable) spread over the chunks unevenly: 1024 per
+  // chunk, more when there are only a few chunks
+  int caps = 1024;
+  while (caps < 4096 && caps * w.nchunks < 16384) caps *= 2;
+  w.caps = caps;
+  const size_t rows = (size_t)pb.Hkv * pb.W;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  w.smp = take(rows * w.ns * 4);
+  w.scnt = take(rows * w.nchunks * 4);
+  w.sval = take(rows * w.nchunks * w.caps * 4);
+  w.sidx = take(rows * w.nchunks * w.caps * 4);
+  w.bytes = off;
+  return w;
+}
+
 static bool g_force_fp32 = false;   // see restkv_debug_force_fp32
 
 static int check_ws(const void* ws, size_t have, size_t need) {
@@ -111,6 +131,9 @@ size_t restkv_workspace_bytes(const restkv_params* p) {
   size_t n = score_ws(pb).bytes;
   if (smooth_ws(pb).bytes > n) n = smooth_ws(pb).bytes;
   if (select_ws_bytes(pb) > n) n = select_ws_bytes(pb);
+  // the fused call keeps the score scratch, the smoothing scratch and its own side by side
+  const size_t f = align_up(score_ws(pb).bytes) + align_up(smooth_ws(pb).bytes) + fuse_ws(pb).bytes;
+  if (f > n) n = f;
   return n;
 }
 
@@ -150,6 +173,42 @@ int restkv_smooth(const restkv_params* p, const float* score, float* ema, float*
   if (rc) return rc;
   return launch_smooth(pb, score, ema, final_score, aws_info, aws_d, (char*)workspace, lay,
                        (hipStream_t)stream);
+}
+
+int restkv_score_smooth(const restkv_params* p, const void* q, const void* k, const void* v,
+                        const float* gram, float* score, float* ema, float* final_score,
+                        int32_t* aws_info, double* aws_d, void* workspace, size_t workspace_bytes,
+                        restkv_stream_t stream) {
+  Prob pb;
+  int rc = resolve(p, &pb);
+  if (rc) return rc;
+  if (!q || !k || !v || !score || !final_score) return RESTKV_EINVAL;
+  const ScoreWs ls = score_ws(pb);
+  const SmoothWs lm = smooth_ws(pb);
+  hipStream_t st = (hipStream_t)stream;
+  if (g_force_fp32 || !fused_eligible(pb, q, k, v)) {
+    // same result from the two separate calls (they use the workspace one after the other)
+    rc = restkv_score(p, q, k, v, gram, score, workspace, workspace_bytes, stream);
+    if (rc) return rc;
+    return restkv_smooth(p, score, ema, final_score, aws_info, aws_d, workspace, workspace_bytes, stream);
+  }
+  const FuseWs lf = fuse_ws(pb);
+  const size_t o_sm = align_up(ls.bytes), o_fu = o_sm + align_up(lm.bytes);
+  rc = check_ws(workspace, workspace_bytes, o_fu + lf.bytes);
+  if (rc) return rc;
+  char* ws = (char*)workspace;
+  char* wm = ws + o_sm;
+  char* wf = ws + o_fu;
+  FusedPtrs fp;
+  fp.smp = (float*)(wf + lf.smp); fp.ns = lf.ns;
+  fp.thr = (float2*)(wm + lm.thr); fp.cnt_hi = (uint32_t*)(wm + lm.cnt_hi);
+  fp.sum_hi = (unsigned long long*)(wm + lm.sum_hi);
+  fp.scnt = (uint32_t*)(wf + lf.scnt); fp.sval = (float*)(wf + lf.sval); fp.sidx = (int*)(wf + lf.sidx);
+  fp.caps = lf.caps;
+  fp.ema = ema ? ema : (float*)(wm + lm.ema);
+  rc = launch_score_fused(pb, q, k, v, gram, score, ws, ls, fp, st);
+  if (rc) return rc;
+  return launch_smooth_fused_tail(pb, score, fp.ema, final_score, aws_info, aws_d, wm, lm, fp, lf.nchunks, st);
 }
 
 int restkv_select(const restkv_params* p, const float* final_score, int32_t* idx, void* workspace,

@@ -42,8 +42,19 @@ struct SmoothWs {
   size_t cand_val, cand_idx;      // [Hkv*W, 4096] f32 / i32 candidates inside the bracket
   size_t bytes;
 };
+// extra scratch of the fused score + smoothing call (after the two layouts above)
+struct FuseWs {
+  int ns;                // sampled prefix keys per row (multiple of 64)
+  int nchunks;           // key chunks = workgroups along the keys of the score pass
+  int caps;              // capacity of one (row, chunk) candidate slice
+  size_t smp;            // [Hkv*W, ns] f32 scores of the sampled keys
+  size_t scnt;           // [Hkv*W, nchunks] u32 slice fill counts
+  size_t sval, sidx;     // [Hkv*W, nchunks, caps] f32 / i32 candidate slices
+  size_t bytes;
+};
 ScoreWs score_ws(const Prob& pb);
 SmoothWs smooth_ws(const Prob& pb);
+FuseWs fuse_ws(const Prob& pb);
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
@@ -57,6 +68,23 @@ int launch_score_mfma(const Prob& pb, const void* q, const void* k, const void* 
                       float* score, char* ws, const ScoreWs& lay, hipStream_t st);
 int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, int32_t* aws_info,
                   double* aws_d, char* ws, const SmoothWs& lay, hipStream_t st);
+// Fused score + smoothing (matrix-core path only).  fused_eligible() says whether the shape
+// qualifies; score_pass_chunks() is the number of key chunks the score pass will use.
+struct FusedPtrs {
+  float* smp; int ns;
+  float2* thr; uint32_t* cnt_hi; unsigned long long* sum_hi;
+  uint32_t* scnt; float* sval; int* sidx; int caps;
+  float* ema;
+};
+bool fused_eligible(const Prob& pb, const void* q, const void* k, const void* v);
+int score_pass_chunks(const Prob& pb);
+int launch_score_fused(const Prob& pb, const void* q, const void* k, const void* v, const float* gram,
+                       float* score, char* ws, const ScoreWs& lay, const FusedPtrs& fp, hipStream_t st);
+int launch_bracket_samples(const Prob& pb, const float* smp, int ns, float2* thr, uint32_t* cnt_hi,
+                           unsigned long long* sum_hi, hipStream_t st);
+int launch_smooth_fused_tail(const Prob& pb, const float* score, const float* ema, float* fin,
+                             int32_t* aws_info, double* aws_d, char* ws, const SmoothWs& lay,
+                             const FusedPtrs& fp, int nchunks, hipStream_t st);
 size_t select_ws_bytes(const Prob& pb);
 int launch_select(const Prob& pb, const float* fin, int32_t* idx, char* ws, hipStream_t st);
 int launch_compact(const Prob& pb, const void* k, const void* v, const int32_t* idx, void* k_out,

@@ -148,12 +148,18 @@ struct TileRing {
   template <int NW>
   __device__ static __forceinline__ void issue(const uint16_t* base, uint32_t pitch, int kb, int L,
                                                uint16_t* lds_tile, int wv, int lane) {
+    issue_rows<NW>(base, pitch, [&](int r) { return min(kb + r, L - 1); }, lds_tile, wv, lane);
+  }
+  // the same with an arbitrary matrix row for every tile row r (row_of(r) must be a valid row)
+  template <int NW, typename F>
+  __device__ static __forceinline__ void issue_rows(const uint16_t* base, uint32_t pitch, F row_of,
+                                                    uint16_t* lds_tile, int wv, int lane) {
     static_assert(NI % NW == 0, "tile instructions must divide over the wavefronts");
 #pragma unroll
     for (int j = 0; j < NI / NW; ++j) {
       const int blk = wv * (NI / NW) + j;
       const int r = blk * RPI + lane / CH, cs = lane % CH;
-      const uint32_t voff = (uint32_t)min(kb + r, L - 1) * pitch + (uint32_t)(swz(r, cs) * 16);
+      const uint32_t voff = (uint32_t)row_of(r) * pitch + (uint32_t)(swz(r, cs) * 16);
       dma_1k(base, voff, lds_tile + blk * 512);
     }
   }
@@ -606,12 +612,36 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
 // t-1 (last read before E_2t) and the vv slot of tile t-2 (last read before E_2t-1); each
 // wavefront waits for its own share of tile t+1 before its mid-step barrier, which for both
 // halves precedes E_2t+2, the first barrier after which tile t+1 is read.
-template <int D, int GP>
+// MODE 0: the pass as described.
+// MODE 1: sample pass.  The "tiles" are made of fa.ns sampled prefix keys (runs of 16 consecutive
+//         keys, evenly spread); their scores go to fa.smp [Hkv*W, fa.ns] instead of `score`.
+// MODE 2: fused pass (needs Gp >= 4, one row block).  Besides writing `score`, the vector
+//         half-step feeds the temporal and the spatial smoothing so that nothing has to read the
+//         raw score again:
+//   * EMA over the window queries as a weighted sum (weights of Sec. 3.3 unrolled): partial sums
+//     per wavefront meet in LDS, one wavefront writes fa.ema for the tile two steps later;
+//   * per (head, query) row and lane: count and position sum of the scores above the row's
+//     bracket fa.thr (registers, reduced once at the end into fa.cnt_hi / fa.sum_hi);
+//   * scores inside the bracket go, with their position, to a private LDS list of the lane;
+//     when a lane holds two or more the wavefront flushes its lists into the slices
+//     fa.sval / fa.sidx [row, key chunk = blockIdx.x, fa.caps] that only it writes (positions by
+//     wave ballots, no atomics); the slice fill counts go to fa.scnt at the end.
+struct FuseArgs {
+  float* smp; int ns; int ns_tiles; double step;
+  const float2* thr; uint32_t* cnt_hi; unsigned long long* sum_hi;
+  uint32_t* scnt; float* sval; int* sidx; int caps;
+  float* ema; float alpha;
+};
+constexpr int FUSE_CAPL = 10;        // private list entries per lane: a flush is due from 2 on, a tile adds at most 8
+
+template <int D, int GP, int MODE>
 __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __restrict__ q,
                                                     const uint16_t* __restrict__ k,
                                                     const uint16_t* __restrict__ v, ScorePtrs o, int ldv,
-                                                    float* __restrict__ score, int tiles_per_wg, int nwb) {
+                                                    float* __restrict__ score, int tiles_per_wg, int nwb,
+                                                    FuseArgs fa) {
   constexpr int NW = 8, KS = D / 16, LG = ilog2(GP), IW = 32 / GP;
+  static_assert(MODE != 2 || GP == 4 || GP == 8, "the fused pass keeps at most four rows per lane and needs LDS for its lists");
   constexpr int GV = GP < 4 ? 4 : GP;               // vv rows per ring slot (whole 1 KiB copies)
   constexpr int NVB = GV / 4;                       // 1 KiB copies per vv tile
   constexpr int ND = GP <= 4 ? GP : GP / 2;         // distinct heads among a lane's 16 registers
@@ -621,6 +651,10 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[3][TN * D];
   __shared__ __attribute__((aligned(1024))) float vvs[4][GV][TN];
   __shared__ __attribute__((aligned(16))) float rowc[NW][4][32];   // per local row: accumulator start values, champion key and score
+  constexpr int FL = MODE == 2 ? FUSE_CAPL : 1;
+  __shared__ float fval[FL][NW * 64];               // MODE 2: private lists, value ...
+  __shared__ uint32_t fpos[FL][NW * 64];            // ... and position | row slot << 30
+  __shared__ float epart[2][NW][TN];                // MODE 2: EMA partial sums of two tiles
 
   const int g = blockIdx.z;
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
@@ -628,10 +662,13 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   const uint16_t* kg = k + (int64_t)g * pb.kv_sh;
   const uint16_t* vg = v + (int64_t)g * pb.kv_sh;
 
-  const int NT = (pb.P + TN - 1) / TN;
+  const int NT = MODE == 1 ? fa.ns_tiles : (pb.P + TN - 1) / TN;
   const int t0 = blockIdx.x * tiles_per_wg;
   const int t1 = min(NT, t0 + tiles_per_wg);
   if (t0 >= t1) return;
+  // MODE 1: sample j (tile j / 64, row j % 64) is key start(j / 16) + j % 16, the starts evenly
+  // spread over the prefix and multiples of 4 (a vv copy moves 4 keys)
+  auto key_of = [&](int j) { return min((int)((double)(j >> 4) * fa.step) & ~3, pb.P - 16) + (j & 15); };
 
   // vv copy of this wavefront: block wv % NVB (duplicates write identical bytes)
   const int vb = wv % NVB;
@@ -641,9 +678,15 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   auto issue_tile = [&](int t) {
     const int tt = min(t, t1 - 1);                  // past the end: harmless repeat into a free slot
     const int kb = tt * TN;
-    Ring::template issue<NW>(kg, pitch, kb, pb.L, Ks[t % 3], wv, l);
-    Ring::template issue<NW>(vg, pitch, kb, pb.L, Vs[t % 3], wv, l);
-    dma_1k(vv_g, (vv_row + (uint32_t)min(kb + 4 * (l & 15), ldv - 4)) * 4u, &vvs[t & 3][4 * vb][0]);
+    if constexpr (MODE == 1) {
+      Ring::template issue_rows<NW>(kg, pitch, [&](int r) { return key_of(kb + r); }, Ks[t % 3], wv, l);
+      Ring::template issue_rows<NW>(vg, pitch, [&](int r) { return key_of(kb + r); }, Vs[t % 3], wv, l);
+      dma_1k(vv_g, (vv_row + (uint32_t)key_of(kb + 4 * (l & 15))) * 4u, &vvs[t & 3][4 * vb][0]);
+    } else {
+      Ring::template issue<NW>(kg, pitch, kb, pb.L, Ks[t % 3], wv, l);
+      Ring::template issue<NW>(vg, pitch, kb, pb.L, Vs[t % 3], wv, l);
+      dma_1k(vv_g, (vv_row + (uint32_t)min(kb + 4 * (l & 15), ldv - 4)) * 4u, &vvs[t & 3][4 * vb][0]);
+    }
   };
   issue_tile(t0);          // ring indices run on the absolute tile number
   issue_tile(t0 + 1);
@@ -699,6 +742,53 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   char* sbase = (char*)(score + (int64_t)g * pb.W * pb.ld);
   const uint32_t ld4 = (uint32_t)pb.ld * 4u;
   const uint32_t voff0 = (uint32_t)i0 * ld4 + (uint32_t)rr * 4u;   // 32-bit: checked on the host
+  // MODE 2: per output row of this lane the bracket, the EMA weight and the running statistics
+  float thi[NOUT], tlo[NOUT], wq[NOUT];
+  uint32_t hc[NOUT], hsm[NOUT], scount[NOUT];
+  int kp = 0;                                        // entries in this lane's private list
+  if constexpr (MODE == 2) {
+#pragma unroll
+    for (int a = 0; a < NOUT; ++a) {
+      const int i = i0 + out_pos0(a);
+      const bool ok = i < pb.W;
+      const float2 th = ok ? fa.thr[g * pb.W + i] : make_float2(INFINITY, INFINITY);
+      tlo[a] = th.x; thi[a] = th.y;
+      // e_W-1 = sum_i w_i I_i with w_0 = (1-alpha)^(W-1), w_i = alpha (1-alpha)^(W-1-i)
+      wq[a] = ok ? (i == 0 ? 1.f : fa.alpha) * powf(1.f - fa.alpha, (float)(pb.W - 1 - i)) : 0.f;
+      if (ok && pb.W == 1) wq[a] = 1.f;
+      hc[a] = 0; hsm[a] = 0; scount[a] = 0;
+    }
+  }
+  // MODE 2: lists -> slices.  Row slot a of lane half hf is one row; the 32 lanes of the half
+  // rank their entries with ballots, entry index by entry index.
+  auto flush = [&]() {
+    if constexpr (MODE == 2) {
+      const unsigned long long below = (1ull << l) - 1ull;
+      const unsigned long long half = hf ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull;
+#pragma unroll
+      for (int e = 0; e < FUSE_CAPL; ++e) {
+        const bool have = e < kp;
+        if (__ballot(have) == 0ull) break;
+        const uint32_t pe = fpos[e][threadIdx.x];
+        const float ve = fval[e][threadIdx.x];
+        const int slot = have ? (int)(pe >> 30) : -1;
+#pragma unroll
+        for (int a = 0; a < NOUT; ++a) {
+          const unsigned long long mk = __ballot(slot == a) & half;
+          if (slot == a) {
+            const uint32_t ps = scount[a] + (uint32_t)__popcll(mk & below);
+            if (ps < (uint32_t)fa.caps) {
+              const int64_t so = ((int64_t)(g * pb.W + i0 + out_pos0(a)) * gridDim.x + blockIdx.x) * fa.caps + ps;
+              fa.sval[so] = ve;
+              fa.sidx[so] = (int)(pe & 0x3FFFFFFFu);
+            }
+          }
+          scount[a] += (uint32_t)__popcll(mk);
+        }
+      }
+      kp = 0;
+    }
+  };
 
   wait_vm<NG>();           // own share of tile t0
   wg_barrier();            // E_2t0
@@ -711,6 +801,16 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
     // wavefront wins every arbitration and the younger one's copies and MFMAs start late).
     __builtin_amdgcn_s_setprio(2);
     issue_tile(t + 2);
+    if constexpr (MODE == 2) {
+      // tile t-2: every wavefront left its partial sum before the barrier just passed
+      if (wv == 0 && t - 2 >= t0) {
+        const int n = (t - 2) * TN + l;
+        float e = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) e += epart[t & 1][w2][l];
+        if (n < pb.P) fa.ema[(int64_t)g * pb.ld + n] = e;
+      }
+    }
     // ---- matrix half-step ----
     const uint16_t* kt = Ks[t % 3];
     const uint16_t* vt = Vs[t % 3];
@@ -777,7 +877,20 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
         for (int e = 0; e < 8; ++e) sacc[mb][b8 + e] = a[e] * x[e];
       }
     }
-    if (__ballot(nslane >= kb && nslane < kb + TN) != 0ull) {   // a champion of this wavefront is here
+    // key of this lane in the two 32-key blocks of the tile
+    int nk[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) nk[mb] = MODE == 1 ? key_of(kb + 32 * mb + rr) : kb + 32 * mb + rr;
+    bool champ_here = nslane >= kb && nslane < kb + TN;
+    if constexpr (MODE == 1) {             // the tile is four runs of 16 keys
+      champ_here = false;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int s0 = key_of(kb + 16 * r4);
+        champ_here = champ_here || (nslane >= s0 && nslane < s0 + 16);
+      }
+    }
+    if (__ballot(champ_here) != 0ull) {    // a champion of this wavefront is here
 #pragma unroll
       for (int j = 0; j < 16; ++j) {       // register j of lane half hf is local row 8 (j/4) + 4 hf + j%4
         const int m_ = 8 * (j >> 2) + 4 * hf + (j & 3);
@@ -785,7 +898,7 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
         const float is = rowc[wv][3][m_];
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-          if (kb + 32 * mb + rr == ns) sacc[mb][j] = is;
+          if (nk[mb] == ns) sacc[mb][j] = is;
       }
     }
     // ---- mean over the group (in-lane, one half swap from GP = 8 on), store ----
@@ -822,6 +935,14 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
         }
       }
     }
+    if constexpr (MODE == 1) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int a = 0; a < NOUT; ++a)
+          if (i0 + out_pos0(a) < pb.W)
+            fa.smp[(int64_t)(g * pb.W + i0 + out_pos0(a)) * fa.ns + kb + 32 * mb + rr] = outv[mb][a];
+    } else {
     const uint32_t toff = (uint32_t)kb * 4u;
     if (rows_full && kb + TN <= pb.P) {             // wave-uniform: no lane needs a guard
 #pragma unroll
@@ -837,10 +958,69 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
           if (i0 + out_pos0(a) < pb.W && kb + 32 * mb + rr < pb.P)
             *(float*)(sbase + (voff0 + toff + (uint32_t)(128 * mb) + (uint32_t)out_pos0(a) * ld4)) = outv[mb][a];
     }
+    }
+    if constexpr (MODE == 2) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        const bool inp = nk[mb] < pb.P;            // keys past the prefix count for nothing
+        // temporal smoothing: this lane's rows, the other lane half's, then LDS
+        float es = 0.f;
+#pragma unroll
+        for (int a = 0; a < NOUT; ++a) es = fmaf(wq[a], outv[mb][a], es);
+        if constexpr (HS != 0) es = xhalf_sum(es);
+        if (hf == 0) epart[t & 1][wv][32 * mb + rr] = inp ? es : 0.f;
+        // spatial statistics against the bracket of each row
+#pragma unroll
+        for (int a = 0; a < NOUT; ++a) {
+          const float x = outv[mb][a];
+          const bool hi = inp && x > thi[a];
+          hc[a] += hi ? 1u : 0u;
+          hsm[a] += hi ? (uint32_t)nk[mb] : 0u;
+          if (inp && x > tlo[a] && !hi) {          // inside the bracket: rare
+            fval[kp][threadIdx.x] = x;
+            fpos[kp][threadIdx.x] = (uint32_t)nk[mb] | ((uint32_t)a << 30);
+            ++kp;
+          }
+        }
+      }
+      if (__ballot(kp >= 2) != 0ull) flush();
+    }
     wg_barrier();
   }
   if (!late) wg_barrier();
   wait_vm<0>();            // no copy may land in LDS after the workgroup has gone
+  if constexpr (MODE == 2) {
+    // the last two tiles' EMA (every partial sum is in LDS after the barriers above)
+    if (wv == 0) {
+      for (int t = max(t0, t1 - 2); t < t1; ++t) {
+        const int n = t * TN + l;
+        float e = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) e += epart[t & 1][w2][l];
+        if (n < pb.P) fa.ema[(int64_t)g * pb.ld + n] = e;
+      }
+    }
+    flush();
+    // per row: statistics over the 32 lanes of the half (rotations inside the 16-lane rows, one
+    // row swap), slice fill count
+#pragma unroll
+    for (int a = 0; a < NOUT; ++a) {
+      uint32_t c = hc[a];
+      unsigned long long s = hsm[a];                // a lane's sum fits 32 bits (checked on the host)
+#pragma unroll
+      for (int sh = 1; sh < 32; sh <<= 1) {
+        c += (uint32_t)__shfl_xor((int)c, sh, 64);
+        s += ((unsigned long long)(uint32_t)__shfl_xor((int)(s >> 32), sh, 64) << 32) |
+             (unsigned long long)(uint32_t)__shfl_xor((int)(uint32_t)s, sh, 64);
+      }
+      const int i = i0 + out_pos0(a);
+      if (rr == 0 && i < pb.W) {
+        const int row = g * pb.W + i;
+        if (c) { atomicAdd(&fa.cnt_hi[row], c); atomicAdd(&fa.sum_hi[row], s); }
+        fa.scnt[(int64_t)row * gridDim.x + blockIdx.x] = scount[a];
+      }
+    }
+  }
 }
 
 // compute units of the current device (queried once)
@@ -857,9 +1037,25 @@ int n_cu() {
   return n;
 }
 
+// geometry of the score pass: padded group size, row blocks, tiles per workgroup, key chunks
+struct ScoreGeom { int gp, gy, tpp, chunks; };
+ScoreGeom score_geom(const Prob& pb) {
+  ScoreGeom s;
+  s.gp = 1;
+  while (s.gp < pb.G) s.gp <<= 1;
+  const int iw = 32 / s.gp;
+  const int nwr = (pb.W + iw - 1) / iw;            // wavefronts needed to cover the window
+  s.gy = (nwr + 7) / 8;                            // row blocks of 8 wavefronts
+  const int NT = (pb.P + TN - 1) / TN;
+  s.tpp = (int)(((int64_t)NT * s.gy * pb.Hkv + n_cu() - 1) / n_cu());
+  if (s.tpp < 1) s.tpp = 1;
+  s.chunks = (NT + s.tpp - 1) / s.tpp;
+  return s;
+}
+
 template <int D>
 int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const float* gram,
-             float* score, char* ws, const ScoreWs& lay, hipStream_t st) {
+             float* score, char* ws, const ScoreWs& lay, hipStream_t st, const FusedPtrs* fp) {
   const uint16_t* qq = (const uint16_t*)q;
   const uint16_t* kk = (const uint16_t*)k;
   const uint16_t* vp = (const uint16_t*)v;
@@ -895,21 +1091,47 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
               w.vv, lay.ldv);
   }
   // score pass: one resident workgroup per compute unit, each walking a run of tiles
-  const int NT = (pb.P + TN - 1) / TN;
-  const int gy2 = gy;
-  int tpp = (int)(((int64_t)NT * gy2 * pb.Hkv + n_cu() - 1) / n_cu());
-  if (tpp < 1) tpp = 1;
-  const dim3 g2((NT + tpp - 1) / tpp, gy2, pb.Hkv);
-#define RK_CASE(GPV)                                                                          \
-  case GPV:                                                                                   \
-    RK_LAUNCH(ST_SCORE, st, (k_score_pipe<D, GPV>), g2, dim3(512), 0, st, pb, qq, kk, vp, w,  \
-              lay.ldv, score, tpp, lay.nwb);                                                           \
-    break;
-  switch (gp) {
-    RK_CASE(1) RK_CASE(2) RK_CASE(4) RK_CASE(8) RK_CASE(16) RK_CASE(32)
+  const ScoreGeom sg = score_geom(pb);
+  const int tpp = sg.tpp;
+  const dim3 g2(sg.chunks, sg.gy, pb.Hkv);
+  FuseArgs fa = {};
+#define RK_SCORE(GPV, MODE, GRID, TPW)                                                              \
+  RK_LAUNCH(ST_SCORE, st, (k_score_pipe<D, GPV, MODE>), GRID, dim3(512), 0, st, pb, qq, kk, vp, w,  \
+            lay.ldv, score, TPW, lay.nwb, fa)
+  if (fp) {
+    // sample pass -> brackets -> fused pass
+    fa.smp = fp->smp; fa.ns = fp->ns; fa.ns_tiles = fp->ns / TN;
+    fa.step = (double)(pb.P - 16) / (double)(fp->ns / 16 - 1);
+    fa.thr = fp->thr; fa.cnt_hi = fp->cnt_hi; fa.sum_hi = fp->sum_hi;
+    fa.scnt = fp->scnt; fa.sval = fp->sval; fa.sidx = fp->sidx; fa.caps = fp->caps;
+    fa.ema = fp->ema; fa.alpha = pb.alpha;
+    int tps = (int)(((int64_t)fa.ns_tiles * pb.Hkv + n_cu() - 1) / n_cu());
+    if (tps < 1) tps = 1;
+    const dim3 gs((fa.ns_tiles + tps - 1) / tps, 1, pb.Hkv);
+    switch (sg.gp) {
+      case 4: RK_SCORE(4, 1, gs, tps); break;
+      case 8: RK_SCORE(8, 1, gs, tps); break;
+      default: return RESTKV_EUNSUPPORTED;
+    }
+    const int rc = launch_bracket_samples(pb, fp->smp, fp->ns, fp->thr, fp->cnt_hi, fp->sum_hi, st);
+    if (rc) return rc;
+    switch (sg.gp) {
+      case 4: RK_SCORE(4, 2, g2, tpp); break;
+      case 8: RK_SCORE(8, 2, g2, tpp); break;
+      default: return RESTKV_EUNSUPPORTED;
+    }
+    return hip_status();
+  }
+  switch (sg.gp) {
+    case 1: RK_SCORE(1, 0, g2, tpp); break;
+    case 2: RK_SCORE(2, 0, g2, tpp); break;
+    case 4: RK_SCORE(4, 0, g2, tpp); break;
+    case 8: RK_SCORE(8, 0, g2, tpp); break;
+    case 16: RK_SCORE(16, 0, g2, tpp); break;
+    case 32: RK_SCORE(32, 0, g2, tpp); break;
     default: break;
   }
-#undef RK_CASE
+#undef RK_SCORE
   return hip_status();
 }
 
@@ -929,8 +1151,26 @@ bool mfma_eligible(const Prob& pb, const void* q, const void* k, const void* v) 
 
 int launch_score_mfma(const Prob& pb, const void* q, const void* k, const void* v, const float* gram,
                       float* score, char* ws, const ScoreWs& lay, hipStream_t st) {
-  return pb.d == 64 ? run_mfma<64>(pb, q, k, v, gram, score, ws, lay, st)
-                    : run_mfma<128>(pb, q, k, v, gram, score, ws, lay, st);
+  return pb.d == 64 ? run_mfma<64>(pb, q, k, v, gram, score, ws, lay, st, nullptr)
+                    : run_mfma<128>(pb, q, k, v, gram, score, ws, lay, st, nullptr);
+}
+
+int launch_score_fused(const Prob& pb, const void* q, const void* k, const void* v, const float* gram,
+                       float* score, char* ws, const ScoreWs& lay, const FusedPtrs& fp, hipStream_t st) {
+  return pb.d == 64 ? run_mfma<64>(pb, q, k, v, gram, score, ws, lay, st, &fp)
+                    : run_mfma<128>(pb, q, k, v, gram, score, ws, lay, st, &fp);
+}
+
+int score_pass_chunks(const Prob& pb) { return score_geom(pb).chunks; }
+
+bool fused_eligible(const Prob& pb, const void* q, const void* k, const void* v) {
+  if (!mfma_eligible(pb, q, k, v) || !pb.adaptive) return false;
+  const ScoreGeom sg = score_geom(pb);
+  if (sg.gy != 1 || sg.gp < 4 || sg.gp > 8) return false;
+  if (pb.P < 32768 || pb.P >= (1 << 30)) return false;          // sampling pays off; 30-bit positions
+  if (2ull * (uint64_t)sg.tpp * (uint64_t)pb.P >= (1ull << 32)) return false;   // a lane's position sum
+  if (sg.chunks > 256) return false;                             // slice directory of the finishing kernel
+  return true;
 }
 
 }  // namespace restkv

@@ -150,7 +150,11 @@ __global__ __launch_bounds__(SEL_NT) void k_sel_fallback(Prob pb, const float* _
 
 __device__ __forceinline__ bool sel_pred(float x, int n, uint32_t tau, uint32_t pos_cut) {
   const uint32_t key = float_key(x);
-  return key > tau || (key == tau && (uint32_t)n <= pos_cut);
+  // one 64-bit comparison of (key, inverted position) against (tau, inverted cut); the form
+  // "key > tau || (key == tau && n <= pos_cut)" has been seen miscompiled by hipcc 7.2 at -O3
+  const unsigned long long a = ((unsigned long long)key << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)n);
+  const unsigned long long b = ((unsigned long long)tau << 32) | (unsigned long long)(0xFFFFFFFFu - pos_cut);
+  return a >= b;
 }
 
 // grid (chunks, Hkv), 256 threads; thread t owns the 16 consecutive positions 16 t .. 16 t + 15

@@ -41,6 +41,37 @@ __global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __
     thr[r] = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
 }
 
+// The same bracket from scores of sampled keys that the score pass left contiguously:
+// smp [Hkv*W, ns], ns a multiple of 256.  grid (W, Hkv), 256 threads.
+__global__ __launch_bounds__(256) void k_bracket_samples(Prob pb, const float* __restrict__ smp, int ns,
+                                                         float2* __restrict__ thr,
+                                                         uint32_t* __restrict__ cnt_hi,
+                                                         unsigned long long* __restrict__ sum_hi) {
+  constexpr int NPT = SMP_NS / 256;
+  __shared__ CountSmem cs;
+  const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
+  const int k = min(pb.B, pb.P);
+  if (threadIdx.x == 0) { cnt_hi[r] = 0; sum_hi[r] = 0ull; }
+  if (k >= pb.P) {
+    if (threadIdx.x == 0) thr[r] = make_float2(INFINITY, INFINITY);
+    return;
+  }
+  uint32_t keys[NPT];
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    const int x = threadIdx.x + j * 256;
+    keys[j] = x < ns ? float_key(smp[(int64_t)r * ns + x]) : 0u;
+  }
+  int r_hi, r_lo, it = 0;
+  bracket_ranks(pb.P, ns, k, r_hi, r_lo);
+  uint32_t thi, tlo;
+  block_kth2<NPT>(keys, (uint32_t)max(r_hi, 1), (uint32_t)min(r_lo, ns), cs, it, thi, tlo, 16);
+  const uint32_t khi = r_hi >= 1 ? (thi | 0xFFFFu) : 0xFFFFFFFFu;
+  const uint32_t klo = r_lo <= ns ? tlo : 0u;
+  if (threadIdx.x == 0)
+    thr[r] = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
+}
+
 // Fused single read of the raw score: EMA over the window queries (the recursion of Sec. 3.3:
 // first query as is, every later one enters with weight alpha) and, per (head, query) row,
 // the count / position sum of the entries above the bracket and the list of entries inside it.
@@ -279,6 +310,39 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
 
 constexpr unsigned long long ROW_PENDING = ~0ull;   // rowsum marker: the bracket missed this row
 
+// Exact threshold among the candidates of one row (keys ck, positions ci, NPT per thread, 256
+// threads; empty slots have key 0): `need` of them belong to the top-B, ties cut by position.
+// Returns this thread's share of the position sum of the taken candidates.
+template <int NPT>
+__device__ inline unsigned long long finish_candidates(const uint32_t (&ck)[NPT], const uint32_t (&ci)[NPT],
+                                                       uint32_t need, float2 th, CountSmem& cs) {
+  int it = 0, top_bit;
+  uint32_t prefix, cge, cgt;
+  common_prefix(float_key(th.x), float_key(th.y), top_bit, prefix);   // every candidate lies inside the bracket
+  const uint32_t t = block_kth<NPT>(ck, need, cs, it, top_bit, prefix);
+  block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);
+  const uint32_t k_eq = need - cgt;              // ties at t to take, lowest positions first
+  uint32_t pos_cut = 0xFFFFFFFFu;                // take tied entries with position <= pos_cut
+  if (cge - cgt > k_eq) {
+    // k_eq-th smallest position among the ties = k_eq-th largest inverted position
+    uint32_t inv[NPT];
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) inv[j] = ck[j] == t ? 0xFFFFFFFFu - ci[j] : 0u;
+    pos_cut = 0xFFFFFFFFu - block_kth<NPT>(inv, k_eq, cs, it);
+  }
+  // One 64-bit comparison per entry: (key, inverted position) >= (t, inverted cut).  (The form
+  // "key > t || (key == t && position <= cut)" is miscompiled by hipcc 7.2 at -O3: the addend of
+  // the tie case is dropped.)
+  const unsigned long long cut = ((unsigned long long)t << 32) | (unsigned long long)(0xFFFFFFFFu - pos_cut);
+  unsigned long long acc = 0;
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    const unsigned long long kj = ((unsigned long long)ck[j] << 32) | (unsigned long long)(0xFFFFFFFFu - ci[j]);
+    acc += kj >= cut ? (unsigned long long)ci[j] : 0ull;
+  }
+  return acc;
+}
+
 // Sum of the positions of the top-min(B,P) entries of one (head, query) row: the entries above
 // the bracket were summed by the fused pass; the threshold is found among the candidates by
 // bisection on their keys, equal values are taken in position order (a second bisection on the
@@ -315,27 +379,71 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __r
     ck[j] = x < nc ? float_key(cand_val[o]) : 0u;
     ci[j] = x < nc ? (uint32_t)cand_idx[o] : 0u;
   }
-  int it = 0, top_bit;
-  uint32_t prefix, cge, cgt;
-  {                                              // every candidate lies inside the bracket: its leading bits are known
-    const float2 th = thr[r];
-    common_prefix(float_key(th.x), float_key(th.y), top_bit, prefix);
-  }
-  const uint32_t t = block_kth<NPT>(ck, need, cs, it, top_bit, prefix);
-  block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);
-  const uint32_t k_eq = need - cgt;              // ties at t to take, lowest positions first
-  uint32_t pos_cut = 0xFFFFFFFFu;                // take tied entries with position <= pos_cut
-  if (cge - cgt > k_eq) {
-    // k_eq-th smallest position among the ties = k_eq-th largest inverted position
-    uint32_t inv[NPT];
+  unsigned long long acc = finish_candidates<NPT>(ck, ci, need, thr[r], cs);
 #pragma unroll
-    for (int j = 0; j < NPT; ++j) inv[j] = ck[j] == t ? 0xFFFFFFFFu - ci[j] : 0u;
-    pos_cut = 0xFFFFFFFFu - block_kth<NPT>(inv, k_eq, cs, it);
+  for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  if ((threadIdx.x & 63) == 0) isum[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) rowsum[r] = isum[0] + isum[1] + isum[2] + isum[3] + sum_hi[r];
+}
+
+// The finishing step when the candidates of a row sit in per-chunk slices
+// (sval / sidx [row, nchunks, caps], fill counts scnt [row, nchunks]; nchunks <= 256).
+// grid (W, Hkv), 256 threads.
+__global__ __launch_bounds__(256) void k_row_finish_slices(Prob pb, const uint32_t* __restrict__ cnt_hi,
+                                                           const unsigned long long* __restrict__ sum_hi,
+                                                           const uint32_t* __restrict__ scnt,
+                                                           const float* __restrict__ sval,
+                                                           const int* __restrict__ sidx, int nchunks, int caps,
+                                                           const float2* __restrict__ thr,
+                                                           unsigned long long* __restrict__ rowsum) {
+  constexpr int NPT = CAND_CAP / 256;
+  __shared__ CountSmem cs;
+  __shared__ unsigned long long isum[4];
+  __shared__ uint32_t pre[257];              // exclusive prefix of the slice fill counts
+  __shared__ uint32_t over;
+  const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
+  const int k = min(pb.B, pb.P);
+  if (k >= pb.P) {
+    if (threadIdx.x == 0) rowsum[r] = (unsigned long long)pb.P * (unsigned long long)(pb.P - 1) / 2ull;
+    return;
   }
-  unsigned long long acc = 0;
+  if (threadIdx.x == 0) {
+    uint32_t run = 0, ov = 0;
+    for (int c = 0; c < nchunks; ++c) {
+      const uint32_t n = scnt[(int64_t)r * nchunks + c];
+      pre[c] = run;
+      run += min(n, (uint32_t)caps);
+      ov |= n > (uint32_t)caps ? 1u : 0u;
+    }
+    pre[nchunks] = run;
+    over = ov;
+  }
+  __syncthreads();
+  const uint32_t ch = cnt_hi[r], nc = pre[nchunks];
+  const bool ok = !over && ch < (uint32_t)k && (uint32_t)k <= ch + nc && nc <= (uint32_t)CAND_CAP;
+  if (!ok) {
+    if (threadIdx.x == 0) rowsum[r] = ROW_PENDING;
+    return;
+  }
+  const uint32_t need = (uint32_t)k - ch;
+  uint32_t ck[NPT], ci[NPT];
 #pragma unroll
-  for (int j = 0; j < NPT; ++j)
-    if (ck[j] > t || (ck[j] == t && ci[j] <= pos_cut)) acc += (unsigned long long)ci[j];
+  for (int j = 0; j < NPT; ++j) {
+    const uint32_t x = threadIdx.x + j * 256;
+    ck[j] = 0u; ci[j] = 0u;
+    if (x < nc) {
+      int lo = 0, hi = nchunks - 1;           // last chunk whose prefix is <= x
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (pre[mid] <= x) lo = mid; else hi = mid - 1;
+      }
+      const int64_t o = ((int64_t)r * nchunks + lo) * caps + (x - pre[lo]);
+      ck[j] = float_key(sval[o]);
+      ci[j] = (uint32_t)sidx[o];
+    }
+  }
+  unsigned long long acc = finish_candidates<NPT>(ck, ci, need, thr[r], cs);
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 64);
   if ((threadIdx.x & 63) == 0) isum[threadIdx.x >> 6] = acc;
@@ -444,6 +552,26 @@ int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, in
     RK_LAUNCH(ST_ROWTOPK, st, k_row_fallback, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
   }
   RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, e, rowsum, fin,
+            aws_info, aws_d);
+  return hip_status();
+}
+
+int launch_bracket_samples(const Prob& pb, const float* smp, int ns, float2* thr, uint32_t* cnt_hi,
+                           unsigned long long* sum_hi, hipStream_t st) {
+  if (ns > SMP_NS) return RESTKV_EINVAL;
+  RK_LAUNCH(ST_ROWTOPK, st, k_bracket_samples, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, smp, ns, thr,
+            cnt_hi, sum_hi);
+  return hip_status();
+}
+
+int launch_smooth_fused_tail(const Prob& pb, const float* score, const float* ema, float* fin,
+                             int32_t* aws_info, double* aws_d, char* ws, const SmoothWs& lay,
+                             const FusedPtrs& fp, int nchunks, hipStream_t st) {
+  unsigned long long* rowsum = (unsigned long long*)(ws + lay.rowsum);
+  RK_LAUNCH(ST_ROWTOPK, st, k_row_finish_slices, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, fp.cnt_hi,
+            fp.sum_hi, fp.scnt, fp.sval, fp.sidx, nchunks, fp.caps, fp.thr, rowsum);
+  RK_LAUNCH(ST_ROWTOPK, st, k_row_fallback, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
+  RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, ema, rowsum, fin,
             aws_info, aws_d);
   return hip_status();
 }

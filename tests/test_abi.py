@@ -28,7 +28,7 @@ def test_exports_every_declared_symbol(rk):
     text = open(os.path.join(ROOT, "include", "restkv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(restkv_[a-z_]+)\s*\(", text)))
-    assert {"restkv_score", "restkv_smooth", "restkv_select", "restkv_compact", "restkv_prepare_wo",
+    assert {"restkv_score", "restkv_score_smooth", "restkv_smooth", "restkv_select", "restkv_compact", "restkv_prepare_wo",
             "restkv_workspace_bytes", "restkv_strerror", "restkv_version"} <= set(names)
     L = rk.lib()
     for n in names:
@@ -64,7 +64,9 @@ def test_error_codes_without_launch(rk):
     assert L.restkv_prepare_wo(ctypes.byref(p), None, 128, one, None) == -1
     # workspace: missing, too small, misaligned
     assert L.restkv_score(ctypes.byref(p), one, one, one, None, one, None, 0, None) == -3
-    assert L.restkv_score(ctypes.byref(p), one, one, one, None, one, one, ws_n - 1, None) == -3
+    assert L.restkv_score(ctypes.byref(p), one, one, one, None, one, one, 256, None) == -3
+    assert L.restkv_score_smooth(ctypes.byref(p), one, one, one, None, one, None, one, None, None, one, 256, None) == -3
+    assert L.restkv_score_smooth(ctypes.byref(p), one, one, one, None, None, None, one, None, None, one, ws_n, None) == -1
     assert L.restkv_score(ctypes.byref(p), one, one, one, None, one, ctypes.c_void_p(264), ws_n, None) == -3
     assert L.restkv_smooth(ctypes.byref(p), one, None, one, None, None, one, 8, None) == -3
     # unsupported / invalid blocks

@@ -280,6 +280,12 @@ def _full_size_head_check(rk, oracle_mod, w, layer, g, budget=None, rows_only=No
         assert_score_close(got[rows_only], Ig, tol, f"{w.name} head {g} rows {rows_only}")
         return
     assert_score_close(got, Ig, tol, f"{w.name} layer {layer} head {g}")
+    # the top-B statistics of the adaptive window are exact on the GPU's own raw scores, head by head
+    Bt = min(w.budget, P)
+    tk = torch.topk(buf.score[:, :, :P], Bt, dim=2).indices.double().sum(2)
+    hw = w.window // 2
+    want_d = torch.stack([tk[:, :hw].sum(1) / (Bt * hw), tk[:, hw:].sum(1) / (Bt * (w.window - hw))], dim=1)
+    assert torch.allclose(want_d, buf.aws_d, rtol=1e-12, atol=0.0), (want_d, buf.aws_d)
     sm = oracle_mod.smooth_head(Ig, w.alpha, w.beta, w.base_window, True, w.budget)
     dd = buf.aws_d[g].cpu().numpy()
     assert abs(dd[0] - sm["d_front"]) <= 2e-3 * P and abs(dd[1] - sm["d_rear"]) <= 2e-3 * P
@@ -316,6 +322,38 @@ def test_gqa8_128k_full_size_one_head(rk, oracle_mod):
 def test_lowrank_32k_budgets(rk, oracle_mod, budget):
     """BASELINE config 3 (rank-16 key/query structure, L 32768, W 64) at its three budgets."""
     _full_size_head_check(rk, oracle_mod, workloads.WORKLOADS["lowrank_32k"], layer=9, g=budget % 7, budget=budget)
+@pytest.mark.gpu
+@pytest.mark.parametrize("Hq,Hkv,W,L,B,structure", [
+    (8, 2, 64, 40000, 1500, "drift"),     # G = 4, 256 rows: the fused path, several key chunks per head
+    (16, 2, 30, 33000, 700, "plain"),     # G = 8, a row block that is not full
+    (6, 2, 40, 36000, 3000, "sinks"),     # G = 3 padded to 4, budget above the sample-based bracket
+])
+def test_fused_score_smooth_matches_separate_calls(rk, Hq, Hkv, W, L, B, structure):
+    """restkv_score_smooth against restkv_score + restkv_smooth on the same inputs: same raw score
+    bit for bit, EMA to rounding (weighted sum vs recursion), identical top-B statistics, window
+    and final score to rounding, identical selection unless two final scores are within rounding."""
+    w = workloads.WORKLOADS["drift_128k"].with_(n_layers=1, n_q_heads=Hq, n_kv_heads=Hkv, seq_len=L, window=W,
+                                               budget=B, structure=structure, d_model=512, beta=300.0)
+    q, k, v = workloads.make_qkv(w, 0, "cuda")
+    wo = workloads.make_wo(w, 0, "cuda")
+    p = params_for(rk, w)
+    gram = torch.empty((Hq, w.head_dim, w.head_dim), dtype=torch.float32, device="cuda")
+    rk.restkv_prepare_wo(p, wo, gram)
+    a = rk.alloc_layer_buffers(p, q.dtype, "cuda")
+    b = rk.alloc_layer_buffers(p, q.dtype, "cuda")
+    rk.evict_layer(p, q, k, v, gram, a)
+    rk.evict_layer(p, q, k, v, gram, b, fused=True)
+    torch.cuda.synchronize()
+    P = w.prefix
+    assert torch.equal(a.score[..., :P], b.score[..., :P])
+    np.testing.assert_allclose(b.ema[..., :P].cpu().numpy(), a.ema[..., :P].cpu().numpy(), rtol=2e-5, atol=1e-30)
+    assert torch.equal(a.aws_d, b.aws_d), (a.aws_d, b.aws_d)
+    assert torch.equal(a.aws_info, b.aws_info)
+    fa, fb = a.final[..., :P].cpu().numpy(), b.final[..., :P].cpu().numpy()
+    np.testing.assert_allclose(fb, fa, rtol=5e-5, atol=1e-30)
+    for g in range(Hkv):
+        check_selection(b.idx[g].cpu().numpy(), fa[g].astype(np.float64), W, B, 2e-4)
+
 @pytest.mark.gpu
 def test_layers_folded_into_heads(rk, oracle_mod):
     """A batch (here: three layers) folds into the head dimension: one call over 3*Hkv KV heads
