@@ -107,6 +107,7 @@ def main():
     ap.add_argument("--workload", default="drift_128k")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused", action="store_true", help="score and smoothing as the one fused call")
     ap.add_argument("--no-overlap", action="store_true", help="skip the extra two-stream measurement")
     ap.add_argument("--no-fold", action="store_true", help="skip the extra measurement with all layers as one call")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -170,7 +171,7 @@ def main():
             for st in streams[1:ns]:
                 st.wait_stream(streams[0])
         for j, (q, k, v, gram) in enumerate(layers):
-            rk.evict_layer(p, q, k, v, gram, bufs[j % ns], stream=streams[j % ns])
+            rk.evict_layer(p, q, k, v, gram, bufs[j % ns], stream=streams[j % ns], fused=args.fused)
         if ns > 1:
             for st in streams[1:ns]:
                 streams[0].wait_stream(st)

@@ -96,10 +96,9 @@ FuseWs fuse_ws(const Prob& pb) {
   FuseWs w;
   w.ns = 8192;
   w.nchunks = pb.G <= 32 ? score_pass_chunks(pb) : 1;
-  // a row's candidates (at most 4096 are usable) spread over the chunks unevenly: 1024 per
-  // chunk, more when there are only a few chunks
-  int caps = 1024;
-  while (caps < 4096 && caps * w.nchunks < 16384) caps *= 2;
+  // a row's candidates (at most 4096 are usable) cluster in a few chunks: room for half of them
+  // in every chunk, for all of them when there are only a few chunks
+  const int caps = w.nchunks < 8 ? 4096 : 2048;
   w.caps = caps;
   const size_t rows = (size_t)pb.Hkv * pb.W;
   size_t off = 0;

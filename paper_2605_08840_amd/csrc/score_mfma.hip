@@ -632,7 +632,7 @@ struct FuseArgs {
   uint32_t* scnt; float* sval; int* sidx; int caps;
   float* ema; float alpha;
 };
-constexpr int FUSE_CAPL = 10;        // private list entries per lane: a flush is due from 2 on, a tile adds at most 8
+constexpr int FUSE_CAPL = 512;       // candidate list entries per wavefront (a tile adds at most 512)
 
 template <int D, int GP, int MODE>
 __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __restrict__ q,
@@ -652,8 +652,10 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   __shared__ __attribute__((aligned(1024))) float vvs[4][GV][TN];
   __shared__ __attribute__((aligned(16))) float rowc[NW][4][32];   // per local row: accumulator start values, champion key and score
   constexpr int FL = MODE == 2 ? FUSE_CAPL : 1;
-  __shared__ float fval[FL][NW * 64];               // MODE 2: private lists, value ...
-  __shared__ uint32_t fpos[FL][NW * 64];            // ... and position | row slot << 30
+  __shared__ float fval[NW][FL];                    // MODE 2: candidate list of each wavefront, value ...
+  __shared__ uint32_t fpos[NW][FL];                 // ... and position | row slot << 29 | lane half << 31
+  __shared__ __attribute__((aligned(16))) uint32_t fcnt[NW][8];   // MODE 2: slice fill count of each wavefront's rows
+  __shared__ __attribute__((aligned(16))) float frow[NW][3][8];   // MODE 2: per row (slot + 4 half): bracket lo, hi, EMA weight
   __shared__ float epart[2][NW][TN];                // MODE 2: EMA partial sums of two tiles
 
   const int g = blockIdx.z;
@@ -743,50 +745,61 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   const uint32_t ld4 = (uint32_t)pb.ld * 4u;
   const uint32_t voff0 = (uint32_t)i0 * ld4 + (uint32_t)rr * 4u;   // 32-bit: checked on the host
   // MODE 2: per output row of this lane the bracket, the EMA weight and the running statistics
-  float thi[NOUT], tlo[NOUT], wq[NOUT];
-  uint32_t hc[NOUT], hsm[NOUT], scount[NOUT];
-  int kp = 0;                                        // entries in this lane's private list
+  uint32_t hc[NOUT], hsm[NOUT];
+  uint32_t wcount = 0;                               // entries in this wavefront's list (wave-uniform)
   if constexpr (MODE == 2) {
 #pragma unroll
-    for (int a = 0; a < NOUT; ++a) {
-      const int i = i0 + out_pos0(a);
-      const bool ok = i < pb.W;
+    for (int a = 0; a < NOUT; ++a) { hc[a] = 0; hsm[a] = 0; }
+    if (l < 8) {                                     // row l & 3 of lane half l >> 2
+      const int i = wb * IW + out_pos0(l & 3) + (l >> 2) * HS;
+      const bool ok = (l & 3) < NOUT && i < pb.W;
       const float2 th = ok ? fa.thr[g * pb.W + i] : make_float2(INFINITY, INFINITY);
-      tlo[a] = th.x; thi[a] = th.y;
+      frow[wv][0][l] = th.x;
+      frow[wv][1][l] = th.y;
       // e_W-1 = sum_i w_i I_i with w_0 = (1-alpha)^(W-1), w_i = alpha (1-alpha)^(W-1-i)
-      wq[a] = ok ? (i == 0 ? 1.f : fa.alpha) * powf(1.f - fa.alpha, (float)(pb.W - 1 - i)) : 0.f;
-      if (ok && pb.W == 1) wq[a] = 1.f;
-      hc[a] = 0; hsm[a] = 0; scount[a] = 0;
+      frow[wv][2][l] = ok ? (i == 0 ? 1.f : fa.alpha) * powf(1.f - fa.alpha, (float)(pb.W - 1 - i)) : 0.f;
+      fcnt[wv][l] = 0;
     }
   }
-  // MODE 2: lists -> slices.  Row slot a of lane half hf is one row; the 32 lanes of the half
-  // rank their entries with ballots, entry index by entry index.
+  const unsigned long long lanes_below = (1ull << l) - 1ull;
+  // MODE 2: list -> slices, 64 entries at a time; the entries of one row (slot a of lane half h,
+  // tag 2 h' + ... in the position word) are ranked with a ballot.  Only this wavefront touches
+  // its list, its counts and its rows' slices.
   auto flush = [&]() {
     if constexpr (MODE == 2) {
-      const unsigned long long below = (1ull << l) - 1ull;
-      const unsigned long long half = hf ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull;
+      uint32_t cn[8];                          // fill counts of the wavefront's 8 rows (wave-uniform)
+      {
+        const uint4 c0 = *(const uint4*)&fcnt[wv][0], c1 = *(const uint4*)&fcnt[wv][4];
+        cn[0] = c0.x; cn[1] = c0.y; cn[2] = c0.z; cn[3] = c0.w;
+        cn[4] = c1.x; cn[5] = c1.y; cn[6] = c1.z; cn[7] = c1.w;
+      }
+      const int caps = fa.caps;
+      float* const sval = fa.sval;
+      int* const sidx = fa.sidx;
+      for (uint32_t c0 = 0; c0 < wcount; c0 += 64) {
+        const bool have = c0 + (uint32_t)l < wcount;
+        const uint32_t pe = have ? fpos[wv][c0 + l] : 0u;
+        const float ve = have ? fval[wv][c0 + l] : 0.f;
+        const int tag = have ? (int)(pe >> 29) : -1;          // slot | half << 2
+        uint32_t ps = 0;
 #pragma unroll
-      for (int e = 0; e < FUSE_CAPL; ++e) {
-        const bool have = e < kp;
-        if (__ballot(have) == 0ull) break;
-        const uint32_t pe = fpos[e][threadIdx.x];
-        const float ve = fval[e][threadIdx.x];
-        const int slot = have ? (int)(pe >> 30) : -1;
-#pragma unroll
-        for (int a = 0; a < NOUT; ++a) {
-          const unsigned long long mk = __ballot(slot == a) & half;
-          if (slot == a) {
-            const uint32_t ps = scount[a] + (uint32_t)__popcll(mk & below);
-            if (ps < (uint32_t)fa.caps) {
-              const int64_t so = ((int64_t)(g * pb.W + i0 + out_pos0(a)) * gridDim.x + blockIdx.x) * fa.caps + ps;
-              fa.sval[so] = ve;
-              fa.sidx[so] = (int)(pe & 0x3FFFFFFFu);
-            }
-          }
-          scount[a] += (uint32_t)__popcll(mk);
+        for (int r8 = 0; r8 < 8; ++r8) {
+          const unsigned long long mk = __ballot(tag == r8);
+          if (tag == r8) ps = cn[r8] + (uint32_t)__popcll(mk & lanes_below);
+          cn[r8] += (uint32_t)__popcll(mk);
+        }
+        if (have && ps < (uint32_t)caps) {
+          const int i = wb * IW + 2 * (tag & 3) + (tag >> 2) * HS;     // out_pos0(a) = 2 a for Gp >= 4
+          const int64_t so = ((int64_t)(g * pb.W + i) * gridDim.x + blockIdx.x) * caps + ps;
+          sval[so] = ve;
+          sidx[so] = (int)(pe & 0x1FFFFFFFu);
         }
       }
-      kp = 0;
+      if (l == 0) {
+        *(uint4*)&fcnt[wv][0] = make_uint4(cn[0], cn[1], cn[2], cn[3]);
+        *(uint4*)&fcnt[wv][4] = make_uint4(cn[4], cn[5], cn[6], cn[7]);
+      }
+      wcount = 0;
     }
   };
 
@@ -960,6 +973,14 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
     }
     }
     if constexpr (MODE == 2) {
+      bool cin[2][NOUT];
+      float tlo[4], thi[4], wq[4];
+      {
+        const f32x4 x0 = *(const f32x4*)&frow[wv][0][4 * hf], x1 = *(const f32x4*)&frow[wv][1][4 * hf],
+                    x2 = *(const f32x4*)&frow[wv][2][4 * hf];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) { tlo[a] = x0[a]; thi[a] = x1[a]; wq[a] = x2[a]; }
+      }
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb) {
         const bool inp = nk[mb] < pb.P;            // keys past the prefix count for nothing
@@ -976,14 +997,43 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
           const bool hi = inp && x > thi[a];
           hc[a] += hi ? 1u : 0u;
           hsm[a] += hi ? (uint32_t)nk[mb] : 0u;
-          if (inp && x > tlo[a] && !hi) {          // inside the bracket: rare
-            fval[kp][threadIdx.x] = x;
-            fpos[kp][threadIdx.x] = (uint32_t)nk[mb] | ((uint32_t)a << 30);
-            ++kp;
-          }
+          cin[mb][a] = inp && x > tlo[a] && !hi;   // inside the bracket
         }
       }
-      if (__ballot(kp >= 2) != 0ull) flush();
+      // candidates of this tile: a prefix sum over the lanes' counts (rotations-free DPP shifts
+      // inside the 16-lane rows, the four row totals through scalar registers) gives every lane
+      // its place in the wavefront's list
+      uint32_t myc = 0;
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int a = 0; a < NOUT; ++a) myc += cin[mb][a] ? 1u : 0u;
+      if (__ballot(myc != 0u) != 0ull) {            // wave-uniform
+        uint32_t s = myc;
+#define RK_SHR(n) s += __builtin_amdgcn_update_dpp(0u, s, 0x110 + (n), 0xF, 0xF, true)
+        RK_SHR(1); RK_SHR(2); RK_SHR(4); RK_SHR(8);   // inclusive sums inside each row of 16 lanes
+#undef RK_SHR
+        const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)s, 15), r1 = (uint32_t)__builtin_amdgcn_readlane((int)s, 31),
+                       r2 = (uint32_t)__builtin_amdgcn_readlane((int)s, 47), r3 = (uint32_t)__builtin_amdgcn_readlane((int)s, 63);
+        const int lr = l >> 4;
+        const uint32_t before = lr == 0 ? 0u : (lr == 1 ? r0 : (lr == 2 ? r0 + r1 : r0 + r1 + r2));
+        const uint32_t tot = r0 + r1 + r2 + r3;
+        if (wcount + tot > (uint32_t)FUSE_CAPL) flush();   // (rare: the regular flushes below keep the list short)
+        uint32_t e = wcount + before + s - myc;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int a = 0; a < NOUT; ++a)
+            if (cin[mb][a]) {
+              fval[wv][e] = outv[mb][a];
+              fpos[wv][e] = (uint32_t)nk[mb] | ((uint32_t)a << 29) | ((uint32_t)hf << 31);
+              ++e;
+            }
+        wcount += tot;
+      }
+      // every wavefront empties its list at the same tiles, so that the workgroup pays for one
+      // flush, not for eight at different barriers
+      if (((t - t0) & 31) == 31 && wcount) flush();
     }
     wg_barrier();
   }
@@ -1017,7 +1067,7 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
       if (rr == 0 && i < pb.W) {
         const int row = g * pb.W + i;
         if (c) { atomicAdd(&fa.cnt_hi[row], c); atomicAdd(&fa.sum_hi[row], s); }
-        fa.scnt[(int64_t)row * gridDim.x + blockIdx.x] = scount[a];
+        fa.scnt[(int64_t)row * gridDim.x + blockIdx.x] = fcnt[wv][a + 4 * hf];
       }
     }
   }
@@ -1167,7 +1217,7 @@ bool fused_eligible(const Prob& pb, const void* q, const void* k, const void* v)
   if (!mfma_eligible(pb, q, k, v) || !pb.adaptive) return false;
   const ScoreGeom sg = score_geom(pb);
   if (sg.gy != 1 || sg.gp < 4 || sg.gp > 8) return false;
-  if (pb.P < 32768 || pb.P >= (1 << 30)) return false;          // sampling pays off; 30-bit positions
+  if (pb.P < 32768 || pb.P >= (1 << 29)) return false;          // sampling pays off; 29-bit positions
   if (2ull * (uint64_t)sg.tpp * (uint64_t)pb.P >= (1ull << 32)) return false;   // a lane's position sum
   if (sg.chunks > 256) return false;                             // slice directory of the finishing kernel
   return true;
