@@ -239,6 +239,24 @@ def main():
         ms_alt = (time.perf_counter() - t3) * 1e3 / args.steps
         overlap = {"streams": n_alt, "ms_per_step": ms_alt, "value": tokens / (ms_alt * 1e-3)}
 
+    # The same steps with restkv_score_smooth in place of restkv_score + restkv_smooth.
+    fused_call = None
+    if not args.fused and not args.no_overlap:
+        rk.restkv_timing_enable(False)
+
+        def step_fused():
+            for (q, k, v, gram) in layers:
+                rk.evict_layer(p, q, k, v, gram, bufs[0], fused=True)
+
+        step_fused()
+        torch.cuda.synchronize()
+        t5 = time.perf_counter()
+        for _ in range(args.steps):
+            step_fused()
+        torch.cuda.synchronize()
+        ms_fu = (time.perf_counter() - t5) * 1e3 / args.steps
+        fused_call = {"ms_per_step": ms_fu, "value": tokens / (ms_fu * 1e-3)}
+
     # The same work as ONE call per stage: the layers folded into the head dimension.
     folded = None
     if not args.no_fold and w.n_layers > 1:
@@ -311,6 +329,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "overlap": overlap,
+        "fused_call": fused_call,
         "folded": folded,
         "ms_per_step_all_kernels_bracketed": ms_all_events,
         "stages": {n: {"ms_per_layer": round(s["ms"], 5), "launches_per_layer": s["launches"], "bound": s["bound"],
