@@ -60,7 +60,7 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
                                                              float* __restrict__ rs_istar,
                                                              float* __restrict__ rs_u,
                                                              const T* __restrict__ q, uint16_t* __restrict__ op,
-                                                             int log2gp, int nwb) {
+                                                             int log2gp, int nwb, int ngrp) {
   constexpr int NWV = D / 64, SMAX = 64;     // wavefronts per row; capacity of the split dimension
   __shared__ __attribute__((aligned(16))) float Mh_s[D * D];   // the head's Gram matrix (unused when gram == NULL)
   __shared__ float zq[CMB_RQ][D], xq[CMB_RQ][D];
@@ -70,11 +70,7 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
   __shared__ float s_w[CMB_RQ][SMAX];
   const int h = blockIdx.y, g = h / pb.G;
   const int r = threadIdx.x / D, c = threadIdx.x % D;
-  const int i = blockIdx.x * CMB_RQ + r;
-  const bool live = i < pb.W;
-  const int row = h * pb.W + (live ? i : 0);
   const T* vg = v + (int64_t)g * pb.kv_sh;
-  const int64_t o = (int64_t)row * S;
   // The Gram matrix travels through registers while the splits are merged (written to LDS just
   // before the matrix-vector product): its latency hides behind the merge.
   constexpr int GQ = D * D / 4 / (CMB_RQ * D);     // float4 per thread
@@ -84,6 +80,13 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
 #pragma unroll
     for (int k = 0; k < GQ; ++k) gq[k] = Mh4[threadIdx.x + k * (CMB_RQ * D)];
   }
+  // A workgroup walks ngrp groups of CMB_RQ rows with the one staged Gram matrix.
+  for (int grp = 0; grp < ngrp; ++grp) {
+  const int i = (blockIdx.x * ngrp + grp) * CMB_RQ + r;
+  if ((blockIdx.x * ngrp + grp) * CMB_RQ >= pb.W) break;      // workgroup-uniform
+  const bool live = i < pb.W;
+  const int row = h * pb.W + (live ? i : 0);
+  const int64_t o = (int64_t)row * S;
   // Per-split scalars: thread c < S of the row's first wavefront owns split c (S <= 64).
   float pm = -INFINITY, pmx = 0.f, pref = 0.f, pl = 0.f;
   int pn = -1;
@@ -150,7 +153,7 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
   }
   zq[r][c] = z;
   xq[r][c] = x;
-  if (gram) {
+  if (gram && grp == 0) {
 #pragma unroll
     for (int k = 0; k < GQ; ++k) ((float4*)Mh_s)[threadIdx.x + k * (CMB_RQ * D)] = gq[k];
   }
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
   for (int sh = 32; sh >= 1; sh >>= 1) { s0 += __shfl_xor(s0, sh, 64); s1 += __shfl_xor(s1, sh, 64); }
   if ((c & 63) == 0) { red[r][c >> 6][0] = s0; red[r][c >> 6][1] = s1; }
   __syncthreads();
-  if (!live) return;
+  if (live) {
   float zz = 0.f, qx = 0.f;
 #pragma unroll
   for (int wv = 0; wv < NWV; ++wv) { zz += red[r][wv][0]; qx += red[r][wv][1]; }
@@ -205,10 +208,25 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
     rs_nstar[row] = nstar;
     rs_istar[row] = sqrtf(fmaxf(qx, 0.f)) / l;      // A* ||(z_rest - v*) W_O||,  A* = 1/l
   }
+  }
+  __syncthreads();                           // the next group reuses the LDS scalars and sums
+  }
 }
 
 // launch configuration of k_attn_combine
-inline dim3 combine_grid(const Prob& pb) { return dim3((pb.W + CMB_RQ - 1) / CMB_RQ, pb.Hq); }
+// groups of CMB_RQ rows per workgroup: one when that already gives plenty of workgroups, more
+// (fewer re-reads of the Gram matrix) when there are very many heads
+inline int combine_groups(const Prob& pb) {
+  const int64_t wgs = (int64_t)pb.Hq * ((pb.W + CMB_RQ - 1) / CMB_RQ);
+  int ngrp = (int)(wgs / 2048);
+  if (ngrp < 1) ngrp = 1;
+  const int all = (pb.W + CMB_RQ - 1) / CMB_RQ;
+  return ngrp < all ? ngrp : all;
+}
+inline dim3 combine_grid(const Prob& pb) {
+  const int per = CMB_RQ * combine_groups(pb);
+  return dim3((pb.W + per - 1) / per, pb.Hq);
+}
 template <int D>
 inline dim3 combine_block() { return dim3(CMB_RQ * D); }
 

@@ -1127,7 +1127,7 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
             log2iw, w);
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<bf16_t, D>), combine_grid(pb), combine_block<D>(), 0, st, pb,
             (const bf16_t*)v, S, gram, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
-            w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, (const bf16_t*)q, w.op, ilog2(gp), lay.nwb);
+            w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, (const bf16_t*)q, w.op, ilog2(gp), lay.nwb, combine_groups(pb));
   if (gram) {
     constexpr int HPW = D == 128 ? 4 : 8;
     const int NTv = (pb.P + TN - 1) / TN;

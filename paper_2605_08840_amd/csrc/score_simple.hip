@@ -290,7 +290,7 @@ int run(const Prob& pb, const void* q, const void* k, const void* v, const float
                      pb, qq, kk, vp, S, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z);
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<T, D>), combine_grid(pb), combine_block<D>(), 0, st, pb, vp, S, gram,
             w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m, w.rs_l, w.rs_zz, w.rs_nstar,
-            w.rs_istar, w.rs_u, (const T*)nullptr, (uint16_t*)nullptr, 0, 0);
+            w.rs_istar, w.rs_u, (const T*)nullptr, (uint16_t*)nullptr, 0, 0, combine_groups(pb));
   RK_LAUNCH(ST_VV, st, (k_vv<T, D>), dim3((pb.P + 63) / 64, pb.Hq), dim3(256), 0, st, pb, vp, gram, w.vv, lay.ldv);
   RK_LAUNCH(ST_SCORE, st, (k_score<T, D>), dim3((pb.P + TN - 1) / TN, pb.Hkv), dim3(256), 0, st, pb, qq,
                      kk, vp, w.rs_m, w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, w.vv, lay.ldv, score);

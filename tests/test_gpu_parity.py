@@ -355,6 +355,37 @@ def test_fused_score_smooth_matches_separate_calls(rk, Hq, Hkv, W, L, B, structu
         check_selection(b.idx[g].cpu().numpy(), fa[g].astype(np.float64), W, B, 2e-4)
 
 @pytest.mark.gpu
+def test_decode_reeviction_folded_layers(rk, oracle_mod):
+    """Decode-time re-eviction (App. B): a cache of B + M tokens goes back to B with the last M
+    queries as the window.  Four layers folded into the head dimension, every head against the
+    oracle (scores, window, selection on the GPU's own final scores, gather)."""
+    w = workloads.WORKLOADS["decode_reevict"]
+    Lyr, Hq, Hkv, d, P = 4, w.n_q_heads, w.n_kv_heads, w.head_dim, w.prefix
+    per = [(workloads.make_qkv(w, l, "cpu"), workloads.make_wo(w, l, "cpu")) for l in range(Lyr)]
+    wf = w.with_(n_q_heads=Lyr * Hq, n_kv_heads=Lyr * Hkv)
+    q = torch.cat([x[0][0] for x in per]); k = torch.cat([x[0][1] for x in per]); v = torch.cat([x[0][2] for x in per])
+    pf = params_for(rk, wf)
+    gram = torch.empty((Lyr * Hq, d, d), dtype=torch.float32, device="cuda")
+    for l in range(Lyr):
+        rk.restkv_prepare_wo(params_for(rk, w), per[l][1].cuda(), gram[l * Hq:(l + 1) * Hq])
+    buf = rk.alloc_layer_buffers(pf, q.dtype, "cuda")
+    rk.evict_layer(pf, q.cuda(), k.cuda(), v.cuda(), gram, buf)
+    torch.cuda.synchronize()
+    fin, idx = buf.final[:, :P].cpu().numpy(), buf.idx.cpu().numpy()
+    for l in (0, Lyr - 1):
+        (ql, kl, vl), wol = per[l]
+        ref = oracle_score(oracle_mod, w, ql, kl, vl, wol)
+        for g in range(Hkv):
+            Ig, tol = ref[g]
+            r = l * Hkv + g
+            assert_score_close(buf.score[r, :, :P].cpu().numpy(), Ig, tol, f"re-eviction layer {l} head {g}")
+            sm = oracle_mod.smooth_head(Ig, w.alpha, w.beta, w.base_window, True, w.budget)
+            assert tuple(buf.aws_info[r].cpu().numpy().tolist()) == (sm["w_s"], sm["gamma"])
+            np.testing.assert_allclose(fin[r], sm["final"], rtol=2 * RTOL, atol=1e-12)
+            np.testing.assert_array_equal(idx[r], oracle_mod.select(fin[r].astype(np.float64), w.window, w.budget))
+            np.testing.assert_array_equal(buf.k_out[r].float().cpu().numpy(), kl[g].float().numpy()[idx[r]])
+
+@pytest.mark.gpu
 def test_layers_folded_into_heads(rk, oracle_mod):
     """A batch (here: three layers) folds into the head dimension: one call over 3*Hkv KV heads
     gives, head by head, what the oracle gives for that layer, and selects what the per-layer

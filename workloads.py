@@ -59,6 +59,10 @@ WORKLOADS: Dict[str, Workload] = {
     "drift_128k": Workload("drift_128k", 32, 32, 8, 128, 131072, 64, 2048, "bf16", 4096, 0.3, 5, 2000.0, "drift", 0x5EED + 4),
     # 80 layers, 64 query heads over 8 KV heads
     "gqa8_128k": Workload("gqa8_128k", 80, 64, 8, 128, 131072, 64, 1024, "bf16", 8192, 0.3, 5, 2000.0, "plain", 0x5EED + 5),
+    # Decode-time re-eviction (App. B): a cache held at budget B = 2048 has grown by M = 64 generated
+    # tokens; their queries are the observation window and the cache goes back to B.  Not one of the
+    # five benchmark configurations: the small-L regime of the same path.
+    "decode_reevict": Workload("decode_reevict", 32, 32, 8, 128, 2048 + 64, 64, 2048, "bf16", 4096, 0.3, 5, 2000.0, "drift", 0x5EED + 6),
 }
 
 
