@@ -622,10 +622,11 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
 //     per wavefront meet in LDS, one wavefront writes fa.ema for the tile two steps later;
 //   * per (head, query) row and lane: count and position sum of the scores above the row's
 //     bracket fa.thr (registers, reduced once at the end into fa.cnt_hi / fa.sum_hi);
-//   * scores inside the bracket go, with their position, to a private LDS list of the lane;
-//     when a lane holds two or more the wavefront flushes its lists into the slices
-//     fa.sval / fa.sidx [row, key chunk = blockIdx.x, fa.caps] that only it writes (positions by
-//     wave ballots, no atomics); the slice fill counts go to fa.scnt at the end.
+//   * scores inside the bracket go, with their position and row, to a compact LDS list of the
+//     wavefront (places from a prefix sum over the lanes' counts); every 32 tiles, and when the
+//     list would overflow, the wavefront flushes it into the slices fa.sval / fa.sidx
+//     [row, key chunk = blockIdx.x, fa.caps] that only it writes (ranks by wave ballots, no
+//     atomics, deterministic); the slice fill counts go to fa.scnt at the end.
 struct FuseArgs {
   float* smp; int ns; int ns_tiles; double step;
   const float2* thr; uint32_t* cnt_hi; unsigned long long* sum_hi;
@@ -744,7 +745,8 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   char* sbase = (char*)(score + (int64_t)g * pb.W * pb.ld);
   const uint32_t ld4 = (uint32_t)pb.ld * 4u;
   const uint32_t voff0 = (uint32_t)i0 * ld4 + (uint32_t)rr * 4u;   // 32-bit: checked on the host
-  // MODE 2: per output row of this lane the bracket, the EMA weight and the running statistics
+  // MODE 2: running statistics of this lane's output rows; brackets and EMA weights of the
+  // wavefront's rows sit in LDS (frow)
   uint32_t hc[NOUT], hsm[NOUT];
   uint32_t wcount = 0;                               // entries in this wavefront's list (wave-uniform)
   if constexpr (MODE == 2) {
@@ -762,9 +764,9 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
     }
   }
   const unsigned long long lanes_below = (1ull << l) - 1ull;
-  // MODE 2: list -> slices, 64 entries at a time; the entries of one row (slot a of lane half h,
-  // tag 2 h' + ... in the position word) are ranked with a ballot.  Only this wavefront touches
-  // its list, its counts and its rows' slices.
+  // MODE 2: list -> slices, 64 entries at a time; the entries of one row (tag = slot + 4 * lane
+  // half in the top bits of the position word) are ranked with a ballot.  Only this wavefront
+  // touches its list, its counts and its rows' slices.
   auto flush = [&]() {
     if constexpr (MODE == 2) {
       uint32_t cn[8];                          // fill counts of the wavefront's 8 rows (wave-uniform)
