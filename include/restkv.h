@@ -159,6 +159,24 @@ int restkv_select(const restkv_params* p, const float* final_score, int32_t* idx
                   void* workspace, size_t workspace_bytes, restkv_stream_t stream);
 
 /*
+ * Non-uniform budgets (App. C of the paper pairs the indicator with layer-wise and head-wise
+ * allocation).  A layer-wise budget is just `budget` of that layer's parameter block; the
+ * two calls below take a budget per KV head instead:
+ *   head_budget [Hkv] int32 on the device; entry g is used as min(max(b, W + 1), budget), so
+ *   `budget` of the parameter block is the largest budget and stays the row stride of idx,
+ *   k_out and v_out.
+ * restkv_smooth_b uses min(head_budget[g], P) in place of min(B, P) for the per-query top-B
+ * statistics of head g; restkv_select_b keeps head_budget[g] - W prefix tokens of head g,
+ * appends the W window tokens, and fills idx[g, head_budget[g] .. B) with -1, which
+ * restkv_compact turns into zero rows.  Everything else as restkv_smooth / restkv_select.
+ */
+int restkv_smooth_b(const restkv_params* p, const float* score, const int32_t* head_budget, float* ema,
+                    float* final_score, int32_t* aws_info, double* aws_d, void* workspace,
+                    size_t workspace_bytes, restkv_stream_t stream);
+int restkv_select_b(const restkv_params* p, const float* final_score, const int32_t* head_budget,
+                    int32_t* idx, void* workspace, size_t workspace_bytes, restkv_stream_t stream);
+
+/*
  * Gather of the kept rows (Eq. topk): k_out[g,j,:] = k[g, idx[g,j], :], same for v.
  *   idx [Hkv, B] int32 in, entries in [0, L) (an entry outside is written as zeros);
  *   k_out, v_out [Hkv, B, d] out, contiguous, dtype of the inputs.

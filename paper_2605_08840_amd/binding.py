@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.restkv_smooth.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
         L.restkv_score_smooth.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.restkv_select.argtypes = [P, vp, vp, vp, sz, vp]
+        L.restkv_smooth_b.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.restkv_select_b.argtypes = [P, vp, vp, vp, vp, sz, vp]
         L.restkv_compact.argtypes = [P, vp, vp, vp, vp, vp, vp]
         L.restkv_strerror.restype = ctypes.c_char_p
         L.restkv_strerror.argtypes = [ctypes.c_int]
@@ -67,7 +69,7 @@ def lib() -> ctypes.CDLL:
         L.restkv_stage_name.restype = ctypes.c_char_p
         L.restkv_stage_name.argtypes = [ctypes.c_int]
         for f in ("restkv_timing_enable", "restkv_timing_read", "restkv_prepare_wo", "restkv_score", "restkv_smooth", "restkv_select",
-                  "restkv_compact", "restkv_version", "restkv_score_smooth"):
+                  "restkv_compact", "restkv_version", "restkv_score_smooth", "restkv_smooth_b", "restkv_select_b"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -142,6 +144,18 @@ def restkv_score_smooth(p, q, k, v, gram, score, ema, final, aws_info, aws_d, wo
     _chk(lib().restkv_score_smooth(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(gram), _ptr(score),
                                    _ptr(ema), _ptr(final), _ptr(aws_info), _ptr(aws_d), wp, wn,
                                    _stream(stream)), "restkv_score_smooth")
+
+
+def restkv_smooth_b(p, score, head_budget, ema, final, aws_info, aws_d, workspace, stream=None):
+    wp, wn = _ws(workspace)
+    _chk(lib().restkv_smooth_b(ctypes.byref(p), _ptr(score), _ptr(head_budget), _ptr(ema), _ptr(final),
+                               _ptr(aws_info), _ptr(aws_d), wp, wn, _stream(stream)), "restkv_smooth_b")
+
+
+def restkv_select_b(p, final, head_budget, idx, workspace, stream=None):
+    wp, wn = _ws(workspace)
+    _chk(lib().restkv_select_b(ctypes.byref(p), _ptr(final), _ptr(head_budget), _ptr(idx), wp, wn,
+                               _stream(stream)), "restkv_select_b")
 
 
 def restkv_select(p, final, idx, workspace, stream=None):

@@ -20,7 +20,7 @@ int resolve(const restkv_params* p, Prob* o) {
   if (p->dtype != RESTKV_F32 && p->dtype != RESTKV_BF16) return RESTKV_EUNSUPPORTED;
   o->Hq = p->n_q_heads; o->Hkv = p->n_kv_heads; o->G = o->Hq / o->Hkv;
   o->d = p->head_dim; o->L = p->seq_len; o->W = p->window; o->P = o->L - o->W;
-  o->B = p->budget; o->R = o->G * o->W;
+  o->B = p->budget; o->R = o->G * o->W; o->hb = nullptr;
   if ((int64_t)o->G * o->W > 4096) return RESTKV_EUNSUPPORTED;
   o->dtype = p->dtype; o->causal = p->causal ? 1 : 0; o->base_k = p->base_window;
   o->adaptive = (p->adaptive && o->W >= 2) ? 1 : 0;
@@ -160,18 +160,32 @@ int restkv_score(const restkv_params* p, const void* q, const void* k, const voi
   return launch_score_simple(pb, q, k, v, gram, score, (char*)workspace, lay, (hipStream_t)stream);
 }
 
-int restkv_smooth(const restkv_params* p, const float* score, float* ema, float* final_score,
-                  int32_t* aws_info, double* aws_d, void* workspace, size_t workspace_bytes,
-                  restkv_stream_t stream) {
+static int smooth_impl(const restkv_params* p, const float* score, const int32_t* head_budget, float* ema,
+                       float* final_score, int32_t* aws_info, double* aws_d, void* workspace,
+                       size_t workspace_bytes, restkv_stream_t stream) {
   Prob pb;
   int rc = resolve(p, &pb);
   if (rc) return rc;
   if (!score || !final_score) return RESTKV_EINVAL;
+  pb.hb = head_budget;
   const SmoothWs lay = smooth_ws(pb);
   rc = check_ws(workspace, workspace_bytes, lay.bytes);
   if (rc) return rc;
   return launch_smooth(pb, score, ema, final_score, aws_info, aws_d, (char*)workspace, lay,
                        (hipStream_t)stream);
+}
+
+int restkv_smooth(const restkv_params* p, const float* score, float* ema, float* final_score,
+                  int32_t* aws_info, double* aws_d, void* workspace, size_t workspace_bytes,
+                  restkv_stream_t stream) {
+  return smooth_impl(p, score, nullptr, ema, final_score, aws_info, aws_d, workspace, workspace_bytes, stream);
+}
+
+int restkv_smooth_b(const restkv_params* p, const float* score, const int32_t* head_budget, float* ema,
+                    float* final_score, int32_t* aws_info, double* aws_d, void* workspace,
+                    size_t workspace_bytes, restkv_stream_t stream) {
+  if (!head_budget) return RESTKV_EINVAL;
+  return smooth_impl(p, score, head_budget, ema, final_score, aws_info, aws_d, workspace, workspace_bytes, stream);
 }
 
 int restkv_score_smooth(const restkv_params* p, const void* q, const void* k, const void* v,
@@ -210,15 +224,27 @@ int restkv_score_smooth(const restkv_params* p, const void* q, const void* k, co
   return launch_smooth_fused_tail(pb, score, fp.ema, final_score, aws_info, aws_d, wm, lm, fp, lf.nchunks, st);
 }
 
-int restkv_select(const restkv_params* p, const float* final_score, int32_t* idx, void* workspace,
-                  size_t workspace_bytes, restkv_stream_t stream) {
+static int select_impl(const restkv_params* p, const float* final_score, const int32_t* head_budget,
+                       int32_t* idx, void* workspace, size_t workspace_bytes, restkv_stream_t stream) {
   Prob pb;
   int rc = resolve(p, &pb);
   if (rc) return rc;
   if (!final_score || !idx) return RESTKV_EINVAL;
+  pb.hb = head_budget;
   rc = check_ws(workspace, workspace_bytes, select_ws_bytes(pb));
   if (rc) return rc;
   return launch_select(pb, final_score, idx, (char*)workspace, (hipStream_t)stream);
+}
+
+int restkv_select(const restkv_params* p, const float* final_score, int32_t* idx, void* workspace,
+                  size_t workspace_bytes, restkv_stream_t stream) {
+  return select_impl(p, final_score, nullptr, idx, workspace, workspace_bytes, stream);
+}
+
+int restkv_select_b(const restkv_params* p, const float* final_score, const int32_t* head_budget,
+                    int32_t* idx, void* workspace, size_t workspace_bytes, restkv_stream_t stream) {
+  if (!head_budget) return RESTKV_EINVAL;
+  return select_impl(p, final_score, head_budget, idx, workspace, workspace_bytes, stream);
 }
 
 int restkv_compact(const restkv_params* p, const void* k, const void* v, const int32_t* idx,

@@ -15,6 +15,7 @@ struct Prob {
   int dtype, causal, base_k, adaptive;
   float scale, alpha, beta;
   int64_t q_sh, q_st, kv_sh, kv_st, ld;
+  const int32_t* hb;   // optional per-KV-head budgets (device, [Hkv]); NULL: B for every head
 };
 
 // Fills `out`; returns RESTKV_OK or the error the block deserves.
@@ -125,6 +126,12 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
   x = r[0] + r[1];
   r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
   return r[0] + r[1];
+}
+
+// Budget of KV head g: its own entry of the optional per-head array, held inside (W, B], else B.
+__device__ __forceinline__ int head_budget(const Prob& pb, int g) {
+  if (!pb.hb) return pb.B;
+  return min(max(pb.hb[g], pb.W + 1), pb.B);
 }
 
 // Order-preserving map float -> uint32 (larger float <=> larger key; -0 < +0).

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void k_sel_bracket(Prob pb, const float* __res
   __shared__ CountSmem cs;
   const int g = blockIdx.x;
   const float* row = fin + (int64_t)g * pb.ld;
-  const int k = pb.B - pb.W;
+  const int k = head_budget(pb, g) - pb.W;
   if (threadIdx.x == 0) { w.cnt_hi[g] = 0; w.ncand[g] = 0; }
   if (k >= pb.P) {
     if (threadIdx.x == 0) w.thr[g] = make_float2(INFINITY, INFINITY);
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void k_sel_finish(Prob pb, SelPtrs w) {
   constexpr int NPT = SCAP / 256;
   __shared__ CountSmem cs;
   const int g = blockIdx.x;
-  const int k = pb.B - pb.W;
+  const int k = head_budget(pb, g) - pb.W;
   uint32_t* cut = w.cut + 4 * g;
   if (k >= pb.P) {                      // everything is kept
     if (threadIdx.x == 0) { cut[0] = 0u; cut[1] = 0xFFFFFFFFu; cut[2] = 1u; }
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(SEL_NT) void k_sel_fallback(Prob pb, const float* _
   if (cut[2] != PENDING) return;
   const float* row = fin + (int64_t)g * pb.ld;
   uint32_t tau, n_gt, k_eq;
-  block_kth_key(row, pb.P, pb.B - pb.W, sm, tau, n_gt, k_eq);
+  block_kth_key(row, pb.P, head_budget(pb, g) - pb.W, sm, tau, n_gt, k_eq);
   if (threadIdx.x == 0) maxpos = 0;
   __syncthreads();
   // position of the last tie that is taken
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void k_sel_emit(Prob pb, const float* __restri
   const int g = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const float* row = fin + (int64_t)g * pb.ld;
   const uint32_t tau = w.cut[4 * g], pos_cut = w.cut[4 * g + 1];
-  const int bp = pb.B - pb.W;
+  const int bg = head_budget(pb, g), bp = bg - pb.W;
   int32_t* out = idx + (int64_t)g * pb.B;
   uint32_t off = 0;
   for (int c = 0; c < (int)blockIdx.x; ++c) off += w.counts[g * nchunks + c];
@@ -223,8 +223,10 @@ __global__ __launch_bounds__(256) void k_sel_emit(Prob pb, const float* __restri
     if (pos < (uint32_t)bp) out[pos] = n0 + e;
     ++pos;
   }
-  if (blockIdx.x == 0)
+  if (blockIdx.x == 0) {
     for (int j = tid; j < pb.W; j += 256) out[bp + j] = pb.P + j;
+    for (int j = bg + tid; j < pb.B; j += 256) out[j] = -1;     // a smaller per-head budget: unused tail
+  }
 }
 
 }  // namespace

@@ -28,7 +28,7 @@ __global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __
   __shared__ CountSmem cs;
   const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
   const float* row = score + (int64_t)r * pb.ld;
-  const int k = min(pb.B, pb.P);
+  const int k = min(head_budget(pb, g), pb.P);
   if (threadIdx.x == 0) { cnt_hi[r] = 0; sum_hi[r] = 0ull; ncand[r] = 0; }
   if (k >= pb.P) {                       // every prefix position is taken: nothing to search
     if (threadIdx.x == 0) thr[r] = make_float2(INFINITY, INFINITY);
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void k_bracket_samples(Prob pb, const float* _
   constexpr int NPT = SMP_NS / 256;
   __shared__ CountSmem cs;
   const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
-  const int k = min(pb.B, pb.P);
+  const int k = min(head_budget(pb, g), pb.P);
   if (threadIdx.x == 0) { cnt_hi[r] = 0; sum_hi[r] = 0ull; }
   if (k >= pb.P) {
     if (threadIdx.x == 0) thr[r] = make_float2(INFINITY, INFINITY);
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __r
   __shared__ CountSmem cs;
   __shared__ unsigned long long isum[4];
   const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
-  const int k = min(pb.B, pb.P);
+  const int k = min(head_budget(pb, g), pb.P);
   if (k >= pb.P) {
     if (threadIdx.x == 0) rowsum[r] = (unsigned long long)pb.P * (unsigned long long)(pb.P - 1) / 2ull;
     return;
@@ -403,7 +403,7 @@ __global__ __launch_bounds__(256) void k_row_finish_slices(Prob pb, const uint32
   __shared__ uint32_t pre[257];              // exclusive prefix of the slice fill counts
   __shared__ uint32_t over;
   const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
-  const int k = min(pb.B, pb.P);
+  const int k = min(head_budget(pb, g), pb.P);
   if (k >= pb.P) {
     if (threadIdx.x == 0) rowsum[r] = (unsigned long long)pb.P * (unsigned long long)(pb.P - 1) / 2ull;
     return;
@@ -459,7 +459,7 @@ __global__ __launch_bounds__(SEL_NT) void k_row_fallback(Prob pb, const float* _
   const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
   if (rowsum[r] != ROW_PENDING) return;
   const float* row = score + (int64_t)r * pb.ld;
-  const int k = min(pb.B, pb.P);
+  const int k = min(head_budget(pb, g), pb.P);
   uint32_t tau, n_gt, k_eq;
   block_kth_key(row, pb.P, k, sm, tau, n_gt, k_eq);
   unsigned long long acc = 0;
@@ -483,7 +483,7 @@ __device__ inline void aws_window(const Prob& pb, const unsigned long long* rows
   w_s = pb.base_k; gamma = 0; d_front = 0.0; d_rear = 0.0;
   if (!pb.adaptive) return;
   const int nf = pb.W / 2;
-  const double bt = (double)min(pb.B, pb.P);
+  const double bt = (double)min(head_budget(pb, g), pb.P);
   unsigned long long sf = 0, sr = 0;
   for (int i = 0; i < pb.W; ++i) {
     const unsigned long long s = rowsum[g * pb.W + i];

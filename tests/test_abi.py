@@ -28,7 +28,7 @@ def test_exports_every_declared_symbol(rk):
     text = open(os.path.join(ROOT, "include", "restkv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(restkv_[a-z_]+)\s*\(", text)))
-    assert {"restkv_score", "restkv_score_smooth", "restkv_smooth", "restkv_select", "restkv_compact", "restkv_prepare_wo",
+    assert {"restkv_score", "restkv_score_smooth", "restkv_smooth", "restkv_smooth_b", "restkv_select_b", "restkv_select", "restkv_compact", "restkv_prepare_wo",
             "restkv_workspace_bytes", "restkv_strerror", "restkv_version"} <= set(names)
     L = rk.lib()
     for n in names:

@@ -176,6 +176,42 @@ def test_smooth_select_compact_stage_exact(rk, oracle_mod, kind, W, P, B, k, bet
         np.testing.assert_array_equal(buf.v_out[g].float().cpu().numpy(), (kv[g] * 2).float().numpy()[idx[g]])
 
 
+def test_per_head_budgets_stage_exact(rk, oracle_mod):
+    """Head-wise budgets (restkv_smooth_b / restkv_select_b): every head against the oracle run
+    with that head's budget; unused tail of idx is -1 and gathers zero rows."""
+    Hkv, d, W, P, k, beta, alpha = 4, 64, 12, 9000, 5, 150.0, 0.3
+    L = P + W
+    budgets = [300, 2048, W + 1, 777]
+    B = max(budgets)
+    s = _smooth_select_inputs(23, Hkv, W, P, "drifting")
+    p = rk.make_params(n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=L, window=W, budget=B,
+                       dtype="bf16", ema_alpha=alpha, base_window=k, beta=beta)
+    dev = "cuda"
+    buf = rk.alloc_layer_buffers(p, torch.bfloat16, dev)
+    buf.score.copy_(torch.from_numpy(s))
+    hb = torch.tensor(budgets, dtype=torch.int32, device=dev)
+    rk.restkv_smooth_b(p, buf.score, hb, buf.ema, buf.final, buf.aws_info, buf.aws_d, buf.workspace)
+    rk.restkv_select_b(p, buf.final, hb, buf.idx, buf.workspace)
+    kv = torch.randn((Hkv, L, d), generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
+    kd = kv.to(dev)
+    rk.restkv_compact(p, kd, kd, buf.idx, buf.k_out, buf.v_out)
+    torch.cuda.synchronize()
+    ema, fin = buf.ema.cpu().numpy(), buf.final.cpu().numpy()
+    info, dd, idx = buf.aws_info.cpu().numpy(), buf.aws_d.cpu().numpy(), buf.idx.cpu().numpy()
+    for g in range(Hkv):
+        Bg = budgets[g]
+        sm = oracle_mod.smooth_head(s[g], alpha, beta, k, True, Bg)
+        assert dd[g, 0] == sm["d_front"] and dd[g, 1] == sm["d_rear"]
+        assert tuple(info[g]) == (sm["w_s"], sm["gamma"])
+        want = oracle_mod.box(ema[g].astype(np.float64), sm["w_s"], sm["gamma"])
+        np.testing.assert_allclose(fin[g], want, rtol=1e-5, atol=1e-30)
+        np.testing.assert_array_equal(idx[g, :Bg], oracle_mod.select(fin[g].astype(np.float64), W, Bg))
+        assert np.all(idx[g, Bg:] == -1)
+        got = buf.k_out[g].float().cpu().numpy()
+        np.testing.assert_array_equal(got[:Bg], kv[g].float().numpy()[idx[g, :Bg]])
+        assert np.all(got[Bg:] == 0)
+
+
 def test_smooth_invariants_on_gpu(rk):
     """EMA with decay 0 is the last query; window 1 without adaptation is the identity."""
     Hkv, W, P, d = 2, 5, 1234, 64
