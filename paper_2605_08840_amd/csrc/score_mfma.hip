@@ -185,10 +185,9 @@ __device__ __forceinline__ void wait_vm() {
 // from 2 rb on, so a wavefront takes the row blocks pr and D/32 - 1 - pr of one head: D/16 + 2
 // k-steps whatever pr.  The value tiles arrive through a 4-deep asynchronous LDS ring and are
 // the B operand shared by all wavefronts; the partial dots of a head's wavefronts meet in LDS.
-// A tile has a matrix half-step (the MFMAs) and a vector half-step (row dots), and wavefronts
-// 4..7 run one half-step behind wavefronts 0..3 as in k_score_pipe; a tile is read in both
-// halves, i.e. until E_2t+3 by the late wavefronts, and the copy of tile t+2 goes to the slot
-// of tile t-2.  The two wavefronts of a head are in the same half.
+// The two 32-key halves of a tile each have a matrix quarter (20 MFMAs) and a vector quarter (row
+// dots) of about the same length; wavefronts 0..3 and 4..7 run them in complementary order (see
+// the loop), so the matrix cores stay fed.  The two wavefronts of a head are in the same group.
 // grid (key chunks, ceil(G/HPW), Hkv), 512 threads; HPW = 4 heads per workgroup (8 for D = 64).
 template <int D>
 __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __restrict__ v,
@@ -252,69 +251,87 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
         }
       }
     };
-
-    wait_vm<NG>();           // own share of tile t0 (compiler-issued loads above are older or waited for)
-    wg_barrier();            // E_2t0
-    const bool late = wv >= NW / 2;
-    if (late) wg_barrier();
-    for (int t = t0; t < t1; ++t) {
-      const int buf = (t - t0) & 1;
-      // ---- matrix half-step (raised priority: see k_score_pipe) ----
-      __builtin_amdgcn_s_setprio(2);
-      issue_tile(t + 2);     // into the slot of tile t-2
-      if (t > t0) head_sum(t - 1);
+    f32x16 y0[2], y1[2];
+    // matrix quarter: Y^T = T V^T for the 32 keys of half nb of tile t
+    auto mat = [&](int nb, int t) {
       const uint16_t* vt = Vs[t & 3];
-      f32x16 y0[2], y1[2];
+      __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+      for (int j = 0; j < 16; ++j) { y0[nb][j] = 0.f; y1[nb][j] = 0.f; }
+      // all operand reads of the quarter first: the MFMAs then run back to back instead of one
+      // LDS round trip per k-step
+      bf16x8 b[N0];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) { y0[nb][j] = 0.f; y1[nb][j] = 0.f; }
-      // consecutive MFMAs never touch the same accumulator
+      for (int a = 0; a < N0; ++a) b[a] = as_bf16x8(*(const uint4*)&vt[Ring::off(32 * nb + rr, 2 * (2 * RB0 + a) + hf)]);
 #pragma unroll
       for (int ks = 2 * RB0; ks < KS; ++ks) {
-        const bf16x8 b0 = as_bf16x8(*(const uint4*)&vt[Ring::off(rr, 2 * ks + hf)]);
-        const bf16x8 b1 = as_bf16x8(*(const uint4*)&vt[Ring::off(32 + rr, 2 * ks + hf)]);
-        y0[0] = MFMA(ahi0[ks - 2 * RB0], b0, y0[0]);
-        y0[1] = MFMA(ahi0[ks - 2 * RB0], b1, y0[1]);
-        if (ks >= 2 * RB1) {
-          y1[0] = MFMA(ahi1[ks - 2 * RB1], b0, y1[0]);
-          y1[1] = MFMA(ahi1[ks - 2 * RB1], b1, y1[1]);
-        }
-        y0[0] = MFMA(alo0[ks - 2 * RB0], b0, y0[0]);
-        y0[1] = MFMA(alo0[ks - 2 * RB0], b1, y0[1]);
-        if (ks >= 2 * RB1) {
-          y1[0] = MFMA(alo1[ks - 2 * RB1], b0, y1[0]);
-          y1[1] = MFMA(alo1[ks - 2 * RB1], b1, y1[1]);
-        }
+        y0[nb] = MFMA(ahi0[ks - 2 * RB0], b[ks - 2 * RB0], y0[nb]);
+        if (ks >= 2 * RB1) y1[nb] = MFMA(ahi1[ks - 2 * RB1], b[ks - 2 * RB0], y1[nb]);
+        y0[nb] = MFMA(alo0[ks - 2 * RB0], b[ks - 2 * RB0], y0[nb]);
+        if (ks >= 2 * RB1) y1[nb] = MFMA(alo1[ks - 2 * RB1], b[ks - 2 * RB0], y1[nb]);
+      }
+      __builtin_amdgcn_s_setprio(0);
+    };
+    // vector quarter: row dot with v_n (register j of a block is Gram row 32 rb + 8 (j/4) + 4 hf + j%4)
+    auto dot = [&](int nb, int t) {
+      const uint16_t* vt = Vs[t & 3];
+      float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+      for (int jq = 0; jq < 4; ++jq) {
+        const uint2 u0 = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB0 + jq) + 4 * hf];
+        const uint2 u1 = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB1 + jq) + 4 * hf];
+        acc0 = fmaf(y0[nb][4 * jq + 0], __uint_as_float(u0.x << 16), acc0);
+        acc1 = fmaf(y1[nb][4 * jq + 0], __uint_as_float(u1.x << 16), acc1);
+        acc0 = fmaf(y0[nb][4 * jq + 1], __uint_as_float(u0.x & 0xFFFF0000u), acc0);
+        acc1 = fmaf(y1[nb][4 * jq + 1], __uint_as_float(u1.x & 0xFFFF0000u), acc1);
+        acc0 = fmaf(y0[nb][4 * jq + 2], __uint_as_float(u0.y << 16), acc0);
+        acc1 = fmaf(y1[nb][4 * jq + 2], __uint_as_float(u1.y << 16), acc1);
+        acc0 = fmaf(y0[nb][4 * jq + 3], __uint_as_float(u0.y & 0xFFFF0000u), acc0);
+        acc1 = fmaf(y1[nb][4 * jq + 3], __uint_as_float(u1.y & 0xFFFF0000u), acc1);
+      }
+      const float acc = xhalf_sum(acc0 + acc1);
+      if (hf == 0) part[(t - t0) & 1][hw][PR][32 * nb + rr] = acc;
+    };
+
+    // Half-steps H_0, H_1, ... separated by workgroup barriers.  Wavefronts 0..3 run
+    //   H_2t: matrix(0,t) dot(0,t)      H_2t+1: matrix(1,t) dot(1,t),
+    // wavefronts 4..7 the complementary order
+    //   H_2t: dot(1,t-1) matrix(0,t)    H_2t+1: dot(0,t) matrix(1,t),
+    // so that on every SIMD one wavefront feeds the matrix cores while the other does the (about
+    // equally long) vector quarter.  A tile is read from H_2t to H_2t+2; the copy of tile t+2 is
+    // issued at the top of H_2t+1 (its slot held tile t-2); a wavefront waits for its share of tile
+    // t+1 before the barrier that ends H_2t+1, when only the copy of tile t+2 is younger.
+    const bool late = wv >= NW / 2;
+    wait_vm<NG>();           // own share of tile t0 (compiler-issued loads above are older or waited for)
+    wg_barrier();
+    for (int t = t0; t < t1; ++t) {
+      // ---- H_2t ----
+      if (!late) {
+        if (t > t0) head_sum(t - 1);
+        mat(0, t);
+        dot(0, t);
+      } else {
+        if (t > t0) dot(1, t - 1);
+        mat(0, t);
+      }
+      wg_barrier();
+      // ---- H_2t+1 ----
+      issue_tile(t + 2);     // into the slot of tile t-2
+      if (!late) {
+        mat(1, t);
+        dot(1, t);
+      } else {
+        if (t > t0) head_sum(t - 1);
+        dot(0, t);
+        mat(1, t);
       }
       wait_vm<NG>();         // own share of tile t+1 (only the copy of tile t+2 is younger)
       wg_barrier();
-      __builtin_amdgcn_s_setprio(0);
-      // ---- vector half-step ----
-      // row dot with v_n: register j of a block is Gram row 32 rb + 8 (j/4) + 4 hf + j%4
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        float acc0 = 0.f, acc1 = 0.f;
-#pragma unroll
-        for (int jq = 0; jq < 4; ++jq) {
-          const uint2 u0 = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB0 + jq) + 4 * hf];
-          const uint2 u1 = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB1 + jq) + 4 * hf];
-          acc0 = fmaf(y0[nb][4 * jq + 0], __uint_as_float(u0.x << 16), acc0);
-          acc1 = fmaf(y1[nb][4 * jq + 0], __uint_as_float(u1.x << 16), acc1);
-          acc0 = fmaf(y0[nb][4 * jq + 1], __uint_as_float(u0.x & 0xFFFF0000u), acc0);
-          acc1 = fmaf(y1[nb][4 * jq + 1], __uint_as_float(u1.x & 0xFFFF0000u), acc1);
-          acc0 = fmaf(y0[nb][4 * jq + 2], __uint_as_float(u0.y << 16), acc0);
-          acc1 = fmaf(y1[nb][4 * jq + 2], __uint_as_float(u1.y << 16), acc1);
-          acc0 = fmaf(y0[nb][4 * jq + 3], __uint_as_float(u0.y & 0xFFFF0000u), acc0);
-          acc1 = fmaf(y1[nb][4 * jq + 3], __uint_as_float(u1.y & 0xFFFF0000u), acc1);
-        }
-        const float acc = xhalf_sum(acc0 + acc1);
-        if (hf == 0) part[buf][hw][PR][32 * nb + rr] = acc;
-      }
-      wg_barrier();
     }
-    head_sum(t1 - 1);
-    if (!late) wg_barrier();
+    // ---- H_2n: the late wavefronts' last vector quarter ----
+    if (late) dot(1, t1 - 1); else head_sum(t1 - 1);
+    wg_barrier();
+    if (late) head_sum(t1 - 1);
     wait_vm<0>();            // no copy may land in LDS after the workgroup has gone
   };
   if constexpr (WPH == 1) {
