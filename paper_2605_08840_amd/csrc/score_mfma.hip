@@ -252,6 +252,7 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
       }
     };
     f32x16 y0[2], y1[2];
+    uint2 vq0[2][4], vq1[2][4];      // the value entries the row dots of a half need (fetched with its operands)
     // matrix quarter: Y^T = T V^T for the 32 keys of half nb of tile t
     auto mat = [&](int nb, int t) {
       const uint16_t* vt = Vs[t & 3];
@@ -264,6 +265,11 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
 #pragma unroll
       for (int a = 0; a < N0; ++a) b[a] = as_bf16x8(*(const uint4*)&vt[Ring::off(32 * nb + rr, 2 * (2 * RB0 + a) + hf)]);
 #pragma unroll
+      for (int jq = 0; jq < 4; ++jq) {
+        vq0[nb][jq] = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB0 + jq) + 4 * hf];
+        vq1[nb][jq] = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB1 + jq) + 4 * hf];
+      }
+#pragma unroll
       for (int ks = 2 * RB0; ks < KS; ++ks) {
         y0[nb] = MFMA(ahi0[ks - 2 * RB0], b[ks - 2 * RB0], y0[nb]);
         if (ks >= 2 * RB1) y1[nb] = MFMA(ahi1[ks - 2 * RB1], b[ks - 2 * RB0], y1[nb]);
@@ -274,21 +280,20 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
     };
     // vector quarter: row dot with v_n (register j of a block is Gram row 32 rb + 8 (j/4) + 4 hf + j%4)
     auto dot = [&](int nb, int t) {
-      const uint16_t* vt = Vs[t & 3];
-      float acc0 = 0.f, acc1 = 0.f;
+      float a0[4], a1[4];              // four independent chains per row block
 #pragma unroll
       for (int jq = 0; jq < 4; ++jq) {
-        const uint2 u0 = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB0 + jq) + 4 * hf];
-        const uint2 u1 = *(const uint2*)&vt[Ring::off(32 * nb + rr, 4 * RB1 + jq) + 4 * hf];
-        acc0 = fmaf(y0[nb][4 * jq + 0], __uint_as_float(u0.x << 16), acc0);
-        acc1 = fmaf(y1[nb][4 * jq + 0], __uint_as_float(u1.x << 16), acc1);
-        acc0 = fmaf(y0[nb][4 * jq + 1], __uint_as_float(u0.x & 0xFFFF0000u), acc0);
-        acc1 = fmaf(y1[nb][4 * jq + 1], __uint_as_float(u1.x & 0xFFFF0000u), acc1);
-        acc0 = fmaf(y0[nb][4 * jq + 2], __uint_as_float(u0.y << 16), acc0);
-        acc1 = fmaf(y1[nb][4 * jq + 2], __uint_as_float(u1.y << 16), acc1);
-        acc0 = fmaf(y0[nb][4 * jq + 3], __uint_as_float(u0.y & 0xFFFF0000u), acc0);
-        acc1 = fmaf(y1[nb][4 * jq + 3], __uint_as_float(u1.y & 0xFFFF0000u), acc1);
+        const uint2 u0 = vq0[nb][jq], u1 = vq1[nb][jq];
+        a0[jq] = y0[nb][4 * jq + 0] * __uint_as_float(u0.x << 16);
+        a1[jq] = y1[nb][4 * jq + 0] * __uint_as_float(u1.x << 16);
+        a0[jq] = fmaf(y0[nb][4 * jq + 1], __uint_as_float(u0.x & 0xFFFF0000u), a0[jq]);
+        a1[jq] = fmaf(y1[nb][4 * jq + 1], __uint_as_float(u1.x & 0xFFFF0000u), a1[jq]);
+        a0[jq] = fmaf(y0[nb][4 * jq + 2], __uint_as_float(u0.y << 16), a0[jq]);
+        a1[jq] = fmaf(y1[nb][4 * jq + 2], __uint_as_float(u1.y << 16), a1[jq]);
+        a0[jq] = fmaf(y0[nb][4 * jq + 3], __uint_as_float(u0.y & 0xFFFF0000u), a0[jq]);
+        a1[jq] = fmaf(y1[nb][4 * jq + 3], __uint_as_float(u1.y & 0xFFFF0000u), a1[jq]);
       }
+      const float acc0 = (a0[0] + a0[1]) + (a0[2] + a0[3]), acc1 = (a1[0] + a1[1]) + (a1[2] + a1[3]);
       const float acc = xhalf_sum(acc0 + acc1);
       if (hf == 0) part[(t - t0) & 1][hw][PR][32 * nb + rr] = acc;
     };
