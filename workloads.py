@@ -89,7 +89,7 @@ def make_qkv(w: Workload, layer: int = 0, device="cpu"):
         # position 0 and three seeded prefix positions per KV head carry keys scaled x8
         g = _gen(w, layer, 3, torch.device("cpu"))
         for h in range(Hkv):
-            pos = torch.randint(1, w.prefix, (3,), generator=g).tolist()
+            pos = torch.randint(1, max(w.prefix, 2), (3,), generator=g).tolist()   # (a one-token prefix: position 1 is in the window)
             for p in [0] + pos:
                 k[h, p, :] *= 8.0
     elif w.structure == "lowrank":
