@@ -457,13 +457,20 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int j = 0; j < 16; ++j) sacc[mb][j] = 0.f;
+      // operand reads in batches of eight ahead of their MFMAs (one LDS round trip per batch)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
+      for (int k0 = 0; k0 < KS; k0 += 4) {
+        bf16x8 a[4][2];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-          const bf16x8 a = as_bf16x8(*(const uint4*)&kt[RingK::off(32 * mb + rr, 2 * ks + hf)]);
-          sacc[mb] = MFMA(a, qf[ks], sacc[mb]);
-        }
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+            a[ks][mb] = as_bf16x8(*(const uint4*)&kt[RingK::off(32 * mb + rr, 2 * (k0 + ks) + hf)]);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb) sacc[mb] = MFMA(a[ks][mb], qf[k0 + ks], sacc[mb]);
+      }
       wait_vm<NG>();         // own share of tile t+1 (only the copies of tile t+2 are younger)
       wg_barrier();
       __builtin_amdgcn_s_setprio(0);
