@@ -99,9 +99,9 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
                                                   int vec) {
   constexpr int PG = 4;                          // rows per packed LDS word
   constexpr int NGRP = ROWS_BLK / PG;
-  __shared__ uint32_t pk0[NGRP][256];            // per thread and row group: RG x (count:3 | offset sum:3)
-  __shared__ uint32_t pk1[NGRP][256];            // RG x 4-bit masks of the entries inside the bracket
-  __shared__ uint8_t pk2[NGRP][256][PG];         // candidates of the row in earlier threads of the quarter
+  __shared__ __attribute__((aligned(16))) uint32_t pk0[NGRP][256];            // per thread and row group: RG x (count:3 | offset sum:3)
+  __shared__ __attribute__((aligned(16))) uint32_t pk1[NGRP][256];            // RG x 4-bit masks of the entries inside the bracket
+  __shared__ __attribute__((aligned(16))) uint8_t pk2[NGRP][PG][256];   // candidates of the row in earlier threads of the quarter
   __shared__ float pval[CAPT][256];              // private lists of candidates, in stream order: value ...
   __shared__ uint8_t pmeta[CAPT][256];           // ... and (row in block) * 4 + element
   __shared__ uint32_t rbase[ROWS_BLK][4];        // first list position of each (row, quarter)
@@ -120,19 +120,29 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
       const int itr = rl / PG, rr = rl % PG, sh0 = 6 * rr, sh1 = 4 * rr;
       uint32_t cnt = 0, els = 0, wsum = 0, nc = 0;
       if (rl < nrows) {
-        // (lanes with the same row group and quarter read the same word; the others are 64 or
-        // 256 words apart, so the walk starts at a different word for each of them)
-        const int rot = 4 * (((lane >> 4) << 2) | (lane & 3));
-#pragma unroll 8
-        for (int tt = 0; tt < 64; ++tt) {
-          const int t = (tt + rot) & 63, src = 64 * qd + t;
-          const uint32_t a0 = (pk0[itr][src] >> sh0) & 63u;
-          const uint32_t c = a0 & 7u;
-          cnt += c;
-          els += a0 >> 3;
-          wsum += c * (uint32_t)t;
-          pk2[itr][src][rr] = (uint8_t)nc;       // at most 252: a quarter holds 256 positions
-          nc += (uint32_t)__popc((pk1[itr][src] >> sh1) & 15u);
+        // Four threads' words per step (16-byte LDS reads; the four offset bytes leave as one
+        // word).  Lanes with the same row group and quarter read the same address; the 16
+        // (row group, quarter) pairs of a wavefront start their walk 16 bytes apart, so that no
+        // two of them meet in an LDS bank.
+        const int rot = ((lane >> 4) << 2) | (lane & 3);
+#pragma unroll 4
+        for (int tt = 0; tt < 16; ++tt) {
+          const int t4 = (tt + rot) & 15, src = 64 * qd + 4 * t4;
+          const uint4 a4 = *(const uint4*)&pk0[itr][src];
+          const uint4 m4 = *(const uint4*)&pk1[itr][src];
+          const uint32_t aw[4] = {a4.x, a4.y, a4.z, a4.w}, mw[4] = {m4.x, m4.y, m4.z, m4.w};
+          uint32_t offs = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const uint32_t a0 = (aw[e] >> sh0) & 63u;
+            const uint32_t c = a0 & 7u;
+            cnt += c;
+            els += a0 >> 3;
+            wsum += c * (uint32_t)(4 * t4 + e);
+            offs |= (nc & 255u) << (8 * e);       // at most 252: a quarter holds 256 positions
+            nc += (uint32_t)__popc((mw[e] >> sh1) & 15u);
+          }
+          *(uint32_t*)&pk2[itr][rr][src] = offs;
         }
       }
       // positions above the bracket seen by this quarter: thread t of it owns nb0 + 4 (64 qd + t) + el
@@ -176,7 +186,7 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
 #pragma unroll
       for (int k = 0; k < CAPT; ++k) {
         const int rl = k < kp ? mt[k] >> 2 : 0;
-        pos[k] = rbase[rl][qd] + pk2[rl / PG][tid][rl % PG];
+        pos[k] = rbase[rl][qd] + pk2[rl / PG][rl % PG][tid];
       }
       int prev = -1;
       uint32_t run = 0;
@@ -210,7 +220,7 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
           if (rl >= nrows) break;
           const uint32_t mk = (pk1[itr][tid] >> (4 * rr)) & 15u;
           const int row = g * pb.W + rb0 + rl;
-          uint32_t ps = rbase[rl][qd] + pk2[itr][tid][rr];
+          uint32_t ps = rbase[rl][qd] + pk2[itr][rr][tid];
 #pragma unroll
           for (int el = 0; el < 4; ++el) {
             if ((mk >> el) & 1u) {
