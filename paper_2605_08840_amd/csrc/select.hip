@@ -186,8 +186,14 @@ __global__ __launch_bounds__(256) void k_sel_emit(Prob pb, const float* __restri
   const uint32_t tau = w.cut[4 * g], pos_cut = w.cut[4 * g + 1];
   const int bg = head_budget(pb, g), bp = bg - pb.W;
   int32_t* out = idx + (int64_t)g * pb.B;
+  // selected entries in the chunks before this one: loads spread over the threads, then summed
+  __shared__ uint32_t offs[4];
   uint32_t off = 0;
-  for (int c = 0; c < (int)blockIdx.x; ++c) off += w.counts[g * nchunks + c];
+  for (int c = tid; c < (int)blockIdx.x; c += 256) off += w.counts[g * nchunks + c];
+  off = wave_sum(off);
+  if (lane == 0) offs[wv] = off;
+  __syncthreads();
+  off = offs[0] + offs[1] + offs[2] + offs[3];
   const int n0 = blockIdx.x * SCH + tid * 16;
   uint32_t mask = 0;
 #pragma unroll

@@ -488,17 +488,13 @@ __global__ __launch_bounds__(SEL_NT) void k_row_fallback(Prob pb, const float* _
 
 // Window size and shift from the drift statistic (device function so that every block of
 // the box kernel derives the same integers without a host round trip).
-__device__ inline void aws_window(const Prob& pb, const unsigned long long* rowsum, int g,
+// (front and rear index sums come in already added up)
+__device__ inline void aws_window(const Prob& pb, unsigned long long sf, unsigned long long sr, int g,
                                   int& w_s, int& gamma, double& d_front, double& d_rear) {
   w_s = pb.base_k; gamma = 0; d_front = 0.0; d_rear = 0.0;
   if (!pb.adaptive) return;
   const int nf = pb.W / 2;
   const double bt = (double)min(head_budget(pb, g), pb.P);
-  unsigned long long sf = 0, sr = 0;
-  for (int i = 0; i < pb.W; ++i) {
-    const unsigned long long s = rowsum[g * pb.W + i];
-    if (i < nf) sf += s; else sr += s;
-  }
   d_front = (double)sf / (bt * (double)nf);
   d_rear = (double)sr / (bt * (double)(pb.W - nf));
   const double x = d_front - d_rear;
@@ -516,10 +512,25 @@ __global__ __launch_bounds__(256) void k_box(Prob pb, const float* __restrict__ 
                                              double* __restrict__ aws_d) {
   const int g = blockIdx.y;
   __shared__ int sh_ws, sh_gamma;
+  __shared__ unsigned long long sh_sum[2][4];
+  // the W index sums of the head: all loads in flight at once, wavefront sums, then thread 0
+  {
+    unsigned long long sf = 0, sr = 0;
+    if (pb.adaptive)
+      for (int i = threadIdx.x; i < pb.W; i += 256) {
+        const unsigned long long s = rowsum[g * pb.W + i];
+        if (i < pb.W / 2) sf += s; else sr += s;
+      }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) { sf += __shfl_xor(sf, o, 64); sr += __shfl_xor(sr, o, 64); }
+    if ((threadIdx.x & 63) == 0) { sh_sum[0][threadIdx.x >> 6] = sf; sh_sum[1][threadIdx.x >> 6] = sr; }
+  }
+  __syncthreads();
   if (threadIdx.x == 0) {
     int w_s0, gamma0;
     double df, dr;
-    aws_window(pb, rowsum, g, w_s0, gamma0, df, dr);
+    aws_window(pb, sh_sum[0][0] + sh_sum[0][1] + sh_sum[0][2] + sh_sum[0][3],
+               sh_sum[1][0] + sh_sum[1][1] + sh_sum[1][2] + sh_sum[1][3], g, w_s0, gamma0, df, dr);
     sh_ws = w_s0; sh_gamma = gamma0;
     if (blockIdx.x == 0) {
       if (aws_info) { aws_info[2 * g] = w_s0; aws_info[2 * g + 1] = gamma0; }
