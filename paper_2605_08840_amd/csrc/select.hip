@@ -101,12 +101,24 @@ __global__ __launch_bounds__(256) void k_sel_finish(Prob pb, SelPtrs w) {
     return;
   }
   const uint32_t need = (uint32_t)k - ch;
+  // unconditional loads (an empty slot re-reads entry 0 and is then masked): all in flight at once
   uint32_t ck[NPT], ci[NPT];
+  {
+    float fv[NPT];
+    int iv[NPT];
 #pragma unroll
-  for (int j = 0; j < NPT; ++j) {
-    const uint32_t x = threadIdx.x + j * 256;
-    ck[j] = x < nc ? float_key(w.cand_val[(int64_t)g * SCAP + x]) : 0u;
-    ci[j] = x < nc ? (uint32_t)w.cand_idx[(int64_t)g * SCAP + x] : 0u;
+    for (int j = 0; j < NPT; ++j) {
+      const uint32_t x = threadIdx.x + j * 256;
+      const int64_t o = (int64_t)g * SCAP + (x < nc ? x : 0u);
+      fv[j] = w.cand_val[o];
+      iv[j] = w.cand_idx[o];
+    }
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+      const bool in = (uint32_t)(threadIdx.x + j * 256) < nc;
+      ck[j] = in ? float_key(fv[j]) : 0u;
+      ci[j] = in ? (uint32_t)iv[j] : 0u;
+    }
   }
   int it = 0, top_bit;
   uint32_t prefix;

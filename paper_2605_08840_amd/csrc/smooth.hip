@@ -381,13 +381,25 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __r
     return;
   }
   const uint32_t need = (uint32_t)k - ch;
+  // all loads unconditional (an empty slot re-reads entry 0 and is then masked): independent
+  // loads in flight together instead of one round trip per slot
   uint32_t ck[NPT], ci[NPT];
+  {
+    float fv[NPT];
+    int iv[NPT];
 #pragma unroll
-  for (int j = 0; j < NPT; ++j) {
-    const uint32_t x = threadIdx.x + j * 256;
-    const int64_t o = (int64_t)r * CAND_CAP + x;
-    ck[j] = x < nc ? float_key(cand_val[o]) : 0u;
-    ci[j] = x < nc ? (uint32_t)cand_idx[o] : 0u;
+    for (int j = 0; j < NPT; ++j) {
+      const uint32_t x = threadIdx.x + j * 256;
+      const int64_t o = (int64_t)r * CAND_CAP + (x < nc ? x : 0u);
+      fv[j] = cand_val[o];
+      iv[j] = cand_idx[o];
+    }
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+      const bool in = (uint32_t)(threadIdx.x + j * 256) < nc;
+      ck[j] = in ? float_key(fv[j]) : 0u;
+      ci[j] = in ? (uint32_t)iv[j] : 0u;
+    }
   }
   unsigned long long acc = finish_candidates<NPT>(ck, ci, need, thr[r], cs);
 #pragma unroll
@@ -438,19 +450,26 @@ __global__ __launch_bounds__(256) void k_row_finish_slices(Prob pb, const uint32
   }
   const uint32_t need = (uint32_t)k - ch;
   uint32_t ck[NPT], ci[NPT];
+  {
+    float fv[NPT];
+    int iv[NPT];
 #pragma unroll
-  for (int j = 0; j < NPT; ++j) {
-    const uint32_t x = threadIdx.x + j * 256;
-    ck[j] = 0u; ci[j] = 0u;
-    if (x < nc) {
+    for (int j = 0; j < NPT; ++j) {          // unconditional loads: see k_row_finish
+      const uint32_t x0 = threadIdx.x + j * 256, x = x0 < nc ? x0 : 0u;
       int lo = 0, hi = nchunks - 1;           // last chunk whose prefix is <= x
       while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if (pre[mid] <= x) lo = mid; else hi = mid - 1;
       }
       const int64_t o = ((int64_t)r * nchunks + lo) * caps + (x - pre[lo]);
-      ck[j] = float_key(sval[o]);
-      ci[j] = (uint32_t)sidx[o];
+      fv[j] = sval[o];
+      iv[j] = sidx[o];
+    }
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) {
+      const bool in = (uint32_t)(threadIdx.x + j * 256) < nc;
+      ck[j] = in ? float_key(fv[j]) : 0u;
+      ci[j] = in ? (uint32_t)iv[j] : 0u;
     }
   }
   unsigned long long acc = finish_candidates<NPT>(ck, ci, need, thr[r], cs);
