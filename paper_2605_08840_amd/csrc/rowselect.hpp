@@ -220,11 +220,11 @@ template <int NPT, int RUN>
 __device__ inline int block_sample_regs(const float* __restrict__ row, int n, uint32_t (&k)[NPT]) {
   const int cap = NPT * blockDim.x;
   if (n <= cap) {
+    float f[NPT];            // unconditional loads (clamped, then masked): all in flight together
 #pragma unroll
-    for (int j = 0; j < NPT; ++j) {
-      const int x = threadIdx.x + j * blockDim.x;
-      k[j] = x < n ? float_key(row[x]) : 0u;
-    }
+    for (int j = 0; j < NPT; ++j) f[j] = row[min((int)(threadIdx.x + j * blockDim.x), n - 1)];
+#pragma unroll
+    for (int j = 0; j < NPT; ++j) k[j] = (int)(threadIdx.x + j * blockDim.x) < n ? float_key(f[j]) : 0u;
     return n;
   }
   const int nch = cap / RUN;
