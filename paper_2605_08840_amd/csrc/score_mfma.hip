@@ -396,10 +396,9 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
 
   bf16x8 qf[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    uint4 u = make_uint4(0, 0, 0, 0);
-    if (ri.valid) u = *(const uint4*)(q + (int64_t)ri.h * pb.q_sh + (int64_t)ri.i * pb.q_st + 16 * ks + 8 * hf);
-    qf[ks] = as_bf16x8(u);
+  for (int ks = 0; ks < KS; ++ks) {       // an absent row re-reads row (h, 0) and is masked: no branch around the loads
+    const uint4 u = *(const uint4*)(q + (int64_t)ri.h * pb.q_sh + (int64_t)(ri.valid ? ri.i : 0) * pb.q_st + 16 * ks + 8 * hf);
+    qf[ks] = as_bf16x8(ri.valid ? u : make_uint4(0, 0, 0, 0));
   }
   const int vis_last = (pb.causal && ri.valid) ? pb.P + ri.i : pb.L - 1;
   const float c2 = pb.scale * LOG2E;
@@ -736,18 +735,18 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
     // operand-ordered copies left by the merge kernel: one 1 KiB run per wavefront and register
     const int64_t plane = (int64_t)pb.Hkv * nwb * (KS * 2 * 32 * 8);
     const uint16_t* ob = o.op + (((int64_t)(g * nwb + wb) * KS * 2 + hf) * 32 + rr) * 8;
+    // (loaded whether the row exists or not, then masked: the buffer holds every padded row,
+    // and unconditional loads are all in flight together)
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      uint4 a = make_uint4(0, 0, 0, 0), b = a, c = a;
-      if (valid) {
-        const uint16_t* pk = ob + ks * (2 * 32 * 8);
-        a = *(const uint4*)pk;
-        b = *(const uint4*)(pk + plane);
-        c = *(const uint4*)(pk + 2 * plane);
-      }
-      qf[ks] = as_bf16x8(a);
-      uhi[ks] = as_bf16x8(b);
-      ulo[ks] = as_bf16x8(c);
+      const uint16_t* pk = ob + ks * (2 * 32 * 8);
+      const uint4 a = *(const uint4*)pk;
+      const uint4 b = *(const uint4*)(pk + plane);
+      const uint4 c = *(const uint4*)(pk + 2 * plane);
+      qf[ks] = as_bf16x8(valid ? a : zero4);
+      uhi[ks] = as_bf16x8(valid ? b : zero4);
+      ulo[ks] = as_bf16x8(valid ? c : zero4);
     }
     // Start values of the two accumulators of this row, so that the MFMAs deliver
     //   s + (-M - log2(G l)) / c2   and   u.v_n - zz/2   directly.
