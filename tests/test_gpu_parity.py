@@ -57,6 +57,34 @@ def test_score_noncausal_and_scale(rk, oracle_mod):
         assert_score_close(got["score"][g], Ig, tol, f"noncausal head {g}")
 
 
+@pytest.mark.parametrize("kind", ["equal_values", "zero_queries", "one_key_dominates", "zero_projection"])
+def test_score_degenerate_inputs(rk, oracle_mod, kind):
+    """The degenerate cases of the indicator on the matrix-core path: all values equal (the three
+    terms of the expanded distance cancel: I = 0 up to the cancellation bound), zero queries
+    (uniform attention), one key holding nearly all the mass of every query (leave-one-out form),
+    zero projection (I = 0 exactly)."""
+    w = workloads.small_case(Hq=4, Hkv=2, d=128, L=700, W=16, B=64, dtype="bf16", D=128, seed=11)
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    if kind == "equal_values":
+        v = v[:, :1, :].expand_as(v).contiguous()
+    elif kind == "zero_queries":
+        q = torch.zeros_like(q)
+    elif kind == "one_key_dominates":
+        k = k.clone()
+        k[:, 5, :] = (q.float().reshape(w.n_kv_heads, -1, w.head_dim).mean(1) * 6.0).to(k.dtype)
+    elif kind == "zero_projection":
+        wo = torch.zeros_like(wo)
+    got = run_gpu_layer(rk, w, q, k, v, wo)
+    assert np.all(np.isfinite(got["score"])) and np.all(got["score"] >= 0)
+    if kind == "zero_projection":
+        assert np.all(got["score"] == 0)
+        return
+    ref = oracle_score(oracle_mod, w, q, k, v, wo)
+    for g, (Ig, tol) in ref.items():
+        assert_score_close(got["score"][g], Ig, tol, f"{kind} head {g}")
+
+
 def test_gram_matches_float64_product(rk):
     w = _case("bf16_mha")
     wo = workloads.make_wo(w)
