@@ -5,6 +5,8 @@
 // brackets the row's top-B threshold; the fused pass computes the EMA and, per row, counts and
 // sums the positions above the bracket and collects the few entries inside it; a finishing
 // kernel decides the threshold exactly among those candidates.
+#include <type_traits>
+
 #include "rowselect.hpp"
 
 namespace restkv {
@@ -375,38 +377,45 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __r
     return;
   }
   const uint32_t ch = cnt_hi[r], nc = ncand[r];
+  const unsigned long long shi = sum_hi[r];          // fetched with the counters, used at the very end
   const bool ok = ch < (uint32_t)k && (uint32_t)k <= ch + nc && nc <= (uint32_t)CAND_CAP;
   if (!ok) {
     if (threadIdx.x == 0) rowsum[r] = ROW_PENDING;
     return;
   }
   const uint32_t need = (uint32_t)k - ch;
-  // all loads unconditional (an empty slot re-reads entry 0 and is then masked): independent
-  // loads in flight together instead of one round trip per slot
-  uint32_t ck[NPT], ci[NPT];
-  {
-    float fv[NPT];
-    int iv[NPT];
+  // All loads unconditional (an empty slot re-reads entry 0 and is then masked): independent
+  // loads in flight together instead of one round trip per slot.  Only as many slots per thread
+  // as the row's candidates need (block-uniform), so a short list is counted quickly.
+  const float2 th = thr[r];
+  auto run = [&](auto nsc) {
+    constexpr int NS = decltype(nsc)::value;
+    uint32_t ck[NS], ci[NS];
+    float fv[NS];
+    int iv[NS];
 #pragma unroll
-    for (int j = 0; j < NPT; ++j) {
+    for (int j = 0; j < NS; ++j) {
       const uint32_t x = threadIdx.x + j * 256;
       const int64_t o = (int64_t)r * CAND_CAP + (x < nc ? x : 0u);
       fv[j] = cand_val[o];
       iv[j] = cand_idx[o];
     }
 #pragma unroll
-    for (int j = 0; j < NPT; ++j) {
+    for (int j = 0; j < NS; ++j) {
       const bool in = (uint32_t)(threadIdx.x + j * 256) < nc;
       ck[j] = in ? float_key(fv[j]) : 0u;
       ci[j] = in ? (uint32_t)iv[j] : 0u;
     }
-  }
-  unsigned long long acc = finish_candidates<NPT>(ck, ci, need, thr[r], cs);
+    return finish_candidates<NS>(ck, ci, need, th, cs);
+  };
+  unsigned long long acc = nc <= 1024u  ? run(std::integral_constant<int, 4>{})
+                           : nc <= 2048u ? run(std::integral_constant<int, 8>{})
+                                         : run(std::integral_constant<int, NPT>{});
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 64);
   if ((threadIdx.x & 63) == 0) isum[threadIdx.x >> 6] = acc;
   __syncthreads();
-  if (threadIdx.x == 0) rowsum[r] = isum[0] + isum[1] + isum[2] + isum[3] + sum_hi[r];
+  if (threadIdx.x == 0) rowsum[r] = isum[0] + isum[1] + isum[2] + isum[3] + shi;
 }
 
 // The finishing step when the candidates of a row sit in per-chunk slices
