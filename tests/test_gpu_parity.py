@@ -449,6 +449,30 @@ def test_decode_reeviction_folded_layers(rk, oracle_mod):
             np.testing.assert_array_equal(idx[r], oracle_mod.select(fin[r].astype(np.float64), w.window, w.budget))
             np.testing.assert_array_equal(buf.k_out[r].float().cpu().numpy(), kl[g].float().numpy()[idx[r]])
 
+def test_fused_call_full_size_matches_separate_calls(rk):
+    """The fused call at the benchmark configuration (drift_128k, one layer): same raw score,
+    same top-B statistics and window, final score to rounding, selection equal up to near-ties."""
+    w = workloads.WORKLOADS["drift_128k"]
+    q, k, v = workloads.make_qkv(w, 1, "cuda")
+    wo = workloads.make_wo(w, 1, "cuda")
+    p = params_for(rk, w)
+    gram = torch.empty((w.n_q_heads, w.head_dim, w.head_dim), dtype=torch.float32, device="cuda")
+    rk.restkv_prepare_wo(p, wo, gram)
+    del wo
+    a = rk.alloc_layer_buffers(p, q.dtype, "cuda")
+    b = rk.alloc_layer_buffers(p, q.dtype, "cuda")
+    rk.evict_layer(p, q, k, v, gram, a)
+    rk.evict_layer(p, q, k, v, gram, b, fused=True)
+    torch.cuda.synchronize()
+    P = w.prefix
+    assert torch.equal(a.score[..., :P], b.score[..., :P])
+    assert torch.equal(a.aws_d, b.aws_d) and torch.equal(a.aws_info, b.aws_info)
+    fa, fb = a.final[..., :P].cpu().numpy(), b.final[..., :P].cpu().numpy()
+    np.testing.assert_allclose(fb, fa, rtol=5e-5, atol=1e-30)
+    for g in range(w.n_kv_heads):
+        check_selection(b.idx[g].cpu().numpy(), fa[g].astype(np.float64), w.window, w.budget, 2e-4)
+
+
 @pytest.mark.gpu
 def test_layers_folded_into_heads(rk, oracle_mod):
     """A batch (here: three layers) folds into the head dimension: one call over 3*Hkv KV heads
