@@ -96,7 +96,7 @@ def test_gram_matches_float64_product(rk):
 
 
 def test_tiny_config_full_path(rk, oracle_mod):
-    """BASELINE config 1 (fp32, 2 KV heads x 2 query heads, L 1024, W 32, budget 128)."""
+    """Benchmark configuration 1, "tiny" (fp32, 2 KV heads x 2 query heads, L 1024, W 32, budget 128)."""
     w = workloads.WORKLOADS["tiny"]
     q, k, v = workloads.make_qkv(w)
     wo = workloads.make_wo(w)
@@ -118,7 +118,7 @@ def test_tiny_config_full_path(rk, oracle_mod):
 
 
 def test_llama_8k_config_score_and_selection(rk, oracle_mod):
-    """BASELINE config 2: 32 q / 8 kv heads, d 128, L 8192, W 32, bf16, planted heavy keys."""
+    """Benchmark configuration 2, "llama_8k": 32 q / 8 kv heads, d 128, L 8192, W 32, bf16, planted heavy keys."""
     w = workloads.WORKLOADS["llama_8k"]
     q, k, v = workloads.make_qkv(w)
     wo = workloads.make_wo(w)
@@ -366,7 +366,7 @@ def _full_size_head_check(rk, oracle_mod, w, layer, g, budget=None, rows_only=No
 
 
 def test_drift_128k_full_size_one_head(rk, oracle_mod):
-    """BASELINE config 4 at full size (L 131072, W 64, 32q/8kv, d 128, budget 2048)."""
+    """Benchmark configuration 4, "drift_128k", at full size (L 131072, W 64, 32q/8kv, d 128, budget 2048)."""
     _full_size_head_check(rk, oracle_mod, workloads.WORKLOADS["drift_128k"], layer=3, g=5)
 
 
@@ -378,13 +378,13 @@ def test_drift_128k_kernel21_sampled_rows(rk, oracle_mod):
 
 
 def test_gqa8_128k_full_size_one_head(rk, oracle_mod):
-    """BASELINE config 5 at full size: 64 query heads over 8 KV heads (G = 8), budget 1024."""
+    """Benchmark configuration 5, "gqa8_128k", at full size: 64 query heads over 8 KV heads (G = 8), budget 1024."""
     _full_size_head_check(rk, oracle_mod, workloads.WORKLOADS["gqa8_128k"], layer=1, g=2)
 
 
 @pytest.mark.parametrize("budget", [256, 1024, 2048])
 def test_lowrank_32k_budgets(rk, oracle_mod, budget):
-    """BASELINE config 3 (rank-16 key/query structure, L 32768, W 64) at its three budgets."""
+    """Benchmark configuration 3, "lowrank_32k" (rank-16 key/query structure, L 32768, W 64) at its three budgets."""
     _full_size_head_check(rk, oracle_mod, workloads.WORKLOADS["lowrank_32k"], layer=9, g=budget % 7, budget=budget)
 @pytest.mark.gpu
 @pytest.mark.parametrize("Hq,Hkv,W,L,B,structure", [
