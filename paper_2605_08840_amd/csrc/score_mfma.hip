@@ -417,26 +417,33 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
   const int s16 = l & 15;
   const int vrow = 4 * hf + (s16 >> 2), vcol = 16 * ((l >> 4) & 1) + 4 * (s16 & 3);
 
-  // P.V of one tile: O^T[c, row] += V^T P^T
+  // P.V of one tile: O^T[c, row] += V^T P^T.  The transposing reads of the next 16-key group are
+  // issued before the MFMAs of the current one, so the matrix cores do not wait one LDS round
+  // trip per MFMA.
   auto accumulate = [&](const uint16_t* vt) {
+    auto fetch = [&](int grp, bf16x8 (&av)[CB]) {       // grp = 2 mb + kg2
+      const int r0 = 16 * grp + vrow;
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int kg2 = 0; kg2 < 2; ++kg2) {
-        const int r0 = 32 * mb + 16 * kg2 + vrow;
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-          const int col = 32 * cb + vcol;
-          const uint16_t* base = vt + RingV::off(r0, col >> 3) + (col & 7);   // rows r0 and r0+8 share the XOR key
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(base));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(base + 8 * D));
-          union { s16x8 s; bf16x8 b; } a;
-          a.s = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[cb] = MFMA(a.b, pv[mb][kg2], oacc[cb]);
-        }
+      for (int cb = 0; cb < CB; ++cb) {
+        const int col = 32 * cb + vcol;
+        const uint16_t* base = vt + RingV::off(r0, col >> 3) + (col & 7);   // rows r0 and r0+8 share the XOR key
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(base));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(base + 8 * D));
+        union { s16x8 s; bf16x8 b; } a;
+        a.s = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        av[cb] = a.b;
       }
+    };
+    bf16x8 av[2][CB];
+    fetch(0, av[0]);
+#pragma unroll
+    for (int grp = 0; grp < 4; ++grp) {
+      if (grp + 1 < 4) fetch(grp + 1, av[(grp + 1) & 1]);
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) oacc[cb] = MFMA(av[grp & 1][cb], pv[grp >> 1][grp & 1], oacc[cb]);
+    }
   };
 
   if (ntiles > 0) {
