@@ -164,7 +164,10 @@ struct TileRing {
     }
   }
 };
-__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+// Workgroup barrier without the full fence of __syncthreads (which would also wait for the
+// asynchronous tile copies in flight): the wavefront's own LDS accesses are drained first, the
+// copies are accounted for separately with wait_vm.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   static_assert(N == 0 || N == 1 || N == 2 || N == 3 || N == 4 || N == 5 || N == 8, "add the literal");
