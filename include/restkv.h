@@ -68,7 +68,7 @@ typedef struct restkv_params {
   float   ema_alpha;     /* alpha of the EMA recursion: weight of the newest query     */
   int32_t base_window;   /* k: odd >= 1, the fixed kernel size of App. B               */
   int32_t adaptive;      /* 1: W_s and gamma_shift from D_front/D_rear ; 0: W_s=k, 0   */
-  float   beta;          /* scaling factor of the adaptive window (> 0 when adaptive)  */
+  float   beta;          /* scaling factor of the adaptive window (> L / 2^30 when adaptive) */
   int32_t reserved;      /* must be 0                                                  */
   int64_t q_stride_h;    /* elements between query heads  (0: W*d)                     */
   int64_t q_stride_t;    /* elements between window queries (0: d)                     */
@@ -107,6 +107,10 @@ int restkv_prepare_wo(const restkv_params* p, const float* w_o, int64_t d_model,
  *   gram  [Hq, d, d] from restkv_prepare_wo (any symmetric matrices), or NULL for
  *         W_O W_O^T = identity.
  * Columns n >= P of `score` are not written.
+ * The squared distance is evaluated as z M z^T - 2 (z M) v_n^T + v_n M v_n^T in FP32; when the
+ * three terms cancel (v_n W_O within a few 1e-3 of z W_O, relative to their norms) the rounding
+ * residue of that sum enters by its magnitude (matrix-core kernels) or clamped at zero (FP32
+ * kernels): the result then is a small non-negative number where the exact one is near zero.
  */
 int restkv_score(const restkv_params* p, const void* q, const void* k, const void* v,
                  const float* gram, float* score, void* workspace, size_t workspace_bytes,

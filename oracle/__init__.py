@@ -18,15 +18,23 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "restkv_oracle.c")
-_LIB = os.path.join(_HERE, "librestkv_oracle.so")
+# RESTKV_ORACLE_SANITIZE=1: the oracle is built with clang under AddressSanitizer + UBSan into a
+# library of its own (the process that loads it must preload the sanitizer runtime)
+_SAN = os.environ.get("RESTKV_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "librestkv_oracle_san.so" if _SAN else "librestkv_oracle.so")
+_CLANG = "/opt/rocm/lib/llvm/bin/clang"
 _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc (OpenMP); returns the library path."""
+    """Compile the C oracle (gcc, OpenMP); returns the library path."""
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
-        cmd = ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        if _SAN:
+            cmd = [_CLANG, "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                   "-shared-libsan", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        else:
+            cmd = ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

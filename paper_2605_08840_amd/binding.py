@@ -15,7 +15,8 @@ from typing import Optional
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "librestkv.so")
+# RESTKV_LIB names another build of the same library (the host-sanitized one of the CPU tests)
+LIB_PATH = os.environ.get("RESTKV_LIB") or os.path.join(_PKG, "librestkv.so")
 
 RESTKV_F32 = 0
 RESTKV_BF16 = 1
@@ -68,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.restkv_timing_enable.argtypes = [ctypes.c_int]
         L.restkv_stage_name.restype = ctypes.c_char_p
         L.restkv_stage_name.argtypes = [ctypes.c_int]
+        L.restkv_debug_force_fp32.argtypes = [ctypes.c_int]
+        L.restkv_debug_force_fp32.restype = ctypes.c_int
         for f in ("restkv_timing_enable", "restkv_timing_read", "restkv_prepare_wo", "restkv_score", "restkv_smooth", "restkv_select",
                   "restkv_compact", "restkv_version", "restkv_score_smooth", "restkv_smooth_b", "restkv_select_b"):
             getattr(L, f).restype = ctypes.c_int
@@ -190,6 +193,10 @@ def restkv_timing_read():
     cnt = (ctypes.c_int64 * N_STAGES)()
     _chk(lib().restkv_timing_read(ms, cnt, N_STAGES), "restkv_timing_read")
     return {lib().restkv_stage_name(s).decode(): (ms[s], cnt[s]) for s in range(N_STAGES)}
+
+
+def restkv_debug_force_fp32(on: bool):
+    _chk(lib().restkv_debug_force_fp32(int(bool(on))), "restkv_debug_force_fp32")
 
 
 def restkv_version() -> int:

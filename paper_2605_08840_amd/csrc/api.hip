@@ -15,6 +15,8 @@ int resolve(const restkv_params* p, Prob* o) {
   if (p->reserved != 0) return RESTKV_EINVAL;
   if (!(p->ema_alpha >= 0.f && p->ema_alpha <= 1.f)) return RESTKV_EINVAL;
   if (p->adaptive && !(p->beta > 0.f)) return RESTKV_EINVAL;
+  // |D_front - D_rear| < L, so floor(|x| / beta) stays a 32-bit integer with room to spare
+  if (p->adaptive && (double)p->seq_len / (double)p->beta >= 1073741824.0) return RESTKV_EINVAL;
   if (!(p->scale >= 0.f) || isinf(p->scale)) return RESTKV_EINVAL;
   if (p->head_dim != 64 && p->head_dim != 128) return RESTKV_EUNSUPPORTED;
   if (p->dtype != RESTKV_F32 && p->dtype != RESTKV_BF16) return RESTKV_EUNSUPPORTED;
@@ -200,7 +202,10 @@ int restkv_score_smooth(const restkv_params* p, const void* q, const void* k, co
   const SmoothWs lm = smooth_ws(pb);
   hipStream_t st = (hipStream_t)stream;
   if (g_force_fp32 || !fused_eligible(pb, q, k, v)) {
-    // same result from the two separate calls (they use the workspace one after the other)
+    // same result from the two separate calls (they use the workspace one after the other);
+    // both sizes are checked first so that nothing is enqueued when the second call would fail
+    rc = check_ws(workspace, workspace_bytes, ls.bytes > lm.bytes ? ls.bytes : lm.bytes);
+    if (rc) return rc;
     rc = restkv_score(p, q, k, v, gram, score, workspace, workspace_bytes, stream);
     if (rc) return rc;
     return restkv_smooth(p, score, ema, final_score, aws_info, aws_d, workspace, workspace_bytes, stream);

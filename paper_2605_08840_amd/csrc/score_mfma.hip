@@ -352,7 +352,8 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
 
 // ------------------------------------------------------------------------------------------
 // Attention pass, pipelined: per key split, champion-excluded online softmax statistics and
-// A.V sums (same arithmetic and outputs as k_attn_mfma).  grid (S, row blocks, Hkv), 512 threads.
+// A.V sums (outputs: the per-split statistics described in score_common.hpp).
+// grid (S, row blocks, Hkv), 512 threads.
 //
 // K tiles travel through a 4-deep, V tiles through a 5-deep asynchronous LDS ring.  A step t has a
 // matrix half (P.V of tile t-1, then Q.K of tile t: 48 MFMAs) and a vector half (softmax

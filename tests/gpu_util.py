@@ -85,3 +85,42 @@ def check_selection(idx_gpu, ref_final, W, B, margin):
         assert abs(ref_final[n] - tau) <= margin * abs(tau) + 1e-300, \
             f"index {n}: oracle score {ref_final[n]} is not within {margin} of the threshold {tau}"
     return len(diff)
+
+
+def topb_sum_bounds(ref_row, tol_row, bt):
+    """Range of the index sum of the top-`bt` entries of a row whose every entry is only known
+    to lie within ref +- tol.  An entry is surely selected when its lower bound lies above the
+    (bt+1)-th largest upper bound, surely not when its upper bound lies below the bt-th largest
+    lower bound; the rest of the selection may be any subset of the remaining entries.
+    Returns (lowest possible sum, highest possible sum, number of undecided entries)."""
+    P = ref_row.shape[0]
+    if bt >= P:
+        s = P * (P - 1) // 2
+        return s, s, 0
+    lo, hi = ref_row - tol_row, ref_row + tol_row
+    tau_lo = np.partition(lo, P - bt)[P - bt]              # bt-th largest lower bound
+    tau_hi = np.partition(hi, P - bt - 1)[P - bt - 1]      # (bt+1)-th largest upper bound
+    sure = lo > tau_hi
+    amb = np.nonzero((hi >= tau_lo) & ~sure)[0]            # ascending positions
+    need = bt - int(sure.sum())
+    assert 0 <= need <= amb.size, (need, amb.size)
+    base = int(np.nonzero(sure)[0].sum())
+    return base + int(amb[:need].sum()), base + int(amb[amb.size - need:].sum()), int(amb.size)
+
+
+def drift_bounds(Ig, tol, budget, W):
+    """Intervals that D_front and D_rear of a head must fall in when its raw scores are only
+    known to +- tol (Sec. 3.3: mean index of the per-query top-B over each half of the window).
+    Returns ((front lo, front hi), (rear lo, rear hi))."""
+    P = Ig.shape[1]
+    bt = min(budget, P)
+    nf = W // 2
+    fl = fh = rl = rh = 0
+    for i in range(W):
+        a, b, _ = topb_sum_bounds(Ig[i], tol[i], bt)
+        if i < nf:
+            fl, fh = fl + a, fh + b
+        else:
+            rl, rh = rl + a, rh + b
+    den_f, den_r = float(bt) * max(nf, 1), float(bt) * (W - nf)
+    return (fl / den_f, fh / den_f), (rl / den_r, rh / den_r)

@@ -46,7 +46,8 @@ def test_workspace_bytes(rk):
     big = good(rk, n_q_heads=32, n_kv_heads=8, head_dim=128, seq_len=131072, window=64, budget=2048, dtype="bf16")
     assert rk.restkv_workspace_bytes(big) > 32 * 131008 * 4      # holds v M v^T for every head
     for bad in (dict(budget=32), dict(budget=2000), dict(n_q_heads=5), dict(window=0),
-                dict(window=1024), dict(base_window=4), dict(ema_alpha=1.5), dict(beta=0.0)):
+                dict(window=1024), dict(base_window=4), dict(ema_alpha=1.5), dict(beta=0.0),
+                dict(beta=1e-7)):          # floor(|x| / beta) would leave the 32-bit range
         assert rk.restkv_workspace_bytes(good(rk, **bad)) == 0, bad
 
 

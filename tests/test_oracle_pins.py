@@ -320,3 +320,62 @@ def test_run_layer_invariants_tiny(oracle_mod):
         assert np.all(np.diff(idx) > 0) and np.array_equal(idx[-6:], np.arange(P, 160))
         np.testing.assert_array_equal(out["k_out"][g], k.numpy()[g][idx])
         np.testing.assert_array_equal(out["v_out"][g], v.numpy()[g][idx])
+
+
+def test_smooth_head_planted_drift_hand_derived_window(oracle_mod):
+    """The composition EMA -> D_front/D_rear -> W_s, gamma -> Eq. (final_ei) on a planted drift.
+    Front queries (0, 1) have their top-3 at positions 10, 20, 30 (D_front = 20), rear queries
+    (2, 3) at 110, 120, 130 (D_rear = 120): x = -100.  With beta = 40: floor(2.5) = 2, so
+    W_s = k + 4 = 7 for k = 3, and gamma = floor(-2.5) + 1 = -2 (Sec. 3.3).  The final score is
+    then the mean of the EMA over positions n - 5 .. n + 1, written out here directly."""
+    W, P, B, alpha = 4, 200, 3, 0.3
+    Ig = rng(31).random((W, P)) * 0.01
+    Ig[:2, [10, 20, 30]] = [[3.0, 2.0, 1.0], [1.0, 2.0, 3.0]]
+    Ig[2:, [110, 120, 130]] = [[5.0, 5.0, 5.0], [4.0, 6.0, 5.0]]
+    sm = oracle_mod.smooth_head(Ig, alpha, 40.0, 3, True, B)
+    assert (sm["d_front"], sm["d_rear"]) == (20.0, 120.0)
+    assert (sm["w_s"], sm["gamma"]) == (7, -2)
+    wts = np.array([(1 - alpha) ** 3, alpha * (1 - alpha) ** 2, alpha * (1 - alpha), alpha])
+    e = wts @ Ig
+    np.testing.assert_allclose(sm["ema"], e, rtol=1e-13)
+    pad = np.concatenate([np.zeros(8), e, np.zeros(8)])
+    want = np.array([pad[8 + n - 5: 8 + n + 2].sum() / 7.0 for n in range(P)])
+    np.testing.assert_allclose(sm["final"], want, rtol=1e-12, atol=1e-16)
+    # without the adaptive window: kernel k, no shift
+    sm0 = oracle_mod.smooth_head(Ig, alpha, 40.0, 3, False, B)
+    assert (sm0["w_s"], sm0["gamma"]) == (3, 0)
+    want0 = np.array([pad[8 + n - 1: 8 + n + 2].sum() / 3.0 for n in range(P)])
+    np.testing.assert_allclose(sm0["final"], want0, rtol=1e-12, atol=1e-16)
+
+
+def test_run_layer_adaptive_composition(oracle_mod):
+    """run_layer with the adaptive window on: every stage's output is what the next stage's
+    definition gives when applied to it with independent numpy code."""
+    import workloads
+    w = workloads.small_case(Hq=4, Hkv=2, d=16, L=400, W=8, B=40, D=20, k=3, beta=7.0, alpha=0.3)
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    out = oracle_mod.run_layer(q.numpy(), k.numpy(), v.numpy(), wo.numpy(), window=8, budget=40,
+                               alpha=0.3, beta=7.0, base_k=3, adaptive=True)
+    P, W, B = 392, 8, 40
+    wts = np.array([0.7 ** 7] + [0.3 * 0.7 ** (7 - i) for i in range(1, 8)])
+    seen = set()
+    for g in range(2):
+        s = out["score"][g]
+        np.testing.assert_allclose(out["ema"][g], wts @ s, rtol=1e-12)
+        top = np.argsort(-s, axis=1, kind="stable")[:, :B]
+        df, dr = top[:4].mean(), top[4:].mean()
+        assert abs(out["d_front"][g] - df) < 1e-9 and abs(out["d_rear"][g] - dr) < 1e-9
+        x = df - dr
+        ws = 3 + 2 * int(np.floor(abs(x) / 7.0))
+        gm = int(np.floor(x / 7.0)) + (0 if x > 0 else 1)
+        assert (out["w_s"][g], out["gamma"][g]) == (ws, gm)
+        seen.add((ws, gm))
+        e = out["ema"][g]
+        pad = np.concatenate([np.zeros(P), e, np.zeros(P)])
+        want = np.array([pad[P + n + gm - ws // 2: P + n + gm + ws // 2 + 1].sum() / ws for n in range(P)])
+        np.testing.assert_allclose(out["final"][g], want, rtol=1e-12, atol=1e-18)
+        keep = np.sort(np.argsort(-out["final"][g], kind="stable")[:B - W])
+        np.testing.assert_array_equal(out["idx"][g], np.concatenate([keep, np.arange(P, P + W)]))
+        np.testing.assert_array_equal(out["k_out"][g], k.numpy()[g][out["idx"][g]])
+    assert any(ws > 3 or gm != 0 for ws, gm in seen), seen       # the window did adapt
