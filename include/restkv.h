@@ -181,6 +181,22 @@ int restkv_select_b(const restkv_params* p, const float* final_score, const int3
                     int32_t* idx, void* workspace, size_t workspace_bytes, restkv_stream_t stream);
 
 /*
+ * restkv_select for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as
+ * restkv_select (same kernels); the scratch is an array inside the library's device image, one
+ * copy per GPU that lives until the process ends (restkv_select_static_capacity() bytes, 4 MiB).
+ * Returns RESTKV_EWORKSPACE, with nothing enqueued, when the shape needs more than that: about
+ * 32 KiB per KV head plus 4 bytes per 4096 prefix positions and KV head (120 KV heads fit at
+ * 128k tokens).  The call allocates nothing and frees nothing (the first call on a GPU looks up
+ * the array's address once).  Every call on a GPU uses that GPU's
+ * one array: calls that overlap in time on one GPU (different streams or host threads) race;
+ * calls ordered on one stream are safe, and each call clears what it needs cleared itself.
+ */
+int restkv_select_static(const restkv_params* p, const float* final_score, int32_t* idx,
+                         restkv_stream_t stream);
+size_t restkv_select_static_capacity(void);
+
+/*
  * Gather of the kept rows (Eq. topk): k_out[g,j,:] = k[g, idx[g,j], :], same for v.
  *   idx [Hkv, B] int32 in, entries in [0, L) (an entry outside is written as zeros);
  *   k_out, v_out [Hkv, B, d] out, contiguous, dtype of the inputs.

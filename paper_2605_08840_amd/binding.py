@@ -62,6 +62,10 @@ def lib() -> ctypes.CDLL:
         L.restkv_select.argtypes = [P, vp, vp, vp, sz, vp]
         L.restkv_smooth_b.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.restkv_select_b.argtypes = [P, vp, vp, vp, vp, sz, vp]
+        L.restkv_select_static.argtypes = [P, vp, vp, vp]
+        L.restkv_select_static.restype = ctypes.c_int
+        L.restkv_select_static_capacity.restype = sz
+        L.restkv_select_static_capacity.argtypes = []
         L.restkv_compact.argtypes = [P, vp, vp, vp, vp, vp, vp]
         L.restkv_strerror.restype = ctypes.c_char_p
         L.restkv_strerror.argtypes = [ctypes.c_int]
@@ -165,6 +169,15 @@ def restkv_select(p, final, idx, workspace, stream=None):
     wp, wn = _ws(workspace)
     _chk(lib().restkv_select(ctypes.byref(p), _ptr(final), _ptr(idx), wp, wn, _stream(stream)),
          "restkv_select")
+
+
+def restkv_select_static(p, final, idx, stream=None):
+    _chk(lib().restkv_select_static(ctypes.byref(p), _ptr(final), _ptr(idx), _stream(stream)),
+         "restkv_select_static")
+
+
+def restkv_select_static_capacity() -> int:
+    return int(lib().restkv_select_static_capacity())
 
 
 def restkv_compact(p, k, v, idx, k_out, v_out, stream=None):

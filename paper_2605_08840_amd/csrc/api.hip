@@ -252,6 +252,17 @@ int restkv_select_b(const restkv_params* p, const float* final_score, const int3
   return select_impl(p, final_score, head_budget, idx, workspace, workspace_bytes, stream);
 }
 
+int restkv_select_static(const restkv_params* p, const float* final_score, int32_t* idx,
+                         restkv_stream_t stream) {
+  Prob pb;
+  int rc = resolve(p, &pb);
+  if (rc) return rc;
+  if (!final_score || !idx) return RESTKV_EINVAL;
+  return launch_select_static(pb, final_score, idx, (hipStream_t)stream);
+}
+
+size_t restkv_select_static_capacity(void) { return select_static_capacity(); }
+
 int restkv_compact(const restkv_params* p, const void* k, const void* v, const int32_t* idx,
                    void* k_out, void* v_out, restkv_stream_t stream) {
   Prob pb;
@@ -266,7 +277,7 @@ const char* restkv_strerror(int code) {
     case RESTKV_OK: return "ok";
     case RESTKV_EINVAL: return "invalid argument (null pointer, inconsistent shape or budget outside (W, L])";
     case RESTKV_EUNSUPPORTED: return "unsupported configuration (head_dim must be 64 or 128; dtype f32 or bf16)";
-    case RESTKV_EWORKSPACE: return "workspace missing, not 256-byte aligned or smaller than restkv_workspace_bytes()";
+    case RESTKV_EWORKSPACE: return "workspace missing, not 256-byte aligned or smaller than restkv_workspace_bytes() (restkv_select_static: the problem needs more than the library's static scratch)";
     case RESTKV_EHIP: return "HIP runtime error at kernel launch";
     default: return "unknown error code";
   }

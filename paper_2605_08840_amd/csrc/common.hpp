@@ -88,6 +88,9 @@ int launch_smooth_fused_tail(const Prob& pb, const float* score, const float* em
                              const FusedPtrs& fp, int nchunks, hipStream_t st);
 size_t select_ws_bytes(const Prob& pb);
 int launch_select(const Prob& pb, const float* fin, int32_t* idx, char* ws, hipStream_t st);
+// the same with the library's own static scratch (RESTKV_EWORKSPACE beyond its capacity)
+size_t select_static_capacity();
+int launch_select_static(const Prob& pb, const float* fin, int32_t* idx, hipStream_t st);
 int launch_compact(const Prob& pb, const void* k, const void* v, const int32_t* idx, void* k_out,
                    void* v_out, hipStream_t st);
 

@@ -8,11 +8,36 @@
 //   fallback: a head whose bracket missed is searched with the exact radix select
 //   count   : per chunk, number of selected entries
 //   emit    : per chunk, ordered write at the offset given by the counts of the earlier chunks
+#include <mutex>
+
 #include "rowselect.hpp"
 
 namespace restkv {
 
 namespace {
+
+// Scratch of restkv_select_static: one array per GPU, held until the process ends.  Host code
+// never passes the array's name to a kernel: its device address is looked up once per device.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+char* g_scratch_ptr[MAX_DEVICES];    // device address of `scratch` on each GPU, nullptr until asked for
+
+// Device address of the current GPU's copy of `scratch` (RESTKV_EHIP if the runtime refuses).
+int static_scratch(char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return RESTKV_EHIP;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return RESTKV_EHIP;
+    g_scratch_ptr[dev] = (char*)ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return RESTKV_OK;
+}
 
 constexpr int SCH = 4096;            // positions per chunk
 constexpr int SCAP = 4096;           // candidates kept per head
@@ -278,6 +303,16 @@ int launch_select(const Prob& pb, const float* fin, int32_t* idx, char* ws, hipS
   RK_LAUNCH(ST_SELECT, st, k_sel_count, dim3(nch, pb.Hkv), dim3(256), 0, st, pb, fin, w, nch);
   RK_LAUNCH(ST_SELECT, st, k_sel_emit, dim3(nch, pb.Hkv), dim3(256), 0, st, pb, fin, w, nch, idx);
   return hip_status();
+}
+
+size_t select_static_capacity() { return STATIC_SCRATCH_BYTES; }
+
+int launch_select_static(const Prob& pb, const float* fin, int32_t* idx, hipStream_t st) {
+  if (select_ws_bytes(pb) > STATIC_SCRATCH_BYTES) return RESTKV_EWORKSPACE;
+  char* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc) return rc;
+  return launch_select(pb, fin, idx, ws, st);
 }
 
 }  // namespace restkv
