@@ -87,9 +87,7 @@ SmoothWs smooth_ws(const Prob& pb) {
   w.thr = take(rows * 8);
   w.cnt_hi = take(rows * 4);
   w.sum_hi = take(rows * 8);
-  w.ncand = take(rows * 4);
-  w.cand_val = take(rows * 4096 * 4);
-  w.cand_idx = take(rows * 4096 * 4);
+  w.cmask = take(rows * (size_t)((pb.P + 1023) / 1024) * 64 * 2);
   w.bytes = off;
   return w;
 }

@@ -39,8 +39,9 @@ struct SmoothWs {
   size_t rowsum;         // [Hkv*W] u64 index sums of the per-query top-B
   size_t ema;            // [Hkv*ld] f32 (used when the caller passes ema == NULL)
   size_t thr;            // [Hkv*W] float2 bracket {lo, hi} of each row's top-B threshold
-  size_t cnt_hi, sum_hi, ncand;   // [Hkv*W] u32 / u64 / u32
-  size_t cand_val, cand_idx;      // [Hkv*W, 4096] f32 / i32 candidates inside the bracket
+  size_t cnt_hi, sum_hi;          // [Hkv*W] u32 / u64: entries above the bracket, their position sum
+  size_t cmask;                   // [Hkv*W, ceil(P/1024), 64] u16: entries inside the bracket, one bit
+                                  // string per lane of the scan
   size_t bytes;
 };
 // extra scratch of the fused score + smoothing call (after the two layouts above)

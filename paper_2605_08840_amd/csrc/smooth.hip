@@ -15,8 +15,6 @@ namespace {
 
 constexpr int CAND_CAP = 4096;      // candidates kept per (head, query) row
 constexpr int SMP_NS = 8192;        // samples per row for the bracket
-constexpr int RG = 4;               // rows in flight per thread of the fused pass (multiple of 4)
-constexpr int NPB = 1024;           // prefix positions per workgroup of the fused pass
 
 // Bracket of the top-min(B,P) threshold of one (head, query) row from a sample of the row.
 // thr[row] = {lo, hi}: the threshold lies in (lo, hi] unless the sample misled us (then the
@@ -25,13 +23,12 @@ constexpr int NPB = 1024;           // prefix positions per workgroup of the fus
 __global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __restrict__ score,
                                                         float2* __restrict__ thr,
                                                         uint32_t* __restrict__ cnt_hi,
-                                                        unsigned long long* __restrict__ sum_hi,
-                                                        uint32_t* __restrict__ ncand) {
+                                                        unsigned long long* __restrict__ sum_hi) {
   __shared__ CountSmem cs;
   const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
   const float* row = score + (int64_t)r * pb.ld;
   const int k = min(head_budget(pb, g), pb.P);
-  if (threadIdx.x == 0) { cnt_hi[r] = 0; sum_hi[r] = 0ull; ncand[r] = 0; }
+  if (threadIdx.x == 0) { cnt_hi[r] = 0; sum_hi[r] = 0ull; }
   if (k >= pb.P) {                       // every prefix position is taken: nothing to search
     if (threadIdx.x == 0) thr[r] = make_float2(INFINITY, INFINITY);
     return;
@@ -74,250 +71,161 @@ __global__ __launch_bounds__(256) void k_bracket_samples(Prob pb, const float* _
     thr[r] = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
 }
 
-// Fused single read of the raw score: EMA over the window queries (the recursion of Sec. 3.3:
-// first query as is, every later one enters with weight alpha) and, per (head, query) row,
-// the count / position sum of the entries above the bracket and the list of entries inside it.
-// A workgroup owns NPB prefix positions of one head for all W queries; a thread owns 4 of them.
-// While streaming, a thread works alone (no cross-lane work, no scalar-ALU ballots): per group
-// of RG rows it packs two LDS words (per row: 3-bit count and 3-bit element-offset sum of its
-// entries above the bracket; 4-bit mask of its entries inside it) and keeps the values of the
-// latter in a private LDS list.  After every ROWS_BLK rows the workgroup turns around:
-//   * thread j = (row, quarter of the workgroup's threads) walks the 64 packed words of its
-//     quarter: it adds up the statistics and leaves every thread's running candidate offset;
-//     the four quarters of a row meet through lane shuffles and one thread per row issues the
-//     row's global atomics (statistics, space in the row's candidate list);
-//   * every thread then writes its own candidates to their final places.  A wavefront whose
-//     private lists did not suffice (a dense cluster of candidates) re-reads its rows instead.
-// grid (ceil(P/NPB), Hkv), 256 threads.
-constexpr int ROWS_BLK = 32;        // rows per turn-around of the fused pass
-constexpr int CAPT = 12;            // private candidate values per thread between turn-arounds
+// Fused single read of the raw score: EMA over the window queries and, per (head, query) row,
+// the count / position sum of the entries above the row's bracket and a bit mask of the entries
+// inside it (the candidates among which the finishing kernel finds the exact threshold).
+//
+// A WAVEFRONT owns EW_POS consecutive prefix positions of one head for all W rows; a lane owns
+// four 16-byte quads of them (quad j of lane l: positions wbase + 256 j + 4 l ..+3, so that a
+// wave-load is one contiguous KiB).  There is no workgroup barrier, no LDS and no cross-wavefront
+// state:
+//   * EMA as the weighted sum the recursion of Sec. 3.3 unrolls to: one FMA per element with a
+//     wave-uniform weight (first query (1-a)^(W-1), query i > 0: a (1-a)^(W-1-i));
+//   * per element and bracket end, ONE compare and ONE add-with-carry shift the outcome into a
+//     per-lane bit string (16 elements per row: bit 15 - k is element k); the count and the
+//     position sum of the entries above the bracket come from population counts of masked bit
+//     strings, one packed wave reduction per row, and lane (row % 64) keeps the row's totals
+//     until the block of 64 rows ends (two atomics per row, wavefront and block);
+//   * the entries inside the bracket leave as what they already are: the lane's 16-bit string
+//     "above the lower end and not above the upper end", one 128-byte store per wavefront and
+//     row into cmask [row][wavefront][lane].  The finishing kernel expands a row's masks into
+//     positions and fetches those few values itself.
+// EPF rows are in flight per lane, so 16 KiB per wavefront are on their way while a row is
+// processed.  grid (ceil(P / (4 EW_POS)), Hkv), 256 threads.
+constexpr int EW_POS = 1024;        // prefix positions per wavefront
+constexpr int EW_NE = EW_POS / 64;  // elements per lane and row (16 = four quads)
+constexpr int EPF = 4;              // rows in flight
 
+// bits = 2 bits + (x > t): one compare, one add with carry (t wave-uniform)
+__device__ __forceinline__ void shift_in_gt(uint32_t& bits, float x, float t) {
+  asm("v_cmp_lt_f32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(bits) : "v"(x), "s"(t) : "vcc");
+}
+
+// weight of window query i in the temporal smoothing (wave-uniform)
+__device__ __forceinline__ float temporal_weight(const Prob& pb, int i) {
+  const int n = pb.W - 1 - i;                      // queries after this one
+  const float b = 1.0f - pb.alpha;
+  const float decay = n == 0 ? 1.0f : exp2f((float)n * log2f(b));    // b = 0: 2^-inf = 0
+  return (i == 0 ? 1.0f : pb.alpha) * decay;
+}
+
+// position of element k (bit 15 - k of a lane's string) of lane l of the wavefront that starts at wbase
+__device__ __forceinline__ int scan_position(int wbase, int l, int k) { return wbase + 256 * (k >> 2) + 4 * l + (k & 3); }
+__host__ __device__ inline int scan_waves(int P) { return (P + EW_POS - 1) / EW_POS; }
+
+template <bool VEC>
 __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restrict__ score,
                                                   float* __restrict__ ema, const float2* __restrict__ thr,
                                                   uint32_t* __restrict__ cnt_hi,
                                                   unsigned long long* __restrict__ sum_hi,
-                                                  uint32_t* __restrict__ ncand,
-                                                  float* __restrict__ cand_val, int* __restrict__ cand_idx,
-                                                  int vec) {
-  constexpr int PG = 4;                          // rows per packed LDS word
-  constexpr int NGRP = ROWS_BLK / PG;
-  __shared__ __attribute__((aligned(16))) uint32_t pk0[NGRP][256];            // per thread and row group: RG x (count:3 | offset sum:3)
-  __shared__ __attribute__((aligned(16))) uint32_t pk1[NGRP][256];            // RG x 4-bit masks of the entries inside the bracket
-  __shared__ __attribute__((aligned(16))) uint8_t pk2[NGRP][PG][256];   // candidates of the row in earlier threads of the quarter
-  __shared__ float pval[CAPT][256];              // private lists of candidates, in stream order: value ...
-  __shared__ uint8_t pmeta[CAPT][256];           // ... and (row in block) * 4 + element
-  __shared__ uint32_t rbase[ROWS_BLK][4];        // first list position of each (row, quarter)
-  const int g = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
-  const int nb0 = blockIdx.x * NPB, n0 = nb0 + tid * 4;
+                                                  uint16_t* __restrict__ cmask) {
+  const int g = blockIdx.y, l = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // (a scalar for the compiler)
+  const int wg = blockIdx.x * 4 + wv;            // wavefront along the prefix
+  const int wbase = wg * EW_POS;
+  if (wbase >= pb.P) return;                     // no barrier anywhere below
+  const int nwt = scan_waves(pb.P);
   const float* s = score + (int64_t)g * pb.W * pb.ld;
-  const float a = pb.alpha, b = 1.0f - pb.alpha;
   const bool scan = pb.adaptive != 0;
-  int kp = 0;                        // candidates of this thread since the last turn-around
+  const bool tail = wbase + EW_POS > pb.P;       // some positions of this wavefront do not exist
+  const int last_quad = (pb.P - 1) & ~3;
 
-  // rows [rb0, rb0 + nrows) of the head have been streamed
-  auto turn_around = [&](int rb0, int nrows) {
-    __syncthreads();
-    {
-      const int rl = tid >> 2, qd = tid & 3;
-      const int itr = rl / PG, rr = rl % PG, sh0 = 6 * rr, sh1 = 4 * rr;
-      uint32_t cnt = 0, els = 0, wsum = 0, nc = 0;
-      if (rl < nrows) {
-        // Four threads' words per step (16-byte LDS reads; the four offset bytes leave as one
-        // word).  Lanes with the same row group and quarter read the same address; the 16
-        // (row group, quarter) pairs of a wavefront start their walk 16 bytes apart, so that no
-        // two of them meet in an LDS bank.
-        const int rot = ((lane >> 4) << 2) | (lane & 3);
-#pragma unroll 4
-        for (int tt = 0; tt < 16; ++tt) {
-          const int t4 = (tt + rot) & 15, src = 64 * qd + 4 * t4;
-          const uint4 a4 = *(const uint4*)&pk0[itr][src];
-          const uint4 m4 = *(const uint4*)&pk1[itr][src];
-          const uint32_t aw[4] = {a4.x, a4.y, a4.z, a4.w}, mw[4] = {m4.x, m4.y, m4.z, m4.w};
-          uint32_t offs = 0;
+  auto load_row = [&](int i, float (&x)[EW_NE]) {
+    const float* rp = s + (int64_t)i * pb.ld;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const uint32_t a0 = (aw[e] >> sh0) & 63u;
-            const uint32_t c = a0 & 7u;
-            cnt += c;
-            els += a0 >> 3;
-            wsum += c * (uint32_t)(4 * t4 + e);
-            offs |= (nc & 255u) << (8 * e);       // at most 252: a quarter holds 256 positions
-            nc += (uint32_t)__popc((mw[e] >> sh1) & 15u);
-          }
-          *(uint32_t*)&pk2[itr][rr][src] = offs;
-        }
-      }
-      // positions above the bracket seen by this quarter: thread t of it owns nb0 + 4 (64 qd + t) + el
-      const unsigned long long hs_own = (unsigned long long)cnt * (unsigned long long)(nb0 + 256 * qd) +
-                                        4ull * wsum + (unsigned long long)els;
-      unsigned long long hs = hs_own;
-      uint32_t cnt_tot = cnt, nc_tot = nc, nc_below = 0;
-      // the four quarters of a row sit in four adjacent lanes
+    for (int j = 0; j < EW_NE / 4; ++j) {
+      const int n = wbase + 256 * j + 4 * l;
+      if constexpr (VEC) {
+        // past the end: the last aligned quad of the row (inside its ld floats), masked below
+        const float4 v4 = *(const float4*)(rp + min(n, last_quad));
+        x[4 * j] = v4.x; x[4 * j + 1] = v4.y; x[4 * j + 2] = v4.z; x[4 * j + 3] = v4.w;
+      } else {
 #pragma unroll
-      for (int d = 1; d < 4; ++d) {
-        const int src = (lane & ~3) | ((lane + d) & 3);
-        const uint32_t onc = (uint32_t)__shfl((int)nc, src, 64);
-        cnt_tot += (uint32_t)__shfl((int)cnt, src, 64);
-        hs += ((unsigned long long)(uint32_t)__shfl((int)(hs_own >> 32), src, 64) << 32) |
-              (unsigned long long)(uint32_t)__shfl((int)(uint32_t)hs_own, src, 64);
-        nc_tot += onc;
-        if (((lane + d) & 3) < qd) nc_below += onc;
-      }
-      uint32_t base = 0;
-      if (qd == 0 && rl < nrows) {
-        const int row = g * pb.W + rb0 + rl;
-        if (cnt_tot) { atomicAdd(&cnt_hi[row], cnt_tot); atomicAdd(&sum_hi[row], hs); }
-        if (nc_tot) base = atomicAdd(&ncand[row], nc_tot);
-      }
-      base = (uint32_t)__shfl((int)base, lane & ~3, 64);
-      if (rl < nrows) rbase[rl][qd] = base + nc_below;
-    }
-    __syncthreads();
-    // every thread places its own candidates (the walk above visited this thread's quarter
-    // starting at the walker's rotation, which only permutes the order inside the list)
-    const int qd = tid >> 6;
-    if (__ballot(kp > CAPT) == 0ull) {
-      // Every private list of the wavefront is complete.  All LDS reads are issued up front
-      // (clamped, not branched around), only the stores are predicated: three LDS round trips
-      // and at most 2 CAPT store instructions per wavefront.
-      int mt[CAPT];
-      float pv[CAPT];
-#pragma unroll
-      for (int k = 0; k < CAPT; ++k) { mt[k] = pmeta[k][tid]; pv[k] = pval[k][tid]; }
-      uint32_t pos[CAPT];
-#pragma unroll
-      for (int k = 0; k < CAPT; ++k) {
-        const int rl = k < kp ? mt[k] >> 2 : 0;
-        pos[k] = rbase[rl][qd] + pk2[rl / PG][rl % PG][tid];
-      }
-      int prev = -1;
-      uint32_t run = 0;
-#pragma unroll
-      for (int k = 0; k < CAPT; ++k) {
-        const int rl = mt[k] >> 2;
-        run = rl == prev ? run + 1u : 0u;          // this thread's earlier candidates of the same row
-        prev = rl;
-        const uint32_t ps = pos[k] + run;
-        if (k < kp && ps < (uint32_t)CAND_CAP) {
-          const int64_t o = (int64_t)(g * pb.W + rb0 + rl) * CAND_CAP + ps;
-          cand_val[o] = pv[k];
-          cand_idx[o] = n0 + (mt[k] & 3);
-        }
-      }
-    } else {
-      // a dense cluster: the wavefront re-reads its rows (coalesced, two row groups = 8 rows per
-      // round trip) and walks its masks
-      for (int it0 = 0; it0 * PG < nrows; it0 += 2) {
-        float x4[2 * PG][4];
-#pragma unroll
-        for (int q = 0; q < 2 * PG; ++q) {
-          const int rl = min(it0 * PG + q, nrows - 1);
-          const float* rp = s + (int64_t)(rb0 + rl) * pb.ld + n0;
-#pragma unroll
-          for (int el = 0; el < 4; ++el) x4[q][el] = n0 + el < pb.P ? rp[el] : 0.f;
-        }
-#pragma unroll
-        for (int q = 0; q < 2 * PG; ++q) {
-          const int itr = it0 + q / PG, rr = q % PG, rl = it0 * PG + q;
-          if (rl >= nrows) break;
-          const uint32_t mk = (pk1[itr][tid] >> (4 * rr)) & 15u;
-          const int row = g * pb.W + rb0 + rl;
-          uint32_t ps = rbase[rl][qd] + pk2[itr][rr][tid];
-#pragma unroll
-          for (int el = 0; el < 4; ++el) {
-            if ((mk >> el) & 1u) {
-              if (ps < (uint32_t)CAND_CAP) {
-                cand_val[(int64_t)row * CAND_CAP + ps] = x4[q][el];
-                cand_idx[(int64_t)row * CAND_CAP + ps] = n0 + el;
-              }
-              ++ps;
-            }
-          }
-        }
-      }
-    }
-    kp = 0;
-    __syncthreads();
-  };
-
-  float e[4] = {0.f, 0.f, 0.f, 0.f};
-  // the rows of the next group are fetched while the current group is scanned
-  float xs[RG][4];
-  float2 ths[RG];
-  auto fetch = [&](int i0) {
-#pragma unroll
-    for (int r = 0; r < RG; ++r) {
-      const int i = i0 + r;
-      if (i < pb.W) {
-        if (vec) {
-          // one 16-byte load per thread, no branch at the tail: threads past the end re-read the
-          // last aligned quad of the row (inside its ld floats) and discard it
-          const float4 v4 = *(const float4*)(s + (int64_t)i * pb.ld + min(n0, (pb.P - 1) & ~3));
-          xs[r][0] = n0 + 0 < pb.P ? v4.x : -INFINITY;
-          xs[r][1] = n0 + 1 < pb.P ? v4.y : -INFINITY;
-          xs[r][2] = n0 + 2 < pb.P ? v4.z : -INFINITY;
-          xs[r][3] = n0 + 3 < pb.P ? v4.w : -INFINITY;
-        } else {
-          const float* rp = s + (int64_t)i * pb.ld + n0;
-#pragma unroll
-          for (int el = 0; el < 4; ++el) xs[r][el] = n0 + el < pb.P ? rp[el] : -INFINITY;
-        }
-        ths[r] = scan ? thr[g * pb.W + i] : make_float2(INFINITY, INFINITY);
+        for (int e = 0; e < 4; ++e) x[4 * j + e] = rp[min(n + e, pb.P - 1)];
       }
     }
   };
-  fetch(0);
-  int rb0 = 0;                       // first row since the last turn-around
-  for (int i0 = 0; i0 < pb.W; i0 += RG) {
-    float xc[RG][4];
-    float2 thc[RG];
+
+  float e[EW_NE];
 #pragma unroll
-    for (int r = 0; r < RG; ++r) {
-      thc[r] = ths[r];
+  for (int k = 0; k < EW_NE; ++k) e[k] = 0.f;
+  uint32_t acc_cnt = 0, acc_sum = 0;             // lane (row % 64): totals of that row above its bracket
+
+  // `live` is false for the rows that pad a block to a multiple of EPF: weight 0, no bracket
+  auto process = [&](int i, bool live, float (&x)[EW_NE]) {
+    if (tail) {
 #pragma unroll
-      for (int el = 0; el < 4; ++el) xc[r][el] = xs[r][el];
+      for (int k = 0; k < EW_NE; ++k)
+        if (scan_position(wbase, l, k) >= pb.P) x[k] = -INFINITY;   // counts for nothing, never stored
     }
-    if (i0 + RG < pb.W) fetch(i0 + RG);
-    uint32_t w0[RG / PG], w1[RG / PG];
+    const float w = live ? temporal_weight(pb, i) : 0.f;
 #pragma unroll
-    for (int q = 0; q < RG / PG; ++q) { w0[q] = 0; w1[q] = 0; }
+    for (int k = 0; k < EW_NE; ++k) e[k] = fmaf(w, x[k], e[k]);
+    if (!scan || !live) return;
+    const float2 th = thr[g * pb.W + i];         // the threshold lies in (th.x, th.y]
+    const float tlo = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.x)));
+    const float thi = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.y)));
+    uint32_t hb = 0, lb = 0;
 #pragma unroll
-    for (int r = 0; r < RG; ++r) {
-      const int i = i0 + r;
-      if (i >= pb.W) break;
-      const float* x = xc[r];
-      const float2 th = thc[r];
-      uint32_t cnt = 0, els = 0, cm = 0;
-#pragma unroll
-      for (int el = 0; el < 4; ++el) {
-        e[el] = i == 0 ? x[el] : a * x[el] + b * e[el];
-        const bool hi = x[el] > th.y;              // th.y = +inf: the bracket has no upper bound
-        cnt += hi ? 1u : 0u;
-        els += hi ? (uint32_t)el : 0u;
-        if (x[el] > th.x && !hi) {                 // inside the bracket: rare
-          if (kp < CAPT) { pval[kp][tid] = x[el]; pmeta[kp][tid] = (uint8_t)((i - rb0) * 4 + el); }
-          ++kp;
-          cm |= 1u << el;
-        }
-      }
-      w0[r / PG] |= (cnt | (els << 3)) << (6 * (r % PG));
-      w1[r / PG] |= cm << (4 * (r % PG));
+    for (int k = 0; k < EW_NE; ++k) {
+      shift_in_gt(hb, x[k], thi);
+      shift_in_gt(lb, x[k], tlo);
     }
-    if (scan) {
+    // entries above the bracket: element k = 4 j + q of this lane sits at bit 15 - k and at
+    // position wbase + 256 j + 4 l + q, so with c = popcount
+    //   sum of j = 3 c - [bits 4..7, 12..15] - 2 [bits 8..15],  sum of q = 3 c - [odd bits] - 2 [bits 2,3 mod 4]
+    const uint32_t c = (uint32_t)__popc(hb);
+    const uint32_t sj = 3u * c - (uint32_t)__popc(hb & 0xF0F0u) - 2u * (uint32_t)__popc(hb & 0xFF00u);
+    const uint32_t sq = 3u * c - (uint32_t)__popc(hb & 0xAAAAu) - 2u * (uint32_t)__popc(hb & 0xCCCCu);
+    const uint32_t rel = 4u * (uint32_t)l * c + 256u * sj + sq;      // < 2^14 per lane, < 2^20 per wavefront
+    const uint32_t tot = wave_sum((rel << 11) | c);                   // c <= 1024 per wavefront
+    if (l == (i & 63)) { acc_cnt = tot & 0x7FFu; acc_sum = tot >> 11; }
+    // entries inside the bracket
+    cmask[((int64_t)(g * pb.W + i) * nwt + wg) * 64 + l] = (uint16_t)(lb & ~hb);
+  };
+
+  // end of a block of 64 rows (or of the rows): lane = row adds the wavefront's totals to the row's
+  auto end_block = [&](int blk) {
+    if (!scan) return;
+    const int row = blk * 64 + l;
+    if (row < pb.W && acc_cnt) {
+      atomicAdd(&cnt_hi[g * pb.W + row], acc_cnt);
+      atomicAdd(&sum_hi[g * pb.W + row],
+                (unsigned long long)acc_cnt * (unsigned long long)wbase + (unsigned long long)acc_sum);
+    }
+    acc_cnt = 0; acc_sum = 0;
+  };
+
+  for (int blk = 0; blk * 64 < pb.W; ++blk) {
+    const int r0 = blk * 64, r1 = min(pb.W, r0 + 64);
+    float xs[EPF][EW_NE];
 #pragma unroll
-      for (int q = 0; q < RG / PG; ++q) {
-        pk0[(i0 - rb0) / PG + q][tid] = w0[q];
-        pk1[(i0 - rb0) / PG + q][tid] = w1[q];
-      }
-      if (i0 + RG - rb0 >= ROWS_BLK || i0 + RG >= pb.W) {      // block-uniform
-        turn_around(rb0, min(i0 + RG, pb.W) - rb0);
-        rb0 = i0 + RG;
+    for (int u = 0; u < EPF; ++u) load_row(min(r0 + u, r1 - 1), xs[u]);   // (past the end: the last row again)
+    for (int i0 = r0; i0 < r1; i0 += EPF) {
+#pragma unroll
+      for (int u = 0; u < EPF; ++u) {
+        // every group issues its EPF row loads whatever the row count (past the end: the last row
+        // again, processed with weight 0): the number of loads in flight is then known at
+        // compile time and a row only waits for its own
+        const int i = i0 + u;
+        process(min(i, r1 - 1), i < r1, xs[u]);
+        load_row(min(i + EPF, r1 - 1), xs[u]);
       }
     }
+    end_block(blk);
   }
 #pragma unroll
-  for (int el = 0; el < 4; ++el)
-    if (n0 + el < pb.P) ema[(int64_t)g * pb.ld + n0 + el] = e[el];
+  for (int j = 0; j < EW_NE / 4; ++j) {
+    const int n = wbase + 256 * j + 4 * l;
+    float* ep = ema + (int64_t)g * pb.ld + n;
+    if (VEC && n + 3 < pb.P) {
+      *(float4*)ep = make_float4(e[4 * j], e[4 * j + 1], e[4 * j + 2], e[4 * j + 3]);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (n + q < pb.P) ep[q] = e[4 * j + q];
+    }
+  }
 }
 
 constexpr unsigned long long ROW_PENDING = ~0ull;   // rowsum marker: the bracket missed this row
@@ -356,38 +264,64 @@ __device__ inline unsigned long long finish_candidates(const uint32_t (&ck)[NPT]
 }
 
 // Sum of the positions of the top-min(B,P) entries of one (head, query) row: the entries above
-// the bracket were summed by the fused pass; the threshold is found among the candidates by
-// bisection on their keys, equal values are taken in position order (a second bisection on the
-// position, only when a tie straddles the cut).  A row whose bracket missed is marked pending
-// and searched exactly by k_row_fallback.  grid (W, Hkv), 256 threads.
-__global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __restrict__ cnt_hi,
+// the bracket were summed by the fused pass; the entries inside it arrive as bit masks (one
+// 16-bit string per lane of the scan, see k_ema_scan), are expanded into positions here and
+// their values fetched from the raw score.  The threshold is found among them by bisection on
+// their keys; equal values are taken in position order (a second bisection on the position,
+// only when a tie straddles the cut).  A row whose bracket missed, or that has more than
+// CAND_CAP candidates, is marked pending and searched exactly by k_row_fallback.
+// grid (W, Hkv), 256 threads.
+__global__ __launch_bounds__(256) void k_row_finish(Prob pb, const float* __restrict__ score,
+                                                    const uint32_t* __restrict__ cnt_hi,
                                                     const unsigned long long* __restrict__ sum_hi,
-                                                    const uint32_t* __restrict__ ncand,
-                                                    const float* __restrict__ cand_val,
-                                                    const int* __restrict__ cand_idx,
+                                                    const uint16_t* __restrict__ cmask,
                                                     const float2* __restrict__ thr,
                                                     unsigned long long* __restrict__ rowsum) {
   constexpr int NPT = CAND_CAP / 256;
   __shared__ CountSmem cs;
   __shared__ unsigned long long isum[4];
+  __shared__ uint32_t wsum[SEL_NW];
+  __shared__ int cpos[CAND_CAP];                 // positions of the row's candidates
   const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
   const int k = min(head_budget(pb, g), pb.P);
   if (k >= pb.P) {
     if (threadIdx.x == 0) rowsum[r] = (unsigned long long)pb.P * (unsigned long long)(pb.P - 1) / 2ull;
     return;
   }
-  const uint32_t ch = cnt_hi[r], nc = ncand[r];
+  const uint32_t ch = cnt_hi[r];
   const unsigned long long shi = sum_hi[r];          // fetched with the counters, used at the very end
+  const float2 th = thr[r];
+  // the row's masks, two lanes of the scan per 32-bit word (a row's masks start 128-byte aligned)
+  const int nwt = scan_waves(pb.P), ndw = nwt * 32;
+  const uint32_t* mrow = (const uint32_t*)(cmask + (int64_t)r * nwt * 64);
+  uint32_t c = 0;
+  for (int x = threadIdx.x; x < ndw; x += 256) c += (uint32_t)__popc(mrow[x]);
+  const uint32_t incl = block_incl_scan(c, wsum);
+  __syncthreads();
+  if (threadIdx.x == 255) wsum[0] = incl;            // (every thread has read the wave sums)
+  __syncthreads();
+  const uint32_t nc = wsum[0];
   const bool ok = ch < (uint32_t)k && (uint32_t)k <= ch + nc && nc <= (uint32_t)CAND_CAP;
-  if (!ok) {
+  if (!ok) {                                         // block-uniform
     if (threadIdx.x == 0) rowsum[r] = ROW_PENDING;
     return;
   }
+  uint32_t slot = incl - c;
+  for (int x = threadIdx.x; x < ndw; x += 256) {
+    uint32_t m = mrow[x];
+    while (m) {
+      const int b = __builtin_ctz(m);
+      m &= m - 1;
+      const int li = 2 * x + (b >> 4);               // lane of the scan, counted along the row
+      cpos[slot++] = scan_position((li >> 6) * EW_POS, li & 63, 15 - (b & 15));
+    }
+  }
+  __syncthreads();
   const uint32_t need = (uint32_t)k - ch;
-  // All loads unconditional (an empty slot re-reads entry 0 and is then masked): independent
-  // loads in flight together instead of one round trip per slot.  Only as many slots per thread
-  // as the row's candidates need (block-uniform), so a short list is counted quickly.
-  const float2 th = thr[r];
+  const float* row = score + (int64_t)r * pb.ld;
+  // All loads unconditional (an empty slot re-reads the first candidate and is then masked):
+  // independent loads in flight together instead of one round trip per slot.  Only as many
+  // slots per thread as the row's candidates need (block-uniform), so a short list is counted quickly.
   auto run = [&](auto nsc) {
     constexpr int NS = decltype(nsc)::value;
     uint32_t ck[NS], ci[NS];
@@ -396,9 +330,8 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const uint32_t* __r
 #pragma unroll
     for (int j = 0; j < NS; ++j) {
       const uint32_t x = threadIdx.x + j * 256;
-      const int64_t o = (int64_t)r * CAND_CAP + (x < nc ? x : 0u);
-      fv[j] = cand_val[o];
-      iv[j] = cand_idx[o];
+      iv[j] = cpos[x < nc ? x : 0u];
+      fv[j] = row[iv[j]];
     }
 #pragma unroll
     for (int j = 0; j < NS; ++j) {
@@ -585,19 +518,20 @@ int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, in
   float2* thr = (float2*)(ws + lay.thr);
   uint32_t* cnt_hi = (uint32_t*)(ws + lay.cnt_hi);
   unsigned long long* sum_hi = (unsigned long long*)(ws + lay.sum_hi);
-  uint32_t* ncand = (uint32_t*)(ws + lay.ncand);
-  float* cand_val = (float*)(ws + lay.cand_val);
-  int* cand_idx = (int*)(ws + lay.cand_idx);
+  uint16_t* cmask = (uint16_t*)(ws + lay.cmask);
   float* e = ema ? ema : (float*)(ws + lay.ema);
-  const int vec = ((pb.ld & 3) == 0 && ((uintptr_t)score & 15u) == 0) ? 1 : 0;
+  const bool vec = (pb.ld & 3) == 0 && (((uintptr_t)score | (uintptr_t)e) & 15u) == 0;
   if (pb.adaptive)
     RK_LAUNCH(ST_ROWTOPK, st, k_sample_bracket, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, score, thr,
-              cnt_hi, sum_hi, ncand);
-  RK_LAUNCH(ST_EMA, st, k_ema_scan, dim3((pb.P + NPB - 1) / NPB, pb.Hkv), dim3(256), 0, st, pb, score, e,
-            thr, cnt_hi, sum_hi, ncand, cand_val, cand_idx, vec);
+              cnt_hi, sum_hi);
+  const dim3 ge((pb.P + 4 * EW_POS - 1) / (4 * EW_POS), pb.Hkv);
+  if (vec)
+    RK_LAUNCH(ST_EMA, st, k_ema_scan<true>, ge, dim3(256), 0, st, pb, score, e, thr, cnt_hi, sum_hi, cmask);
+  else
+    RK_LAUNCH(ST_EMA, st, k_ema_scan<false>, ge, dim3(256), 0, st, pb, score, e, thr, cnt_hi, sum_hi, cmask);
   if (pb.adaptive) {
-    RK_LAUNCH(ST_ROWTOPK, st, k_row_finish, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, cnt_hi, sum_hi,
-              ncand, cand_val, cand_idx, thr, rowsum);
+    RK_LAUNCH(ST_ROWTOPK, st, k_row_finish, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, score, cnt_hi, sum_hi,
+              cmask, thr, rowsum);
     RK_LAUNCH(ST_ROWTOPK, st, k_row_fallback, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
   }
   RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, e, rowsum, fin,
