@@ -132,6 +132,12 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
   return r[0] + r[1];
 }
 
+// bits = 2 bits + (x > t): one compare whose outcome an add-with-carry shifts into a bit string
+// (t wave-uniform).  Sixteen calls leave element k of a lane at bit 15 - k.
+__device__ __forceinline__ void shift_in_gt(uint32_t& bits, float x, float t) {
+  asm("v_cmp_lt_f32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(bits) : "v"(x), "s"(t) : "vcc");
+}
+
 // Budget of KV head g: its own entry of the optional per-head array, held inside (W, B], else B.
 __device__ __forceinline__ int head_budget(const Prob& pb, int g) {
   if (!pb.hb) return pb.B;

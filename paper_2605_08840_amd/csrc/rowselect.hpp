@@ -100,13 +100,17 @@ constexpr int SEL_NS = 4096;     // samples / candidate capacity of the brackete
 // no pivot >= 1 counts).  One barrier per call; `it` alternates the two reduction buffers.
 struct CountSmem { uint32_t red[2][3][SEL_NW]; };
 
-// counts of keys >= piv[0..NP) (NP <= 6): per-lane counts on the vector ALU, two 16-bit counts per
-// register through the wave reduction (NPT * 64 < 65536), one LDS word per pair and wavefront
-template <int NPT, int NP>
+// counts of keys >= piv[0..NP) (NP <= 6): per-lane counts on the vector ALU, several counts per
+// register through the wave reduction (three of 10 bits while a wavefront holds fewer than 1024
+// keys, else two of 16 bits), one LDS word per register and wavefront.
+// NWV: wavefronts that take part (0: all of the block; otherwise the first NWV, the others having left)
+template <int NPT, int NP, int NWV = 0>
 __device__ __forceinline__ void block_count_geN(const uint32_t (&k)[NPT], const uint32_t (&piv)[NP],
                                                 CountSmem& cs, int& it, uint32_t (&cnt)[NP]) {
   static_assert(NP >= 1 && NP <= 6, "three packed registers");
-  constexpr int NR = (NP + 1) / 2;
+  constexpr int BITS = NPT * 64 < 1024 ? 10 : 16, PER = 32 / BITS;
+  constexpr int NR = (NP + PER - 1) / PER;
+  constexpr uint32_t FM = (1u << BITS) - 1u;
   uint32_t c[NP];
 #pragma unroll
   for (int q = 0; q < NP; ++q) c[q] = 0;
@@ -114,31 +118,43 @@ __device__ __forceinline__ void block_count_geN(const uint32_t (&k)[NPT], const 
   for (int j = 0; j < NPT; ++j)
 #pragma unroll
     for (int q = 0; q < NP; ++q) c[q] += k[j] >= piv[q] ? 1u : 0u;
-  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6, p = it & 1;
+  const int w = threadIdx.x >> 6, nw = NWV ? NWV : (int)(blockDim.x >> 6), p = it & 1;
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
-    const uint32_t packed = wave_sum(c[2 * r] | ((2 * r + 1 < NP ? c[2 * r + 1] : 0u) << 16));
+    uint32_t pk = 0;
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+      if (PER * r + u < NP) pk |= c[PER * r + u] << (BITS * u);
+    const uint32_t packed = wave_sum(pk);
     if ((threadIdx.x & 63) == 0) cs.red[p][r][w] = packed;
   }
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < NP; ++q) cnt[q] = 0;
-  for (int j = 0; j < nw; ++j)
+  auto add_wave = [&](int j) {
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
       const uint32_t x = cs.red[p][r][j];
-      cnt[2 * r] += x & 0xFFFFu;
-      if (2 * r + 1 < NP) cnt[2 * r + 1] += x >> 16;
+#pragma unroll
+      for (int u = 0; u < PER; ++u)
+        if (PER * r + u < NP) cnt[PER * r + u] += (x >> (BITS * u)) & FM;
     }
+  };
+  if constexpr (NWV != 0) {
+#pragma unroll
+    for (int j = 0; j < NWV; ++j) add_wave(j);
+  } else {
+    for (int j = 0; j < nw; ++j) add_wave(j);
+  }
   ++it;
 }
 
-template <int NPT>
+template <int NPT, int NWV = 0>
 __device__ __forceinline__ void block_count_ge2(const uint32_t (&k)[NPT], uint32_t va, uint32_t vb,
                                                 CountSmem& cs, int& it, uint32_t& ca, uint32_t& cb) {
   const uint32_t piv[2] = {va, vb};
   uint32_t cnt[2];
-  block_count_geN<NPT, 2>(k, piv, cs, it, cnt);
+  block_count_geN<NPT, 2, NWV>(k, piv, cs, it, cnt);
   ca = cnt[0]; cb = cnt[1];
 }
 
@@ -152,10 +168,12 @@ __device__ __forceinline__ uint32_t bisect_pick(uint32_t a, int sh, uint32_t kk,
   return a;
 }
 
-// k-th largest key of the block (largest t with count(key >= t) >= k).  Bits above `top_bit` are
-// known (`prefix`, e.g. the common leading bits of a bracket that holds every key); the others
-// are resolved two per barrier (three pivots at a time).
-template <int NPT>
+// A threshold t for the k largest keys of the block: count(key >= t) >= k, and either the count
+// is exactly k (t then need not be a key: the search stops as soon as a pivot separates the k
+// largest from the rest) or t is the k-th largest key itself (equal keys straddle the cut).  Bits
+// above `top_bit` are known (`prefix`, e.g. the common leading bits of a bracket that holds every
+// key); the others are resolved two per barrier (three pivots at a time).
+template <int NPT, int NWV = 0>
 __device__ inline uint32_t block_kth(const uint32_t (&k)[NPT], uint32_t kk, CountSmem& cs, int& it,
                                      int top_bit = 31, uint32_t prefix = 0u) {
   uint32_t a = prefix;
@@ -163,7 +181,8 @@ __device__ inline uint32_t block_kth(const uint32_t (&k)[NPT], uint32_t kk, Coun
   if ((bit & 1) == 0) {                 // odd number of bits: one single-bit step first
     const uint32_t piv[1] = {a | (1u << bit)};
     uint32_t c[1];
-    block_count_geN<NPT, 1>(k, piv, cs, it, c);
+    block_count_geN<NPT, 1, NWV>(k, piv, cs, it, c);
+    if (c[0] == kk) return piv[0];
     if (c[0] >= kk) a = piv[0];
     --bit;
   }
@@ -171,7 +190,12 @@ __device__ inline uint32_t block_kth(const uint32_t (&k)[NPT], uint32_t kk, Coun
     const int sh = bit - 1;
     const uint32_t piv[3] = {a | (1u << sh), a | (2u << sh), a | (3u << sh)};
     uint32_t c[3];
-    block_count_geN<NPT, 3>(k, piv, cs, it, c);
+    block_count_geN<NPT, 3, NWV>(k, piv, cs, it, c);
+    // a pivot with exactly kk keys at or above it separates the kk largest from the rest: the
+    // lower bits do not matter any more (block-uniform: every thread holds the same counts)
+    if (c[0] == kk) return piv[0];
+    if (c[1] == kk) return piv[1];
+    if (c[2] == kk) return piv[2];
     a = bisect_pick(a, sh, kk, c[0], c[1], c[2]);
   }
   return a;
@@ -311,6 +335,26 @@ __device__ inline void block_kth_key_fast(const float* __restrict__ row, int n, 
   n_gt = above + cgt;
   k_eq = need - cgt;
   __syncthreads();
+}
+
+// Calls f(word index, word) for every 32-bit word of a row of ndw mask words (ndw a multiple of
+// 4, the row 16-byte aligned): 16-byte loads, four of them in flight per thread (NT threads).
+template <int NT, typename F>
+__device__ __forceinline__ void for_each_mask_word(const uint32_t* __restrict__ mrow, int ndw, F f) {
+  const int nq = ndw >> 2;
+  for (int q0 = 0; q0 < nq; q0 += 4 * NT) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = q0 + u * NT + (int)threadIdx.x;
+      v[u] = ((const uint4*)mrow)[min(q, nq - 1)];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = q0 + u * NT + (int)threadIdx.x;
+      if (q < nq) { f(4 * q, v[u].x); f(4 * q + 1, v[u].y); f(4 * q + 2, v[u].z); f(4 * q + 3, v[u].w); }
+    }
+  }
 }
 
 // Visits row[0..n) in position order, wave after wave; f(position, selected_rank)

@@ -39,23 +39,39 @@ int static_scratch(char** out) {
   return RESTKV_OK;
 }
 
-constexpr int SCH = 4096;            // positions per chunk
-constexpr int SCAP = 4096;           // candidates kept per head
+constexpr int SCH = 4096;            // positions per chunk = workgroup of the scan (4 per thread)
+constexpr int SCAP = 4096;           // candidates the finishing step can take
+constexpr int LHIST = 8192;          // chunk counters kept in LDS by the finishing step
 constexpr uint32_t PENDING = 0xFFFFFFFFu;
 
 struct SelPtrs {
-  float2* thr; uint32_t* cnt_hi; uint32_t* ncand; float* cand_val; int* cand_idx;
-  uint32_t* cut;          // [Hkv,4]: threshold key, position cut for ties, state, unused
-  uint32_t* counts;       // [Hkv, nchunks]
+  float2* thr;            // [Hkv] bracket of the head's threshold
+  uint32_t* above;        // [Hkv, nchunks] entries above the bracket
+  uint8_t* cmask;         // [Hkv, nchunks * 1024] entries inside the bracket: 4 bits per thread of the scan
+  uint32_t* cut;          // [Hkv, 4] threshold key, position cut for ties
+  uint32_t* offs;         // [Hkv, nchunks] selected entries in the chunks before
 };
 
-// grid (Hkv), 256 threads
+SelPtrs sel_ptrs(const Prob& pb, char* ws, size_t* bytes) {
+  const size_t nch = (size_t)(pb.P + SCH - 1) / SCH;
+  size_t off = 0;
+  auto take = [&](size_t b) { char* p = ws ? ws + off : nullptr; off = align_up(off + b); return p; };
+  SelPtrs w;
+  w.thr = (float2*)take((size_t)pb.Hkv * 8);
+  w.above = (uint32_t*)take((size_t)pb.Hkv * nch * 4);
+  w.cmask = (uint8_t*)take((size_t)pb.Hkv * nch * 1024);
+  w.cut = (uint32_t*)take((size_t)pb.Hkv * 16);
+  w.offs = (uint32_t*)take((size_t)pb.Hkv * nch * 4);
+  if (bytes) *bytes = off;
+  return w;
+}
+
+// grid (Hkv), 256 threads: bracket of the head's top-(B-W) threshold from a sample
 __global__ __launch_bounds__(256) void k_sel_bracket(Prob pb, const float* __restrict__ fin, SelPtrs w) {
   __shared__ CountSmem cs;
   const int g = blockIdx.x;
   const float* row = fin + (int64_t)g * pb.ld;
   const int k = head_budget(pb, g) - pb.W;
-  if (threadIdx.x == 0) { w.cnt_hi[g] = 0; w.ncand[g] = 0; }
   if (k >= pb.P) {
     if (threadIdx.x == 0) w.thr[g] = make_float2(INFINITY, INFINITY);
     return;
@@ -67,124 +83,6 @@ __global__ __launch_bounds__(256) void k_sel_bracket(Prob pb, const float* __res
     w.thr[g] = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
 }
 
-// grid (chunks, Hkv), 256 threads, 16 positions per thread
-__global__ __launch_bounds__(256) void k_sel_scan(Prob pb, const float* __restrict__ fin, SelPtrs w) {
-  __shared__ uint32_t list[SCH];
-  __shared__ uint32_t lcnt, hcnt, base;
-  const int g = blockIdx.y, tid = threadIdx.x;
-  const int n00 = blockIdx.x * SCH;
-  const float* row = fin + (int64_t)g * pb.ld;
-  const float2 th = w.thr[g];
-  if (tid == 0) { lcnt = 0; hcnt = 0; }
-  __syncthreads();
-  uint32_t nh = 0;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int nl = (j * 256 + tid) * 4;            // coalesced float4 per thread
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int n = n00 + nl + e;
-      const float x = n < pb.P ? row[n] : -INFINITY;
-      if (x > th.y) ++nh;
-      else if (x > th.x) list[atomicAdd(&lcnt, 1u)] = (uint32_t)(nl + e);
-    }
-  }
-  nh = wave_sum(nh);
-  if ((tid & 63) == 0 && nh) atomicAdd(&hcnt, nh);
-  __syncthreads();
-  const uint32_t E = lcnt;
-  if (tid == 0) {
-    if (E) base = atomicAdd(&w.ncand[g], E);
-    if (hcnt) atomicAdd(&w.cnt_hi[g], hcnt);
-  }
-  __syncthreads();
-  for (uint32_t x = tid; x < E; x += 256) {
-    const uint32_t pos = base + x;
-    if (pos < (uint32_t)SCAP) {
-      const int n = n00 + (int)list[x];
-      w.cand_val[(int64_t)g * SCAP + pos] = row[n];
-      w.cand_idx[(int64_t)g * SCAP + pos] = n;
-    }
-  }
-}
-
-// grid (Hkv), 256 threads
-__global__ __launch_bounds__(256) void k_sel_finish(Prob pb, SelPtrs w) {
-  constexpr int NPT = SCAP / 256;
-  __shared__ CountSmem cs;
-  const int g = blockIdx.x;
-  const int k = head_budget(pb, g) - pb.W;
-  uint32_t* cut = w.cut + 4 * g;
-  if (k >= pb.P) {                      // everything is kept
-    if (threadIdx.x == 0) { cut[0] = 0u; cut[1] = 0xFFFFFFFFu; cut[2] = 1u; }
-    return;
-  }
-  const uint32_t ch = w.cnt_hi[g], nc = w.ncand[g];
-  const bool ok = ch < (uint32_t)k && (uint32_t)k <= ch + nc && nc <= (uint32_t)SCAP;
-  if (!ok) {
-    if (threadIdx.x == 0) cut[2] = PENDING;
-    return;
-  }
-  const uint32_t need = (uint32_t)k - ch;
-  // unconditional loads (an empty slot re-reads entry 0 and is then masked): all in flight at once
-  uint32_t ck[NPT], ci[NPT];
-  {
-    float fv[NPT];
-    int iv[NPT];
-#pragma unroll
-    for (int j = 0; j < NPT; ++j) {
-      const uint32_t x = threadIdx.x + j * 256;
-      const int64_t o = (int64_t)g * SCAP + (x < nc ? x : 0u);
-      fv[j] = w.cand_val[o];
-      iv[j] = w.cand_idx[o];
-    }
-#pragma unroll
-    for (int j = 0; j < NPT; ++j) {
-      const bool in = (uint32_t)(threadIdx.x + j * 256) < nc;
-      ck[j] = in ? float_key(fv[j]) : 0u;
-      ci[j] = in ? (uint32_t)iv[j] : 0u;
-    }
-  }
-  int it = 0, top_bit;
-  uint32_t prefix;
-  {                                     // every candidate lies inside the bracket: its leading bits are known
-    const float2 th = w.thr[g];
-    common_prefix(float_key(th.x), float_key(th.y), top_bit, prefix);
-  }
-  const uint32_t t = block_kth<NPT>(ck, need, cs, it, top_bit, prefix);
-  uint32_t cge, cgt;
-  block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);
-  const uint32_t k_eq = need - cgt;
-  uint32_t pos_cut = 0xFFFFFFFFu;
-  if (cge - cgt > k_eq) {               // a run of equal values straddles the cut: lowest positions win
-    uint32_t inv[NPT];
-#pragma unroll
-    for (int j = 0; j < NPT; ++j) inv[j] = ck[j] == t ? 0xFFFFFFFFu - ci[j] : 0u;
-    pos_cut = 0xFFFFFFFFu - block_kth<NPT>(inv, k_eq, cs, it);
-  }
-  if (threadIdx.x == 0) { cut[0] = t; cut[1] = pos_cut; cut[2] = 1u; }
-}
-
-// grid (Hkv), SEL_NT threads; exits unless the head is pending
-__global__ __launch_bounds__(SEL_NT) void k_sel_fallback(Prob pb, const float* __restrict__ fin, SelPtrs w) {
-  __shared__ SelectSmem sm;
-  __shared__ uint32_t maxpos;
-  const int g = blockIdx.x;
-  uint32_t* cut = w.cut + 4 * g;
-  if (cut[2] != PENDING) return;
-  const float* row = fin + (int64_t)g * pb.ld;
-  uint32_t tau, n_gt, k_eq;
-  block_kth_key(row, pb.P, head_budget(pb, g) - pb.W, sm, tau, n_gt, k_eq);
-  if (threadIdx.x == 0) maxpos = 0;
-  __syncthreads();
-  // position of the last tie that is taken
-  block_visit_topk(row, pb.P, tau, k_eq, sm, [&](int x, uint32_t) {
-    if (float_key(row[x]) == tau) atomicMax(&maxpos, (uint32_t)x);
-  });
-  __syncthreads();
-  if (threadIdx.x == 0) { cut[0] = tau; cut[1] = maxpos; cut[2] = 1u; }
-}
-
 __device__ __forceinline__ bool sel_pred(float x, int n, uint32_t tau, uint32_t pos_cut) {
   const uint32_t key = float_key(x);
   // one 64-bit comparison of (key, inverted position) against (tau, inverted cut); the form
@@ -194,27 +92,188 @@ __device__ __forceinline__ bool sel_pred(float x, int n, uint32_t tau, uint32_t 
   return a >= b;
 }
 
-// grid (chunks, Hkv), 256 threads; thread t owns the 16 consecutive positions 16 t .. 16 t + 15
-__global__ __launch_bounds__(256) void k_sel_count(Prob pb, const float* __restrict__ fin, SelPtrs w,
-                                                   int nchunks) {
-  __shared__ uint32_t tot;
-  const int g = blockIdx.y, tid = threadIdx.x;
+// Scan of one chunk of a head's final scores: thread t owns positions chunk * 4096 + 4 t .. + 3;
+// the entries above the bracket are counted (one count per chunk), the entries inside it leave
+// as a 4-bit mask per thread.  grid (chunks, Hkv), SEL_NT = 1024 threads.
+__global__ __launch_bounds__(SEL_NT) void k_sel_scan(Prob pb, const float* __restrict__ fin, SelPtrs w,
+                                                     int nchunks, int vec) {
+  __shared__ uint32_t red[SEL_NW];
+  const int g = blockIdx.y, ch = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const float* row = fin + (int64_t)g * pb.ld;
-  const uint32_t tau = w.cut[4 * g], pos_cut = w.cut[4 * g + 1];
-  if (tid == 0) tot = 0;
-  __syncthreads();
-  uint32_t c = 0;
+  const float2 th = w.thr[g];
+  const int n0 = ch * SCH + 4 * tid;
+  float x[4];
+  if (vec && n0 + 3 < pb.P) {
+    const float4 v4 = *(const float4*)(row + n0);
+    x[0] = v4.x; x[1] = v4.y; x[2] = v4.z; x[3] = v4.w;
+  } else {
 #pragma unroll
-  for (int j = 0; j < 16; ++j) {
-    const int n = blockIdx.x * SCH + j * 256 + tid;          // order is irrelevant for a count
-    if (n < pb.P && sel_pred(row[n], n, tau, pos_cut)) ++c;
+    for (int e = 0; e < 4; ++e) x[e] = n0 + e < pb.P ? row[n0 + e] : -INFINITY;
   }
-  c = wave_sum(c);
-  if ((tid & 63) == 0 && c) atomicAdd(&tot, c);
+  const float tlo = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.x)));
+  const float thi = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.y)));
+  uint32_t hb = 0, lb = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {                 // element e ends up at bit 3 - e
+    shift_in_gt(hb, x[e], thi);
+    shift_in_gt(lb, x[e], tlo);
+  }
+  w.cmask[((int64_t)g * nchunks + ch) * 1024 + tid] = (uint8_t)(lb & ~hb);
+  const uint32_t c = wave_sum((uint32_t)__popc(hb));
+  if (lane == 0) red[wv] = c;
   __syncthreads();
-  if (tid == 0) w.counts[g * nchunks + blockIdx.x] = tot;
+  if (tid == 0) {
+    uint32_t tot = 0;
+    for (int j = 0; j < SEL_NW; ++j) tot += red[j];
+    w.above[g * nchunks + ch] = tot;
+  }
 }
 
+// Exact threshold of a head and the chunks' output offsets.  One workgroup per head
+//   * adds up the chunks' counts, expands the head's masks into candidate positions and fetches
+//     their values (at most SCAP);
+//   * finds the threshold among them by bisection on the keys (from below the bracket's common
+//     leading bits), cuts a run of equal values by position; this chain of barriers is run by
+//     four wavefronts, the other twelve leave before it;
+//   * or, if the bracket missed or holds too many candidates, searches the row exactly (radix
+//     select and ordered visit, all sixteen wavefronts);
+//   * leaves the cut and, per chunk, the number of selected entries in the chunks before it.
+// grid (Hkv), SEL_NT = 1024 threads.
+__global__ __launch_bounds__(SEL_NT) void k_sel_finish(Prob pb, const float* __restrict__ fin, SelPtrs w,
+                                                       int nchunks) {
+  __shared__ SelectSmem sm;
+  __shared__ CountSmem cs;
+  __shared__ uint32_t red[SEL_NW];
+  __shared__ uint32_t flag, maxpos;
+  __shared__ int cpos[SCAP];
+  __shared__ uint32_t lhist[LHIST];
+  const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const float* row = fin + (int64_t)g * pb.ld;
+  const int k = head_budget(pb, g) - pb.W;
+  const float2 th = w.thr[g];
+  uint32_t* cut = w.cut + 4 * g;
+  uint32_t* offs = w.offs + (int64_t)g * nchunks;
+  const uint32_t* above = w.above + (int64_t)g * nchunks;
+  if (k >= pb.P) {                               // everything is kept
+    if (tid == 0) { cut[0] = 0u; cut[1] = 0xFFFFFFFFu; }
+    for (int c = tid; c < nchunks; c += SEL_NT) offs[c] = (uint32_t)c * (uint32_t)SCH;
+    return;
+  }
+  const bool lds_hist = nchunks <= LHIST;
+  if (lds_hist) for (int c = tid; c < nchunks; c += SEL_NT) lhist[c] = 0;
+  else for (int c = tid; c < nchunks; c += SEL_NT) offs[c] = 0;      // (global counters: offs itself)
+  // counts above the bracket and number of candidates
+  const int ndw = nchunks * 256;
+  const uint32_t* mrow = (const uint32_t*)(w.cmask + (int64_t)g * nchunks * 1024);
+  uint32_t c_mine = 0, a_mine = 0;
+  for_each_mask_word<SEL_NT>(mrow, ndw, [&](int, uint32_t m) { c_mine += (uint32_t)__popc(m); });
+  for (int c = tid; c < nchunks; c += SEL_NT) a_mine += above[c];
+  const uint32_t incl = block_incl_scan(c_mine, sm.wsum);
+  __syncthreads();
+  a_mine = wave_sum(a_mine);
+  if (lane == 0) red[wv] = a_mine;
+  if (tid == SEL_NT - 1) flag = incl;
+  __syncthreads();
+  const uint32_t nc = flag;
+  uint32_t n_above = 0;
+  for (int j = 0; j < SEL_NW; ++j) n_above += red[j];
+  const bool ok = n_above < (uint32_t)k && (uint32_t)k <= n_above + nc && nc <= (uint32_t)SCAP;
+  uint32_t tau, pos_cut;
+  int nthr = SEL_NT;                             // threads that go on
+  if (ok) {                                      // block-uniform
+    uint32_t slot = incl - c_mine;
+    for_each_mask_word<SEL_NT>(mrow, ndw, [&](int x, uint32_t m) {
+      while (m) {
+        const int b = __builtin_ctz(m);
+        m &= m - 1;
+        cpos[slot++] = 4 * (4 * x + (b >> 3)) + 3 - (b & 7);     // byte = thread of the scan, bit 3 - e = element e
+      }
+    });
+    __syncthreads();
+    // The bisection is a chain of barriers: four wavefronts go through it much faster than
+    // sixteen, so the other twelve leave here (whole wavefronts; a barrier only counts the
+    // wavefronts that are still there).
+    constexpr int FW = 4, FT = FW * 64, FPT = SCAP / FT;
+    if (tid >= FT) return;
+    nthr = FT;
+    const uint32_t need = (uint32_t)k - n_above;
+    uint32_t ck[FPT], ci[FPT];
+    {
+      float fv[FPT];
+      int iv[FPT];
+#pragma unroll
+      for (int j = 0; j < FPT; ++j) {            // unconditional loads, masked afterwards: all in flight at once
+        const uint32_t x = tid + j * FT;
+        iv[j] = cpos[x < nc ? x : 0u];
+        fv[j] = row[iv[j]];
+      }
+#pragma unroll
+      for (int j = 0; j < FPT; ++j) {
+        const bool in = (uint32_t)(tid + j * FT) < nc;
+        ck[j] = in ? float_key(fv[j]) : 0u;
+        ci[j] = in ? (uint32_t)iv[j] : 0u;
+      }
+    }
+    int it = 0, top_bit;
+    uint32_t prefix;
+    common_prefix(float_key(th.x), float_key(th.y), top_bit, prefix);   // every candidate lies inside the bracket
+    tau = block_kth<FPT, FW>(ck, need, cs, it, top_bit, prefix);
+    uint32_t cge, cgt;
+    block_count_ge2<FPT, FW>(ck, tau, tau + 1u, cs, it, cge, cgt);
+    const uint32_t k_eq = need - cgt;
+    pos_cut = 0xFFFFFFFFu;
+    if (cge - cgt > k_eq) {                      // a run of equal values straddles the cut: lowest positions win
+      uint32_t inv[FPT];
+#pragma unroll
+      for (int j = 0; j < FPT; ++j) inv[j] = ck[j] == tau ? 0xFFFFFFFFu - ci[j] : 0u;
+      pos_cut = 0xFFFFFFFFu - block_kth<FPT, FW>(inv, k_eq, cs, it);
+    }
+    // selected candidates per chunk
+    const unsigned long long cutw = ((unsigned long long)tau << 32) | (unsigned long long)(0xFFFFFFFFu - pos_cut);
+#pragma unroll
+    for (int j = 0; j < FPT; ++j) {
+      const unsigned long long kj = ((unsigned long long)ck[j] << 32) | (unsigned long long)(0xFFFFFFFFu - ci[j]);
+      if ((uint32_t)(tid + j * FT) < nc && kj >= cutw) atomicAdd(lds_hist ? &lhist[ci[j] / SCH] : &offs[ci[j] / SCH], 1u);
+    }
+  } else {
+    // exact search of the whole row: threshold, then an ordered visit that counts the selected
+    // entries of every chunk and finds the last tie that is taken
+    uint32_t n_gt, k_eq;
+    block_kth_key(row, pb.P, k, sm, tau, n_gt, k_eq);
+    if (tid == 0) maxpos = 0;
+    __syncthreads();
+    block_visit_topk(row, pb.P, tau, k_eq, sm, [&](int x, uint32_t) {
+      if (float_key(row[x]) == tau) atomicMax(&maxpos, (uint32_t)x);
+      atomicAdd(lds_hist ? &lhist[x / SCH] : &offs[x / SCH], 1u);
+    });
+    __syncthreads();
+    pos_cut = maxpos;
+  }
+  __syncthreads();
+  if (!lds_hist) __threadfence();              // (the global counters were atomics of this workgroup)
+  if (tid == 0) { cut[0] = tau; cut[1] = pos_cut; }
+  // selected entries before each chunk: running sum over the chunks, nthr at a time
+  uint32_t run = 0;
+  for (int c0 = 0; c0 < nchunks; c0 += nthr) {
+    const int c = c0 + tid;
+    uint32_t v = 0;
+    if (c < nchunks) {
+      v = lds_hist ? lhist[c] : __hip_atomic_load(&offs[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (ok) v += above[c];
+    }
+    const uint32_t inc = block_incl_scan(v, sm.wsum);
+    if (c < nchunks) offs[c] = run + inc - v;
+    __syncthreads();
+    if (tid == nthr - 1) flag = inc;
+    __syncthreads();
+    run += flag;
+    __syncthreads();
+  }
+}
+
+// Ordered emission: the selected entries of a chunk go to idx at the offset the scan left; the
+// window tokens and the unused tail of a smaller per-head budget are written by chunk 0.
+// grid (chunks, Hkv), 256 threads; thread t owns the 16 consecutive positions 16 t .. 16 t + 15
 __global__ __launch_bounds__(256) void k_sel_emit(Prob pb, const float* __restrict__ fin, SelPtrs w,
                                                   int nchunks, int32_t* __restrict__ idx) {
   __shared__ uint32_t wsum[4];
@@ -223,14 +282,7 @@ __global__ __launch_bounds__(256) void k_sel_emit(Prob pb, const float* __restri
   const uint32_t tau = w.cut[4 * g], pos_cut = w.cut[4 * g + 1];
   const int bg = head_budget(pb, g), bp = bg - pb.W;
   int32_t* out = idx + (int64_t)g * pb.B;
-  // selected entries in the chunks before this one: loads spread over the threads, then summed
-  __shared__ uint32_t offs[4];
-  uint32_t off = 0;
-  for (int c = tid; c < (int)blockIdx.x; c += 256) off += w.counts[g * nchunks + c];
-  off = wave_sum(off);
-  if (lane == 0) offs[wv] = off;
-  __syncthreads();
-  off = offs[0] + offs[1] + offs[2] + offs[3];
+  const uint32_t off = w.offs[(int64_t)g * nchunks + blockIdx.x];
   const int n0 = blockIdx.x * SCH + tid * 16;
   uint32_t mask = 0;
 #pragma unroll
@@ -275,32 +327,18 @@ __global__ __launch_bounds__(256) void k_sel_emit(Prob pb, const float* __restri
 }  // namespace
 
 size_t select_ws_bytes(const Prob& pb) {
-  const int nch = (pb.P + SCH - 1) / SCH;
-  size_t off = 0;
-  auto take = [&](size_t b) { off = align_up(off + b); };
-  take((size_t)pb.Hkv * 8); take((size_t)pb.Hkv * 4); take((size_t)pb.Hkv * 4);
-  take((size_t)pb.Hkv * SCAP * 4); take((size_t)pb.Hkv * SCAP * 4);
-  take((size_t)pb.Hkv * 16); take((size_t)pb.Hkv * nch * 4);
-  return off;
+  size_t n = 0;
+  sel_ptrs(pb, nullptr, &n);
+  return n;
 }
 
 int launch_select(const Prob& pb, const float* fin, int32_t* idx, char* ws, hipStream_t st) {
   const int nch = (pb.P + SCH - 1) / SCH;
-  SelPtrs w;
-  size_t off = 0;
-  auto take = [&](size_t b) { char* p = ws + off; off = align_up(off + b); return p; };
-  w.thr = (float2*)take((size_t)pb.Hkv * 8);
-  w.cnt_hi = (uint32_t*)take((size_t)pb.Hkv * 4);
-  w.ncand = (uint32_t*)take((size_t)pb.Hkv * 4);
-  w.cand_val = (float*)take((size_t)pb.Hkv * SCAP * 4);
-  w.cand_idx = (int*)take((size_t)pb.Hkv * SCAP * 4);
-  w.cut = (uint32_t*)take((size_t)pb.Hkv * 16);
-  w.counts = (uint32_t*)take((size_t)pb.Hkv * nch * 4);
+  const SelPtrs w = sel_ptrs(pb, ws, nullptr);
+  const int vec = ((pb.ld & 3) == 0 && ((uintptr_t)fin & 15u) == 0) ? 1 : 0;
   RK_LAUNCH(ST_SELECT, st, k_sel_bracket, dim3(pb.Hkv), dim3(256), 0, st, pb, fin, w);
-  RK_LAUNCH(ST_SELECT, st, k_sel_scan, dim3(nch, pb.Hkv), dim3(256), 0, st, pb, fin, w);
-  RK_LAUNCH(ST_SELECT, st, k_sel_finish, dim3(pb.Hkv), dim3(256), 0, st, pb, w);
-  RK_LAUNCH(ST_SELECT, st, k_sel_fallback, dim3(pb.Hkv), dim3(SEL_NT), 0, st, pb, fin, w);
-  RK_LAUNCH(ST_SELECT, st, k_sel_count, dim3(nch, pb.Hkv), dim3(256), 0, st, pb, fin, w, nch);
+  RK_LAUNCH(ST_SELECT, st, k_sel_scan, dim3(nch, pb.Hkv), dim3(SEL_NT), 0, st, pb, fin, w, nch, vec);
+  RK_LAUNCH(ST_SELECT, st, k_sel_finish, dim3(pb.Hkv), dim3(SEL_NT), 0, st, pb, fin, w, nch);
   RK_LAUNCH(ST_SELECT, st, k_sel_emit, dim3(nch, pb.Hkv), dim3(256), 0, st, pb, fin, w, nch, idx);
   return hip_status();
 }

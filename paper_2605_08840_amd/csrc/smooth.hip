@@ -96,11 +96,6 @@ constexpr int EW_POS = 1024;        // prefix positions per wavefront
 constexpr int EW_NE = EW_POS / 64;  // elements per lane and row (16 = four quads)
 constexpr int EPF = 4;              // rows in flight
 
-// bits = 2 bits + (x > t): one compare, one add with carry (t wave-uniform)
-__device__ __forceinline__ void shift_in_gt(uint32_t& bits, float x, float t) {
-  asm("v_cmp_lt_f32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(bits) : "v"(x), "s"(t) : "vcc");
-}
-
 // weight of window query i in the temporal smoothing (wave-uniform)
 __device__ __forceinline__ float temporal_weight(const Prob& pb, int i) {
   const int n = pb.W - 1 - i;                      // queries after this one
@@ -239,8 +234,8 @@ __device__ inline unsigned long long finish_candidates(const uint32_t (&ck)[NPT]
   int it = 0, top_bit;
   uint32_t prefix, cge, cgt;
   common_prefix(float_key(th.x), float_key(th.y), top_bit, prefix);   // every candidate lies inside the bracket
-  const uint32_t t = block_kth<NPT>(ck, need, cs, it, top_bit, prefix);
-  block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);
+  const uint32_t t = block_kth<NPT, 4>(ck, need, cs, it, top_bit, prefix);
+  block_count_ge2<NPT, 4>(ck, t, t + 1u, cs, it, cge, cgt);
   const uint32_t k_eq = need - cgt;              // ties at t to take, lowest positions first
   uint32_t pos_cut = 0xFFFFFFFFu;                // take tied entries with position <= pos_cut
   if (cge - cgt > k_eq) {
@@ -248,7 +243,7 @@ __device__ inline unsigned long long finish_candidates(const uint32_t (&ck)[NPT]
     uint32_t inv[NPT];
 #pragma unroll
     for (int j = 0; j < NPT; ++j) inv[j] = ck[j] == t ? 0xFFFFFFFFu - ci[j] : 0u;
-    pos_cut = 0xFFFFFFFFu - block_kth<NPT>(inv, k_eq, cs, it);
+    pos_cut = 0xFFFFFFFFu - block_kth<NPT, 4>(inv, k_eq, cs, it);
   }
   // One 64-bit comparison per entry: (key, inverted position) >= (t, inverted cut).  (The form
   // "key > t || (key == t && position <= cut)" is miscompiled by hipcc 7.2 at -O3: the addend of
@@ -295,7 +290,7 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const float* __rest
   const int nwt = scan_waves(pb.P), ndw = nwt * 32;
   const uint32_t* mrow = (const uint32_t*)(cmask + (int64_t)r * nwt * 64);
   uint32_t c = 0;
-  for (int x = threadIdx.x; x < ndw; x += 256) c += (uint32_t)__popc(mrow[x]);
+  for_each_mask_word<256>(mrow, ndw, [&](int, uint32_t m) { c += (uint32_t)__popc(m); });
   const uint32_t incl = block_incl_scan(c, wsum);
   __syncthreads();
   if (threadIdx.x == 255) wsum[0] = incl;            // (every thread has read the wave sums)
@@ -307,15 +302,14 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const float* __rest
     return;
   }
   uint32_t slot = incl - c;
-  for (int x = threadIdx.x; x < ndw; x += 256) {
-    uint32_t m = mrow[x];
+  for_each_mask_word<256>(mrow, ndw, [&](int x, uint32_t m) {
     while (m) {
       const int b = __builtin_ctz(m);
       m &= m - 1;
-      const int li = 2 * x + (b >> 4);               // lane of the scan, counted along the row
+      const int li = 2 * x + (b >> 4);               // lane of the scan, counted along the row (two per word)
       cpos[slot++] = scan_position((li >> 6) * EW_POS, li & 63, 15 - (b & 15));
     }
-  }
+  });
   __syncthreads();
   const uint32_t need = (uint32_t)k - ch;
   const float* row = score + (int64_t)r * pb.ld;
