@@ -207,28 +207,76 @@ def gather(src, idx) -> np.ndarray:
     return out
 
 
+def indicator_attention(q, qpos, k, v, P: int, scale: float, value_norm: bool = False) -> np.ndarray:
+    """Ablation indicators (App., indicator table): A[n], or A[n] * ||v_n||_2; I [G,nq,P]."""
+    q, qp, k, v, _, _, G, nq, d, L = _head_args(q, qpos, k, v, None)
+    I = np.empty((G, nq, P), np.float64)
+    rc = _load().rk_oracle_indicator_attention(_p(q), _p(qp), _p(k), _p(v), G, nq, d, ctypes.c_int64(L),
+                                               ctypes.c_int64(P), ctypes.c_double(scale), int(value_norm), _p(I))
+    _check(rc, "indicator_attention")
+    return I
+
+
+def group_max(I) -> np.ndarray:
+    I = _f64(I)
+    G, nq, P = I.shape
+    out = np.empty((nq, P), np.float64)
+    _check(_load().rk_oracle_group_max(_p(I), G, nq, ctypes.c_int64(P), _p(out)), "group_max")
+    return out
+
+
+TEMPORAL = {"ema": 0, "mean": 1, "inv_ema": 2}
+
+
+def temporal(Ig, mode: str, alpha: float) -> np.ndarray:
+    """Temporal smoothing over the window queries: 'ema' (Sec. 3.3), 'mean', 'inv_ema' (App.)."""
+    Ig = _f64(Ig)
+    W, P = Ig.shape
+    out = np.empty((P,), np.float64)
+    _check(_load().rk_oracle_temporal(_p(Ig), W, ctypes.c_int64(P), TEMPORAL[mode], ctypes.c_double(alpha),
+                                      _p(out)), "temporal")
+    return out
+
+
+def pool_max(ema_row, w_s: int, gamma: int) -> np.ndarray:
+    e = _f64(ema_row)
+    out = np.empty_like(e)
+    rc = _load().rk_oracle_pool_max(_p(e), ctypes.c_int64(e.shape[0]), ctypes.c_int64(w_s),
+                                    ctypes.c_int64(gamma), _p(out))
+    _check(rc, "pool_max")
+    return out
+
+
 def score_head(q_g, k_g, v_g, fac_g, W: int, scale: float, causal: bool = True,
-               rows: Optional[Sequence[int]] = None, aux: bool = False):
+               rows: Optional[Sequence[int]] = None, aux: bool = False,
+               indicator: str = "reconstruction", group: str = "mean"):
     """Group-reduced indicator of one KV head: Ig [nq,P] for the window queries
-    ``rows`` (default all W).  q_g [G,W,d]; k_g,v_g [L,d]; fac_g [G,d,r] or None."""
+    ``rows`` (default all W).  q_g [G,W,d]; k_g,v_g [L,d]; fac_g [G,d,r] or None.
+    indicator: 'reconstruction' (Eq. rec_ei), 'attention', 'value_norm'; group: 'mean' or 'max'."""
     q_g = _f32(q_g)
     L = k_g.shape[0]
     P = L - W
     rows = list(range(W)) if rows is None else list(rows)
     qsel = q_g[:, rows, :]
     qpos = np.array([P + i if causal else -1 for i in rows], np.int64)
+    reduce = group_mean if group == "mean" else group_max
+    if indicator != "reconstruction":
+        assert not aux
+        return reduce(indicator_attention(qsel, qpos, k_g, v_g, P, scale, indicator == "value_norm"))
     res = indicator_closed(qsel, qpos, k_g, v_g, fac_g, P, scale, aux=aux)
     if aux:
         I, aA, aU = res
-        return group_mean(I), I, aA, aU
-    return group_mean(res)
+        return reduce(I), I, aA, aU
+    return reduce(res)
 
 
-def smooth_head(Ig, alpha: float, beta: float, base_k: int, adaptive: bool, B: int):
-    """EMA + adaptive window for one KV head. Returns dict(ema, final, w_s, gamma, d_front, d_rear)."""
+def smooth_head(Ig, alpha: float, beta: float, base_k: int, adaptive: bool, B: int,
+                temporal_mode: str = "ema", pool: str = "avg"):
+    """Temporal smoothing + (adaptive) window for one KV head.
+    Returns dict(ema, final, w_s, gamma, d_front, d_rear)."""
     Ig = _f64(Ig)
     W = Ig.shape[0]
-    e = ema(Ig, alpha)
+    e = temporal(Ig, temporal_mode, alpha)
     if adaptive and W >= 2:
         df, dr, sf, sr = aws_stats(Ig, B)
         ws, gm = aws_window(df, dr, beta, base_k, True)
@@ -236,13 +284,14 @@ def smooth_head(Ig, alpha: float, beta: float, base_k: int, adaptive: bool, B: i
         df = dr = 0.0
         sf = sr = 0
         ws, gm = aws_window(0.0, 0.0, 1.0, base_k, False)
-    return dict(ema=e, final=box(e, ws, gm), w_s=ws, gamma=gm, d_front=df, d_rear=dr,
-                sum_front=sf, sum_rear=sr)
+    fin = box(e, ws, gm) if pool == "avg" else pool_max(e, ws, gm)
+    return dict(ema=e, final=fin, w_s=ws, gamma=gm, d_front=df, d_rear=dr, sum_front=sf, sum_rear=sr)
 
 
 def run_layer(q, k, v, wo, *, window: int, budget: int, alpha: float, beta: float,
               base_k: int, adaptive: bool = True, scale: Optional[float] = None,
-              causal: bool = True):
+              causal: bool = True, indicator: str = "reconstruction", group: str = "mean",
+              temporal_mode: str = "ema", pool: str = "avg"):
     """The whole path for one layer.  q [Hq,W,d], k,v [Hkv,L,d], wo [Hq*d,D] or None.
 
     Returns dict with score [Hkv,W,P], ema/final [Hkv,P], w_s/gamma [Hkv],
@@ -266,8 +315,8 @@ def run_layer(q, k, v, wo, *, window: int, budget: int, alpha: float, beta: floa
                v_out=np.empty((Hkv, budget, d), np.float32))
     for g in range(Hkv):
         fg = None if fac is None else fac[g * G:(g + 1) * G]
-        Ig = score_head(q[g * G:(g + 1) * G], k[g], v[g], fg, W, scale, causal)
-        sm = smooth_head(Ig, alpha, beta, base_k, adaptive, budget)
+        Ig = score_head(q[g * G:(g + 1) * G], k[g], v[g], fg, W, scale, causal, indicator=indicator, group=group)
+        sm = smooth_head(Ig, alpha, beta, base_k, adaptive, budget, temporal_mode, pool)
         idx = select(sm["final"], W, budget)
         out["score"][g] = Ig
         out["ema"][g] = sm["ema"]

@@ -21,6 +21,9 @@
  *   EMA temporal smoothing             Sec. 3.3, EMA recursion
  *   adaptive-window spatial smoothing  Sec. 3.3, D_front/D_rear, W_s, gamma_shift, Eq. (final_ei)
  *   selection and gather               Sec. 3.3, Eq. (topk)
+ *   ablation variants                  Sec. 4 (ablation table), App. on the ablation study:
+ *                                      attention-weight and value-norm indicators, mean and
+ *                                      inverse-EMA temporal smoothing, max pooling
  *
  * Readings of points the paper leaves open are listed where they are applied
  * and, together, in the design document of this repository.
@@ -29,7 +32,10 @@
  *   - how the G query heads of one KV head are combined (mean of the per-head
  *     indicator, rk_oracle_group_mean);
  *   - how the fixed kernel size k of App. B combines with the W_s equation
- *     (rk_oracle_aws_window, k > 1).
+ *     (rk_oracle_aws_window, k > 1);
+ *   - the maximum over the group as the alternative GQA reduction (rk_oracle_group_max) and
+ *     the meaning of "Inv-EMA" (rk_oracle_temporal, mode 2), which the paper names but does
+ *     not define: the functions themselves are pinned to their stated definitions.
  */
 #include <math.h>
 #include <stdint.h>
@@ -468,3 +474,99 @@ int rk_oracle_gather(const float* src, const int64_t* idx, int64_t B, int d, flo
     memcpy(out + j * d, src + idx[j] * (int64_t)d, sizeof(float) * (size_t)d);
   return RK_OK;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Ablation variants (Sec. 4, ablation table; App. on the ablation study).     */
+
+/*
+ * Indicators the paper compares its own with (App., table on the information
+ * the indicator considers): the attention weight itself, A[n] ("attention
+ * weights"), or the attention weight times the l2 norm of the token's value
+ * row, A[n] * ||v_n||_2 ("attention weights and values").  Same argument layout
+ * as rk_oracle_indicator_closed; no output projection enters.
+ */
+int rk_oracle_indicator_attention(const float* q, const int64_t* qpos, const float* k,
+                                  const float* v, int G, int nq, int d, int64_t L, int64_t P,
+                                  double scale, int value_norm, double* I) {
+  if (!q || !k || !v || !I || G <= 0 || nq <= 0 || d <= 0 || P < 0 || P > L) return RK_EINVAL;
+  int rc = RK_OK;
+#pragma omp parallel for schedule(dynamic)
+  for (int64_t hq = 0; hq < (int64_t)G * nq; ++hq) {
+    const int64_t i = hq % nq;
+    const int64_t nvis = (qpos && qpos[i] >= 0) ? qpos[i] + 1 : L;
+    double* e = (double*)malloc(sizeof(double) * (size_t)L);
+    if (!e) { rc = RK_ENOMEM; continue; }
+    double l;
+    softmax_row(q + hq * d, k, d, nvis, scale, e, &l, NULL);
+    for (int64_t n = 0; n < P; ++n) {
+      double val = n < nvis ? e[n] / l : 0.0;
+      if (value_norm) {
+        double s2 = 0.0;
+        for (int c = 0; c < d; ++c) s2 += (double)v[n * d + c] * (double)v[n * d + c];
+        val *= sqrt(s2);
+      }
+      I[hq * P + n] = val;
+    }
+    free(e);
+  }
+  return rc;
+}
+
+/* Alternative GQA reduction: the largest indicator among the group's query heads. */
+int rk_oracle_group_max(const double* I, int G, int nq, int64_t P, double* Ig) {
+  if (!I || !Ig || G <= 0 || nq <= 0 || P < 0) return RK_EINVAL;
+  for (int64_t x = 0; x < (int64_t)nq * P; ++x) {
+    double m = I[x];
+    for (int h = 1; h < G; ++h) if (I[(int64_t)h * nq * P + x] > m) m = I[(int64_t)h * nq * P + x];
+    Ig[x] = m;
+  }
+  return RK_OK;
+}
+
+/*
+ * Temporal smoothing alternatives (App., table on smoothing methods):
+ *   mode 0  EMA, the recursion of Sec. 3.3 (rk_oracle_ema);
+ *   mode 1  Mean: the plain average over the W window queries;
+ *   mode 2  Inv-EMA: the same recursion run from the newest query to the oldest,
+ *           so that the OLDEST query ends with weight alpha and the newest with
+ *           (1 - alpha)^(W-1) (the paper does not spell the variant out).
+ */
+int rk_oracle_temporal(const double* Ig, int W, int64_t P, int mode, double alpha, double* out) {
+  if (!Ig || !out || W < 1 || P < 0 || mode < 0 || mode > 2) return RK_EINVAL;
+  if (mode == 0) return rk_oracle_ema(Ig, W, P, alpha, out);
+  for (int64_t n = 0; n < P; ++n) {
+    if (mode == 1) {
+      double s = 0.0;
+      for (int i = 0; i < W; ++i) s += Ig[(int64_t)i * P + n];
+      out[n] = s / (double)W;
+    } else {
+      double e = Ig[(int64_t)(W - 1) * P + n];
+      for (int i = W - 2; i >= 0; --i) e = alpha * Ig[(int64_t)i * P + n] + (1.0 - alpha) * e;
+      out[n] = e;
+    }
+  }
+  return RK_OK;
+}
+
+/*
+ * Max pooling as the spatial smoothing alternative: the largest smoothed
+ * indicator among the W_s positions n + gamma - floor(W_s/2) .. n + gamma +
+ * floor(W_s/2) that lie inside the prefix (0 if none does).
+ */
+int rk_oracle_pool_max(const double* ema, int64_t P, int64_t w_s, int64_t gamma, double* out) {
+  if (!ema || !out || w_s < 1 || !(w_s & 1)) return RK_EINVAL;
+  const int64_t half = w_s / 2;
+  for (int64_t n = 0; n < P; ++n) {
+    double m = 0.0;
+    int any = 0;
+    for (int64_t j = gamma - half; j <= gamma + half; ++j) {
+      const int64_t x = n + j;
+      if (x < 0 || x >= P) continue;
+      if (!any || ema[x] > m) m = ema[x];
+      any = 1;
+    }
+    out[n] = m;
+  }
+  return RK_OK;
+}
+

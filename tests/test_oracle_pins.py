@@ -379,3 +379,88 @@ def test_run_layer_adaptive_composition(oracle_mod):
         np.testing.assert_array_equal(out["idx"][g], np.concatenate([keep, np.arange(P, P + W)]))
         np.testing.assert_array_equal(out["k_out"][g], k.numpy()[g][out["idx"][g]])
     assert any(ws > 3 or gm != 0 for ws, gm in seen), seen       # the window did adapt
+
+
+# ---------------------------------------------------------------- ablation variants
+def test_attention_and_value_norm_indicators(oracle_mod):
+    """App. (indicator table): A[n] and A[n] * ||v_n||_2, against the library softmax."""
+    q, k, v, _ = rand_head(40, G=3, nq=4, d=12, L=60)
+    P, scale = 50, 0.31
+    qpos = np.array([P + 1, P + 3, P + 6, -1])
+    Ia = oracle_mod.indicator_attention(q, qpos, k, v, P, scale)
+    Iv = oracle_mod.indicator_attention(q, qpos, k, v, P, scale, value_norm=True)
+    vn = np.linalg.norm(v.astype(np.float64), axis=1)
+    for h in range(3):
+        for i, p in enumerate(qpos):
+            nvis = 60 if p < 0 else p + 1
+            s = torch.tensor(q[h, i], dtype=torch.float64) @ torch.tensor(k[:nvis], dtype=torch.float64).T * scale
+            A = torch.softmax(s, dim=-1).numpy()
+            np.testing.assert_allclose(Ia[h, i], A[:P], rtol=1e-12)
+            np.testing.assert_allclose(Iv[h, i], A[:P] * vn[:P], rtol=1e-12)
+    # a query that sees fewer keys than the prefix gives zero weight to the rest
+    I2 = oracle_mod.indicator_attention(q[:, :1], np.array([20]), k, v, P, scale)
+    assert np.all(I2[:, 0, 21:] == 0) and abs(I2[0, 0, :21].sum() - 1) < 1e-12
+
+
+def test_group_max_and_score_head_variants(oracle_mod):
+    I = rng(41).random((4, 3, 17))
+    np.testing.assert_array_equal(oracle_mod.group_max(I), I.max(0))
+    q, k, v, wo = rand_head(42, G=2, nq=5, d=8, L=40)
+    W, scale = 5, 0.4
+    P = 35
+    a = oracle_mod.score_head(q, k, v, None, W, scale, indicator="attention", group="max")
+    Aall = oracle_mod.indicator_attention(q, np.arange(P, P + W), k, v, P, scale)
+    np.testing.assert_array_equal(a, Aall.max(0))
+    b = oracle_mod.score_head(q, k, v, wo, W, scale, group="max")
+    Ic = oracle_mod.indicator_closed(q, np.arange(P, P + W), k, v, wo, P, scale)
+    np.testing.assert_array_equal(b, Ic.max(0))
+
+
+def test_temporal_mean_and_inverse_ema(oracle_mod):
+    r = rng(43)
+    W, P = 6, 11
+    Ig = r.random((W, P))
+    np.testing.assert_array_equal(oracle_mod.temporal(Ig, "ema", 0.3), oracle_mod.ema(Ig, 0.3))
+    np.testing.assert_allclose(oracle_mod.temporal(Ig, "mean", 0.3), Ig.mean(0), rtol=1e-14)
+    for alpha in (0.1, 0.3, 0.8):
+        # closed-form weights of the recursion run newest -> oldest: the newest query keeps
+        # (1-alpha)^(W-1), query i < W-1 gets alpha (1-alpha)^i
+        w = np.array([alpha * (1 - alpha) ** i for i in range(W - 1)] + [(1 - alpha) ** (W - 1)])
+        assert abs(w.sum() - 1) < 1e-14
+        np.testing.assert_allclose(oracle_mod.temporal(Ig, "inv_ema", alpha), w @ Ig, rtol=1e-13)
+    np.testing.assert_array_equal(oracle_mod.temporal(Ig, "inv_ema", 1.0), Ig[0])     # all weight on the oldest
+    np.testing.assert_array_equal(oracle_mod.temporal(Ig, "inv_ema", 0.0), Ig[-1])
+    np.testing.assert_array_equal(oracle_mod.temporal(Ig[:1], "mean", 0.3), Ig[0])
+
+
+def test_pool_max_against_library_pool_and_shifts(oracle_mod):
+    r = rng(44)
+    e = r.random(50)
+    np.testing.assert_array_equal(oracle_mod.pool_max(e, 1, 0), e)
+    for ws in (3, 5, 21):
+        ref = torch.nn.functional.max_pool1d(torch.tensor(e)[None, None], ws, 1, ws // 2)[0, 0].numpy()
+        np.testing.assert_array_equal(oracle_mod.pool_max(e, ws, 0), ref)
+    got = oracle_mod.pool_max(e, 3, 4)                 # window n+3 .. n+5
+    want = np.array([e[n + 3:n + 6].max() if n + 3 < 50 else 0.0 for n in range(50)])
+    np.testing.assert_array_equal(got, want)
+    got = oracle_mod.pool_max(e, 5, -60)               # entirely outside the prefix
+    assert np.all(got == 0.0)
+
+
+def test_run_layer_variant_composition(oracle_mod):
+    import workloads
+    w = workloads.small_case(Hq=4, Hkv=2, d=16, L=200, W=6, B=30, D=20, k=3)
+    q, k, v = workloads.make_qkv(w)
+    out = oracle_mod.run_layer(q.numpy(), k.numpy(), v.numpy(), None, window=6, budget=30, alpha=0.3, beta=2000.0,
+                               base_k=3, adaptive=False, indicator="value_norm", group="max",
+                               temporal_mode="mean", pool="max")
+    P = 194
+    vn = np.linalg.norm(v.numpy().astype(np.float64), axis=2)
+    for g in range(2):
+        A, _ = oracle_mod.attention(q.numpy()[2 * g:2 * g + 2], k.numpy()[g:g + 1], v.numpy()[g:g + 1], 0.25, True)
+        want = (A[:, :, :P] * vn[g][None, None, :P]).max(0)
+        np.testing.assert_allclose(out["score"][g], want, rtol=1e-12)
+        np.testing.assert_allclose(out["ema"][g], want.mean(0), rtol=1e-12)
+        e = out["ema"][g]
+        pad = np.concatenate([[0.0], e, [0.0]])
+        np.testing.assert_array_equal(out["final"][g], np.maximum(np.maximum(pad[:-2], pad[1:-1]), pad[2:]))
