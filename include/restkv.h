@@ -49,6 +49,29 @@ extern "C" {
 #define RESTKV_F32  0   /* q, k, v and the compacted cache are IEEE binary32 */
 #define RESTKV_BF16 1   /* ... are bfloat16                                   */
 
+/*
+ * Ablation variants (Sec. 4, ablation table; App. on the ablation study), selected through
+ * restkv_params.variant.  0 is the method itself.
+ *   indicator (restkv_score):  RESTKV_IND_ATTENTION   A[n], the attention weight alone
+ *                              RESTKV_IND_VALUE_NORM  A[n] * ||v_n||_2  (gram is ignored by both)
+ *   group reduction:           RESTKV_GROUP_MAX       largest indicator among the G query heads
+ *                                                     of a KV head instead of their mean
+ *   temporal (restkv_smooth):  RESTKV_TEMPORAL_MEAN   plain mean over the W window queries
+ *                              RESTKV_TEMPORAL_INV_EMA the EMA recursion run from the newest
+ *                                                     query to the oldest (oldest weighs alpha)
+ *   spatial pooling:           RESTKV_POOL_MAX        maximum over the window instead of the mean
+ * "No temporal smoothing" is ema_alpha = 1, "no spatial smoothing" base_window = 1 with
+ * adaptive = 0, fixed average pooling adaptive = 0.  restkv_score_smooth runs the two separate
+ * calls for any variant other than 0.
+ */
+#define RESTKV_IND_RECONSTRUCTION 0
+#define RESTKV_IND_ATTENTION      1
+#define RESTKV_IND_VALUE_NORM     2
+#define RESTKV_GROUP_MAX          (1 << 2)
+#define RESTKV_TEMPORAL_MEAN      (1 << 4)
+#define RESTKV_TEMPORAL_INV_EMA   (2 << 4)
+#define RESTKV_POOL_MAX           (1 << 6)
+
 typedef void* restkv_stream_t;    /* a hipStream_t */
 
 /*
@@ -69,7 +92,8 @@ typedef struct restkv_params {
   int32_t base_window;   /* k: odd >= 1, the fixed kernel size of App. B               */
   int32_t adaptive;      /* 1: W_s and gamma_shift from D_front/D_rear ; 0: W_s=k, 0   */
   float   beta;          /* scaling factor of the adaptive window (> L / 2^30 when adaptive) */
-  int32_t reserved;      /* must be 0                                                  */
+  int32_t variant;       /* 0: the method; else a sum of RESTKV_IND_*, RESTKV_GROUP_MAX,
+                            RESTKV_TEMPORAL_*, RESTKV_POOL_MAX (ablation variants, see below) */
   int64_t q_stride_h;    /* elements between query heads  (0: W*d)                     */
   int64_t q_stride_t;    /* elements between window queries (0: d)                     */
   int64_t kv_stride_h;   /* elements between KV heads     (0: L*d)                     */

@@ -20,6 +20,13 @@ LIB_PATH = os.environ.get("RESTKV_LIB") or os.path.join(_PKG, "librestkv.so")
 
 RESTKV_F32 = 0
 RESTKV_BF16 = 1
+# ablation variants (restkv_params.variant, see include/restkv.h)
+RESTKV_IND_ATTENTION = 1
+RESTKV_IND_VALUE_NORM = 2
+RESTKV_GROUP_MAX = 1 << 2
+RESTKV_TEMPORAL_MEAN = 1 << 4
+RESTKV_TEMPORAL_INV_EMA = 2 << 4
+RESTKV_POOL_MAX = 1 << 6
 
 
 class RestkvParams(ctypes.Structure):
@@ -28,7 +35,7 @@ class RestkvParams(ctypes.Structure):
         ("seq_len", ctypes.c_int32), ("window", ctypes.c_int32), ("budget", ctypes.c_int32),
         ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32), ("scale", ctypes.c_float),
         ("ema_alpha", ctypes.c_float), ("base_window", ctypes.c_int32), ("adaptive", ctypes.c_int32),
-        ("beta", ctypes.c_float), ("reserved", ctypes.c_int32),
+        ("beta", ctypes.c_float), ("variant", ctypes.c_int32),
         ("q_stride_h", ctypes.c_int64), ("q_stride_t", ctypes.c_int64),
         ("kv_stride_h", ctypes.c_int64), ("kv_stride_t", ctypes.c_int64), ("ld_score", ctypes.c_int64),
     ]
@@ -88,12 +95,12 @@ def strerror(code: int) -> str:
 
 def make_params(*, n_q_heads, n_kv_heads, head_dim, seq_len, window, budget, dtype,
                 causal=True, scale=0.0, ema_alpha=0.3, base_window=5, adaptive=True, beta=2000.0,
-                q_stride_h=0, q_stride_t=0, kv_stride_h=0, kv_stride_t=0, ld_score=0) -> RestkvParams:
+                q_stride_h=0, q_stride_t=0, kv_stride_h=0, kv_stride_t=0, ld_score=0, variant=0) -> RestkvParams:
     dt = {torch.float32: RESTKV_F32, torch.bfloat16: RESTKV_BF16, "f32": RESTKV_F32,
           "bf16": RESTKV_BF16}.get(dtype, dtype)
     return RestkvParams(n_q_heads, n_kv_heads, head_dim, seq_len, window, budget, int(dt),
                         int(bool(causal)), float(scale), float(ema_alpha), int(base_window),
-                        int(bool(adaptive)), float(beta), 0, q_stride_h, q_stride_t, kv_stride_h,
+                        int(bool(adaptive)), float(beta), int(variant), q_stride_h, q_stride_t, kv_stride_h,
                         kv_stride_t, ld_score)
 
 

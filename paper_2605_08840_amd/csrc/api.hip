@@ -12,7 +12,8 @@ int resolve(const restkv_params* p, Prob* o) {
   if (p->seq_len < 2 || p->window < 1 || p->window >= p->seq_len) return RESTKV_EINVAL;
   if (p->budget <= p->window || p->budget > p->seq_len) return RESTKV_EINVAL;
   if (p->base_window < 1 || !(p->base_window & 1)) return RESTKV_EINVAL;
-  if (p->reserved != 0) return RESTKV_EINVAL;
+  if (p->variant & ~0x77) return RESTKV_EINVAL;
+  if ((p->variant & 3) == 3 || ((p->variant >> 4) & 3) == 3) return RESTKV_EINVAL;
   if (!(p->ema_alpha >= 0.f && p->ema_alpha <= 1.f)) return RESTKV_EINVAL;
   if (p->adaptive && !(p->beta > 0.f)) return RESTKV_EINVAL;
   // |D_front - D_rear| < L, so floor(|x| / beta) stays a 32-bit integer with room to spare
@@ -25,6 +26,8 @@ int resolve(const restkv_params* p, Prob* o) {
   o->B = p->budget; o->R = o->G * o->W; o->hb = nullptr;
   if ((int64_t)o->G * o->W > 4096) return RESTKV_EUNSUPPORTED;
   o->dtype = p->dtype; o->causal = p->causal ? 1 : 0; o->base_k = p->base_window;
+  o->ind = p->variant & 3; o->gmax = (p->variant >> 2) & 1; o->tmode = (p->variant >> 4) & 3;
+  o->pmax = (p->variant >> 6) & 1;
   o->adaptive = (p->adaptive && o->W >= 2) ? 1 : 0;
   o->scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)o->d);
   o->alpha = p->ema_alpha; o->beta = p->beta;
@@ -199,7 +202,7 @@ int restkv_score_smooth(const restkv_params* p, const void* q, const void* k, co
   const ScoreWs ls = score_ws(pb);
   const SmoothWs lm = smooth_ws(pb);
   hipStream_t st = (hipStream_t)stream;
-  if (g_force_fp32 || !fused_eligible(pb, q, k, v)) {
+  if (g_force_fp32 || p->variant != 0 || !fused_eligible(pb, q, k, v)) {
     // same result from the two separate calls (they use the workspace one after the other);
     // both sizes are checked first so that nothing is enqueued when the second call would fail
     rc = check_ws(workspace, workspace_bytes, ls.bytes > lm.bytes ? ls.bytes : lm.bytes);

@@ -13,6 +13,7 @@ namespace restkv {
 struct Prob {
   int Hq, Hkv, G, d, L, W, P, B, R;   // R = G*W rows (queries) per KV head
   int dtype, causal, base_k, adaptive;
+  int ind, gmax, tmode, pmax;          // ablation variant: indicator 0..2, group maximum, temporal 0..2, max pooling
   float scale, alpha, beta;
   int64_t q_sh, q_st, kv_sh, kv_st, ld;
   const int32_t* hb;   // optional per-KV-head budgets (device, [Hkv]); NULL: B for every head

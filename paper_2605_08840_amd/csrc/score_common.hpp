@@ -159,7 +159,11 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
   }
   __syncthreads();
   float u = z, y = x;
-  if (gram) {
+  if (pb.ind != 0) {
+    // attention-weight and value-norm indicators: no output term (u = 0, zz = 0), no key is
+    // evaluated by the leave-one-out form; the score pass then sees sqrt(vv) with vv = 1 or ||v||^2
+    u = 0.f; y = 0.f;
+  } else if (gram) {
     u = 0.f; y = 0.f;
 #pragma unroll 8
     for (int a = 0; a < D; ++a) {
@@ -205,7 +209,7 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
     rs_m[row] = M;
     rs_l[row] = l;
     rs_zz[row] = zz;
-    rs_nstar[row] = nstar;
+    rs_nstar[row] = pb.ind != 0 ? -1 : nstar;
     rs_istar[row] = sqrtf(fmaxf(qx, 0.f)) / l;      // A* ||(z_rest - v*) W_O||,  A* = 1/l
   }
   }

@@ -78,12 +78,17 @@ __device__ __forceinline__ RowInfo row_info(const Prob& pb, int g, int wave_bloc
   return r;
 }
 
-// vv without a projection: squared norm of the value row.  grid (ceil(P/256), Hkv)
+// vv without a projection: squared norm of the value row (1 for the attention-weight
+// indicator, which has no value term).  grid (ceil(P/256), Hkv)
 template <int D>
 __global__ __launch_bounds__(256) void k_vnorm2(Prob pb, const uint16_t* __restrict__ v,
                                                 float* __restrict__ vv, int ldv) {
   const int g = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
   if (n >= pb.P) return;
+  if (pb.ind == 1) {
+    for (int hl = 0; hl < pb.G; ++hl) vv[(int64_t)(g * pb.G + hl) * ldv + n] = 1.0f;
+    return;
+  }
   const uint16_t* vr = v + (int64_t)g * pb.kv_sh + (int64_t)n * pb.kv_st;
   float acc = 0.f;
 #pragma unroll
@@ -735,7 +740,10 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
 
   // A operands: local row rr = position * GP + head
   const float c2 = pb.scale * LOG2E;
-  const float Gf = (float)pb.G, invG = 1.f / Gf;
+  // Gf: what the exponent and the leave-one-out value fold in (G for the mean over the group,
+  // 1 for the maximum); Gd: the factor in 1 - A (0 for the indicators without 1 / (1 - A))
+  const float Gf = pb.gmax ? 1.f : (float)pb.G, invG = 1.f / Gf;
+  const float Gd = pb.ind != 0 ? 0.f : Gf;
   bf16x8 qf[KS], uhi[KS], ulo[KS];
   int nslane = -1;                                   // champion key of local row rr (for the tile test)
   {
@@ -917,7 +925,7 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
 #pragma unroll
         for (int e = 0; e < 8; ++e) a[e] = __builtin_amdgcn_exp2f(a[e]);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) den[e] = fmaf(-Gf, a[e], 1.f);
+        for (int e = 0; e < 8; ++e) den[e] = fmaf(-Gd, a[e], 1.f);
 #pragma unroll
         for (int e = 0; e < 8; ++e) a[e] *= fabsf(x[e]);
 #pragma unroll
@@ -955,40 +963,45 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
           if (nk[mb] == ns) sacc[mb][j] = is;
       }
     }
-    // ---- mean over the group (in-lane, one half swap from GP = 8 on), store ----
+    // ---- mean (or maximum) over the group (in-lane, one half swap from GP = 8 on), store ----
     float outv[2][NOUT];
+    auto group_reduce = [&](auto maxc) {
+      auto comb = [](float x, float y) { return decltype(maxc)::value ? fmaxf(x, y) : x + y; };
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      if constexpr (GP <= 4) {
+      for (int mb = 0; mb < 2; ++mb) {
+        if constexpr (GP <= 4) {
 #pragma unroll
-        for (int a = 0; a < NOUT; ++a) {
-          float s = sacc[mb][GP * a];
+          for (int a = 0; a < NOUT; ++a) {
+            float s = sacc[mb][GP * a];
 #pragma unroll
-          for (int e = 1; e < GP; ++e) s += sacc[mb][GP * a + e];
-          outv[mb][a] = s;
-        }
-      } else {
-        constexpr int RPG = GP / 2;                 // registers per group inside one lane half
-        float s[16 / RPG];
-#pragma unroll
-        for (int a = 0; a < 16 / RPG; ++a) {
-          s[a] = sacc[mb][RPG * a];
-#pragma unroll
-          for (int e = 1; e < RPG; ++e) s[a] += sacc[mb][RPG * a + e];
-        }
-        if constexpr (16 / RPG >= 2) {
-#pragma unroll
-          for (int a = 0; a < 16 / RPG; a += 2) {
-            // lower half ends up with the total of position a, upper half with that of a + 1
-            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(s[a]), __float_as_uint(s[a + 1]),
-                                                            false, false);
-            outv[mb][a / 2] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+            for (int e = 1; e < GP; ++e) s = comb(s, sacc[mb][GP * a + e]);
+            outv[mb][a] = s;
           }
         } else {
-          outv[mb][0] = xhalf_sum(s[0]);            // both halves hold (and store) the same total
+          constexpr int RPG = GP / 2;                 // registers per group inside one lane half
+          float s[16 / RPG];
+#pragma unroll
+          for (int a = 0; a < 16 / RPG; ++a) {
+            s[a] = sacc[mb][RPG * a];
+#pragma unroll
+            for (int e = 1; e < RPG; ++e) s[a] = comb(s[a], sacc[mb][RPG * a + e]);
+          }
+          if constexpr (16 / RPG >= 2) {
+#pragma unroll
+            for (int a = 0; a < 16 / RPG; a += 2) {
+              // lower half ends up with the total of position a, upper half with that of a + 1
+              const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(s[a]), __float_as_uint(s[a + 1]),
+                                                              false, false);
+              outv[mb][a / 2] = comb(__uint_as_float(r[0]), __uint_as_float(r[1]));
+            }
+          } else {
+            // both halves hold (and store) the same total
+            outv[mb][0] = decltype(maxc)::value ? xhalf_max(s[0]) : xhalf_sum(s[0]);
+          }
         }
       }
-    }
+    };
+    if (pb.gmax) group_reduce(std::true_type{}); else group_reduce(std::false_type{});
     if constexpr (MODE == 1) {
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
@@ -1166,6 +1179,7 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
   kps = (kps + TN - 1) / TN * TN;
   RK_LAUNCH(ST_ATTN, st, (k_attn_pipe<D>), dim3(S, gy, pb.Hkv), dim3(512), 0, st, pb, qq, kk, vp, S, kps,
             log2iw, w);
+  if (pb.ind != 0) gram = nullptr;                 // the attention-weight and value-norm indicators have no projection
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<bf16_t, D>), combine_grid(pb), combine_block<D>(), 0, st, pb,
             (const bf16_t*)v, S, gram, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
             w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, (const bf16_t*)q, w.op, ilog2(gp), lay.nwb, combine_groups(pb));
@@ -1256,6 +1270,7 @@ int score_pass_chunks(const Prob& pb) { return score_geom(pb).chunks; }
 
 bool fused_eligible(const Prob& pb, const void* q, const void* k, const void* v) {
   if (!mfma_eligible(pb, q, k, v) || !pb.adaptive) return false;
+  if (pb.ind != 0 || pb.gmax || pb.tmode != 0 || pb.pmax) return false;
   const ScoreGeom sg = score_geom(pb);
   if (sg.gy != 1 || sg.gp < 4 || sg.gp > 8) return false;
   if (pb.P < 32768 || pb.P >= (1 << 29)) return false;          // sampling pays off; 29-bit positions

@@ -261,10 +261,17 @@ __global__ __launch_bounds__(256) void k_score(Prob pb, const T* __restrict__ q,
             cx = fmaf(Us[rl][c], Vs[kk][c], cx);
           }
           const float e = exp2f(dot * c2 - m);
-          const float dist2 = zz - 2.f * cx + vv[(int64_t)h * ldv + n];
-          float val = e / (l - e) * sqrtf(fmaxf(dist2, 0.f));
-          if (n == nstar) val = istar;
-          out[j] += val;
+          const float vvn = vv[(int64_t)h * ldv + n];
+          float val;
+          if (pb.ind == 0) {
+            const float dist2 = zz - 2.f * cx + vvn;
+            val = e / (l - e) * sqrtf(fmaxf(dist2, 0.f));
+            if (n == nstar) val = istar;
+          } else {                             // attention weight, optionally times ||v_n|| (vv = ||v_n||^2 here)
+            val = e / l;
+            if (pb.ind == 2) val *= sqrtf(vvn);
+          }
+          out[j] = pb.gmax ? fmaxf(out[j], val) : out[j] + val;
         }
       }
     }
@@ -272,7 +279,7 @@ __global__ __launch_bounds__(256) void k_score(Prob pb, const T* __restrict__ q,
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int n = n0 + ln + 16 * j;
-        if (n < pb.P) score[((int64_t)g * pb.W + i) * pb.ld + n] = out[j] * invG;
+        if (n < pb.P) score[((int64_t)g * pb.W + i) * pb.ld + n] = pb.gmax ? out[j] : out[j] * invG;
       }
     }
   }
@@ -286,6 +293,7 @@ int run(const Prob& pb, const void* q, const void* k, const void* v, const float
   const T* vp = (const T*)v;
   const ScorePtrs w = score_ptrs(ws, lay);
   const int S = lay.S_simple;
+  if (pb.ind != 0) gram = nullptr;                 // no projection: vv becomes the squared norm of the value row
   RK_LAUNCH(ST_ATTN, st, (k_attn_partial<T, D>), dim3(S, (pb.R + RB - 1) / RB, pb.Hkv), dim3(256), 0, st,
                      pb, qq, kk, vp, S, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z);
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<T, D>), combine_grid(pb), combine_block<D>(), 0, st, pb, vp, S, gram,

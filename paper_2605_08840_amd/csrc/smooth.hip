@@ -96,12 +96,17 @@ constexpr int EW_POS = 1024;        // prefix positions per wavefront
 constexpr int EW_NE = EW_POS / 64;  // elements per lane and row (16 = four quads)
 constexpr int EPF = 4;              // rows in flight
 
-// weight of window query i in the temporal smoothing (wave-uniform)
+// weight of window query i in the temporal smoothing (wave-uniform): the EMA recursion of
+// Sec. 3.3 unrolled, or one of the alternatives of the ablation study (mean; the recursion run
+// from the newest query to the oldest)
 __device__ __forceinline__ float temporal_weight(const Prob& pb, int i) {
-  const int n = pb.W - 1 - i;                      // queries after this one
+  if (pb.tmode == 1) return 1.0f / (float)pb.W;
+  const bool inv = pb.tmode == 2;
+  const int n = inv ? i : pb.W - 1 - i;            // queries the recursion visits after this one
+  const bool first = inv ? i == pb.W - 1 : i == 0;  // the query the recursion starts from
   const float b = 1.0f - pb.alpha;
   const float decay = n == 0 ? 1.0f : exp2f((float)n * log2f(b));    // b = 0: 2^-inf = 0
-  return (i == 0 ? 1.0f : pb.alpha) * decay;
+  return (first ? 1.0f : pb.alpha) * decay;
 }
 
 // position of element k (bit 15 - k of a lane's string) of lane l of the wavefront that starts at wbase
@@ -500,6 +505,11 @@ __global__ __launch_bounds__(256) void k_box(Prob pb, const float* __restrict__ 
   const int half = w_s / 2;
   const int lo = max(0, n + gamma - half), hi = min(pb.P - 1, n + gamma + half);
   float s = 0.f;
+  if (pb.pmax) {                                   // max pooling (ablation study): positions inside the prefix only
+    for (int m = lo; m <= hi; ++m) s = m == lo ? e[m] : fmaxf(s, e[m]);
+    fin[(int64_t)g * pb.ld + n] = s;
+    return;
+  }
   for (int m = lo; m <= hi; ++m) s += e[m];
   fin[(int64_t)g * pb.ld + n] = s / (float)w_s;
 }

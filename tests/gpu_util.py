@@ -40,8 +40,9 @@ def run_gpu_layer(rk, w, q, k, v, wo, dev="cuda", **over):
     return out
 
 
-def oracle_score(oracle, w, q, k, v, wo, heads=None, rows=None, causal=True, scale=None):
-    """Oracle indicator with the per-element tolerance. Returns {g: (Ig [nq,P], tol [nq,P])}."""
+def oracle_score(oracle, w, q, k, v, wo, heads=None, rows=None, causal=True, scale=None, group="mean"):
+    """Oracle indicator with the per-element tolerance. Returns {g: (Ig [nq,P], tol [nq,P])}.
+    group='max': the largest indicator of the group, with the largest of the heads' tolerances."""
     qn, kn, vn = (t.float().numpy() for t in (q, k, v))
     G, d, W = w.group, w.head_dim, w.window
     scale = 1.0 / np.sqrt(d) if scale is None else scale
@@ -51,11 +52,11 @@ def oracle_score(oracle, w, q, k, v, wo, heads=None, rows=None, causal=True, sca
     for g in (range(w.n_kv_heads) if heads is None else heads):
         fg = None if fac is None else fac[g * G:(g + 1) * G]
         Ig, I, A, ub = oracle.score_head(qn[g * G:(g + 1) * G], kn[g], vn[g], fg, W, scale, causal,
-                                         rows=rows, aux=True)
+                                         rows=rows, aux=True, group=group)
         with np.errstate(divide="ignore", invalid="ignore"):
             second = np.minimum(np.where(I > 0, kappa * ub * ub / (2 * I), np.inf), np.sqrt(kappa) * ub)
         second = np.where(A > 0.5, 0.0, second)        # dominant token: leave-one-out form, no cancellation
-        tol = (RTOL * I + second).mean(axis=0)
+        tol = (RTOL * I + second).mean(axis=0) if group == "mean" else (RTOL * I + second).max(axis=0)
         res[g] = (Ig, tol)
     return res
 

@@ -47,7 +47,8 @@ def test_workspace_bytes(rk):
     assert rk.restkv_workspace_bytes(big) > 32 * 131008 * 4      # holds v M v^T for every head
     for bad in (dict(budget=32), dict(budget=2000), dict(n_q_heads=5), dict(window=0),
                 dict(window=1024), dict(base_window=4), dict(ema_alpha=1.5), dict(beta=0.0),
-                dict(beta=1e-7)):          # floor(|x| / beta) would leave the 32-bit range
+                dict(beta=1e-7),           # floor(|x| / beta) would leave the 32-bit range
+                dict(variant=3), dict(variant=0x30), dict(variant=0x80), dict(variant=8)):
         assert rk.restkv_workspace_bytes(good(rk, **bad)) == 0, bad
 
 

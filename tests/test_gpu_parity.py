@@ -594,3 +594,94 @@ def test_folded_layers_full_size_differ_only_at_near_ties(rk):
     assert differing <= 2 * Lyr * Hkv, differing
     print(f"folded vs per-layer: {differing} differing entries of {Lyr * Hkv * (w.budget - w.window)}")
 
+
+# ------------------------------------------------------------------ ablation variants (Sec. 4, App.)
+@pytest.mark.parametrize("case,indicator,group", [
+    ("bf16_sinks_g8", "attention", "mean"),        # matrix-core path, G = 8, dominant keys
+    ("bf16_g3", "value_norm", "mean"),             # padded group
+    ("bf16_mha", "value_norm", "max"),             # G = 1
+    ("bf16_g16", "attention", "max"),
+    ("f32_sinks", "value_norm", "max"),            # FP32 kernels
+    ("f32_d64_ragged", "attention", "mean"),
+])
+def test_variant_indicators_against_oracle(rk, oracle_mod, case, indicator, group):
+    """Attention-weight and value-norm indicators (App., indicator table), mean or maximum over the group."""
+    w = _case(case)
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    var = {"attention": rk.RESTKV_IND_ATTENTION, "value_norm": rk.RESTKV_IND_VALUE_NORM}[indicator]
+    var |= rk.RESTKV_GROUP_MAX if group == "max" else 0
+    got = run_gpu_layer(rk, w, q, k, v, wo, variant=var)
+    qn, kn, vn = (t.float().numpy() for t in (q, k, v))
+    G = w.group
+    for g in range(w.n_kv_heads):
+        ref = oracle_mod.score_head(qn[g * G:(g + 1) * G], kn[g], vn[g], None, w.window, 1 / np.sqrt(w.head_dim),
+                                    indicator=indicator, group=group)
+        np.testing.assert_allclose(got["score"][g], ref, rtol=RTOL, atol=1e-30, err_msg=f"{case} head {g}")
+
+
+@pytest.mark.parametrize("case", ["bf16_sinks_g8", "bf16_g3", "f32_sinks", "bf16_g16"])
+def test_variant_group_max_of_the_reconstruction_indicator(rk, oracle_mod, case):
+    w = _case(case)
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    got = run_gpu_layer(rk, w, q, k, v, wo, variant=rk.RESTKV_GROUP_MAX)
+    ref = oracle_score(oracle_mod, w, q, k, v, wo, group="max")
+    for g, (Ig, tol) in ref.items():
+        assert_score_close(got["score"][g], Ig, tol, f"{case} group max head {g}")
+
+
+@pytest.mark.parametrize("temporal,pool,W,P,B,k,alpha", [
+    ("mean", "avg", 8, 5000, 300, 5, 0.3),
+    ("inv_ema", "avg", 7, 3001, 500, 3, 0.1),
+    ("ema", "max", 16, 20000, 512, 5, 0.3),
+    ("inv_ema", "max", 70, 6000, 400, 21, 0.2),
+    ("mean", "max", 1, 900, 50, 5, 0.3),
+])
+def test_variant_smoothing_stage_exact(rk, oracle_mod, temporal, pool, W, P, B, k, alpha):
+    """Mean / inverse-EMA temporal smoothing and max pooling (App., smoothing table) on the same FP32
+    scores as the oracle: smoothed score to rounding, pooled score and selection exact."""
+    Hkv, d, beta = 3, 64, 100.0
+    L = P + W
+    s = _smooth_select_inputs(17, Hkv, W, P, "drifting" if W > 1 else "lognormal")
+    var = {"ema": 0, "mean": rk.RESTKV_TEMPORAL_MEAN, "inv_ema": rk.RESTKV_TEMPORAL_INV_EMA}[temporal]
+    var |= rk.RESTKV_POOL_MAX if pool == "max" else 0
+    p = rk.make_params(n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=d, seq_len=L, window=W, budget=B, dtype="bf16",
+                       ema_alpha=alpha, base_window=k, beta=beta, variant=var)
+    buf = rk.alloc_layer_buffers(p, torch.bfloat16, "cuda")
+    buf.score.copy_(torch.from_numpy(s))
+    rk.restkv_smooth(p, buf.score, buf.ema, buf.final, buf.aws_info, buf.aws_d, buf.workspace)
+    rk.restkv_select(p, buf.final, buf.idx, buf.workspace)
+    torch.cuda.synchronize()
+    ema, fin, info, idx = (t.cpu().numpy() for t in (buf.ema, buf.final, buf.aws_info, buf.idx))
+    for g in range(Hkv):
+        sm = oracle_mod.smooth_head(s[g], alpha, beta, k, True, B, temporal, pool)
+        np.testing.assert_allclose(ema[g], sm["ema"], rtol=1e-5, atol=1e-30)
+        assert tuple(info[g]) == (sm["w_s"], sm["gamma"])
+        e64 = ema[g].astype(np.float64)
+        if pool == "max":
+            np.testing.assert_array_equal(fin[g], oracle_mod.pool_max(e64, sm["w_s"], sm["gamma"]).astype(np.float32))
+        else:
+            np.testing.assert_allclose(fin[g], oracle_mod.box(e64, sm["w_s"], sm["gamma"]), rtol=1e-5, atol=1e-30)
+        np.testing.assert_array_equal(idx[g], oracle_mod.select(fin[g].astype(np.float64), W, B))
+
+
+def test_variant_whole_path_llama_8k(rk, oracle_mod):
+    """llama_8k with every switch set (value-norm indicator, group maximum, mean over the window,
+    max pooling of size 5, no adaptive window): whole path against the oracle, three heads."""
+    w = workloads.WORKLOADS["llama_8k"]
+    q, k, v = workloads.make_qkv(w)
+    var = rk.RESTKV_IND_VALUE_NORM | rk.RESTKV_GROUP_MAX | rk.RESTKV_TEMPORAL_MEAN | rk.RESTKV_POOL_MAX
+    got = run_gpu_layer(rk, w, q, k, v, None, variant=var, adaptive=False)
+    qn, kn, vn = (t.float().numpy() for t in (q, k, v))
+    G = w.group
+    for g in (1, 4, 6):
+        Ig = oracle_mod.score_head(qn[g * G:(g + 1) * G], kn[g], vn[g], None, w.window, 1 / np.sqrt(w.head_dim),
+                                   indicator="value_norm", group="max")
+        np.testing.assert_allclose(got["score"][g], Ig, rtol=RTOL, atol=1e-30)
+        sm = oracle_mod.smooth_head(Ig, w.alpha, w.beta, w.base_window, False, w.budget, "mean", "max")
+        assert tuple(got["aws_info"][g]) == (5, 0)
+        np.testing.assert_allclose(got["final"][g], sm["final"], rtol=2 * RTOL, atol=1e-30)
+        check_selection(got["idx"][g], sm["final"], w.window, w.budget, 4 * RTOL)
+        assert np.array_equal(got["k_out"][g], kn[g][got["idx"][g]])
+
