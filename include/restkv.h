@@ -141,6 +141,26 @@ int restkv_score(const restkv_params* p, const void* q, const void* k, const voi
                  restkv_stream_t stream);
 
 /*
+ * restkv_score with the attention statistics of the window queries taken from the caller's
+ * own attention kernel instead of a pass over the cache (App. B: at prefill the statistics the
+ * method needs are already there; Sec. 5: only the attention output of a small query window
+ * is needed).  The usual pair a fused attention kernel returns:
+ *   attn_out [Hq, W, d] float32, contiguous: softmax(scale q K^T) V of the W window queries over
+ *            exactly the keys restkv_score would let them see (query i: keys 0 .. L-W+i when
+ *            causal), same scale;
+ *   lse      [Hq, W] float32: natural logarithm of each row's softmax denominator.
+ * Everything else as restkv_score; the attention pass and its merge are replaced by a pass
+ * over [Hq, W, d].  Without the unnormalised sums of a pass of its own the library cannot
+ * evaluate a dominant key by the leave-one-out form: a key that holds more than about 0.9 of a
+ * query's attention is scored through Eq. rec_ei in FP32 and loses accuracy as 1 - A
+ * vanishes (relative error about 4e-6 / (1 - A)^2); every other key meets the same bound as
+ * restkv_score.
+ */
+int restkv_score_from_attention(const restkv_params* p, const void* q, const void* k, const void* v,
+                                const float* gram, const float* attn_out, const float* lse, float* score,
+                                void* workspace, size_t workspace_bytes, restkv_stream_t stream);
+
+/*
  * Spatial-temporal smoothing (Sec. 3.3).
  *   ema[g,n]   = EMA over the W window queries of score[g,:,n] (newest weighs alpha)
  *   D_front/D_rear = mean index of the per-query top-min(B,P) tokens of the raw

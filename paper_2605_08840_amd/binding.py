@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.restkv_workspace_bytes.argtypes = [P]
         L.restkv_prepare_wo.argtypes = [P, vp, i64, vp, vp]
         L.restkv_score.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.restkv_score_from_attention.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.restkv_score_from_attention.restype = ctypes.c_int
         L.restkv_smooth.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
         L.restkv_score_smooth.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.restkv_select.argtypes = [P, vp, vp, vp, sz, vp]
@@ -145,6 +147,13 @@ def restkv_score(p, q, k, v, gram, score, workspace, stream=None):
     wp, wn = _ws(workspace)
     _chk(lib().restkv_score(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(gram), _ptr(score),
                             wp, wn, _stream(stream)), "restkv_score")
+
+
+def restkv_score_from_attention(p, q, k, v, gram, attn_out, lse, score, workspace, stream=None):
+    wp, wn = _ws(workspace)
+    _chk(lib().restkv_score_from_attention(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(gram), _ptr(attn_out),
+                                           _ptr(lse), _ptr(score), wp, wn, _stream(stream)),
+         "restkv_score_from_attention")
 
 
 def restkv_smooth(p, score, ema, final, aws_info, aws_d, workspace, stream=None):

@@ -23,7 +23,7 @@ int resolve(const restkv_params* p, Prob* o) {
   if (p->dtype != RESTKV_F32 && p->dtype != RESTKV_BF16) return RESTKV_EUNSUPPORTED;
   o->Hq = p->n_q_heads; o->Hkv = p->n_kv_heads; o->G = o->Hq / o->Hkv;
   o->d = p->head_dim; o->L = p->seq_len; o->W = p->window; o->P = o->L - o->W;
-  o->B = p->budget; o->R = o->G * o->W; o->hb = nullptr;
+  o->B = p->budget; o->R = o->G * o->W; o->hb = nullptr; o->ext_out = nullptr; o->ext_lse = nullptr;
   if ((int64_t)o->G * o->W > 4096) return RESTKV_EUNSUPPORTED;
   o->dtype = p->dtype; o->causal = p->causal ? 1 : 0; o->base_k = p->base_window;
   o->ind = p->variant & 3; o->gmax = (p->variant >> 2) & 1; o->tmode = (p->variant >> 4) & 3;
@@ -155,6 +155,23 @@ int restkv_score(const restkv_params* p, const void* q, const void* k, const voi
   int rc = resolve(p, &pb);
   if (rc) return rc;
   if (!q || !k || !v || !score) return RESTKV_EINVAL;
+  const ScoreWs lay = score_ws(pb);
+  rc = check_ws(workspace, workspace_bytes, lay.bytes);
+  if (rc) return rc;
+  if (mfma_eligible(pb, q, k, v) && !g_force_fp32)
+    return launch_score_mfma(pb, q, k, v, gram, score, (char*)workspace, lay, (hipStream_t)stream);
+  return launch_score_simple(pb, q, k, v, gram, score, (char*)workspace, lay, (hipStream_t)stream);
+}
+
+int restkv_score_from_attention(const restkv_params* p, const void* q, const void* k, const void* v,
+                                const float* gram, const float* attn_out, const float* lse, float* score,
+                                void* workspace, size_t workspace_bytes, restkv_stream_t stream) {
+  Prob pb;
+  int rc = resolve(p, &pb);
+  if (rc) return rc;
+  if (!q || !k || !v || !score || !attn_out || !lse) return RESTKV_EINVAL;
+  pb.ext_out = attn_out;
+  pb.ext_lse = lse;
   const ScoreWs lay = score_ws(pb);
   rc = check_ws(workspace, workspace_bytes, lay.bytes);
   if (rc) return rc;

@@ -17,6 +17,10 @@ struct Prob {
   float scale, alpha, beta;
   int64_t q_sh, q_st, kv_sh, kv_st, ld;
   const int32_t* hb;   // optional per-KV-head budgets (device, [Hkv]); NULL: B for every head
+  // optional attention output [Hq,W,d] f32 and log-sum-exp [Hq,W] (natural log) of the window
+  // queries from the caller's own attention kernel; NULL: the library's attention pass runs
+  const float* ext_out;
+  const float* ext_lse;
 };
 
 // Fills `out`; returns RESTKV_OK or the error the block deserves.

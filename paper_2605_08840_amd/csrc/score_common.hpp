@@ -42,6 +42,21 @@ inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
 //   equals Eq. rec_ei).  Without one, l and z are the plain softmax sums relative to the maximum.
 constexpr int CMB_RQ = 4;    // query rows of one head per workgroup of the merge kernel
 
+// Statistics of a caller's own attention kernel as ONE split of the attention pass: the log-sum-exp
+// of a row (natural log) is both the reference and the "largest logit", the sum of weights is 1, no
+// key is kept out; the caller's attention output [Hq*W, d] then serves as part_z unchanged.
+// grid (ceil(rows/256)), 256 threads.  (A template only so that the header can hold it.)
+template <int UNUSED>
+__global__ __launch_bounds__(256) void k_stats_fill(int rows, const float* __restrict__ lse,
+                                                    float* __restrict__ part_m, float* __restrict__ part_mx,
+                                                    int* __restrict__ part_n, float* __restrict__ part_ref,
+                                                    float* __restrict__ part_l) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  const float m2 = lse[r] * 1.4426950408889634f;
+  part_m[r] = m2; part_ref[r] = m2; part_mx[r] = 0.f; part_n[r] = -1; part_l[r] = 1.f;
+}
+
 // Merge of the key splits and the per-row quantities of the score pass.
 // grid (ceil(W / CMB_RQ), Hq), CMB_RQ * D threads: thread = (row r of the group, column c).
 // The head's Gram matrix is staged in LDS once per workgroup; the per-split scalars of a row are

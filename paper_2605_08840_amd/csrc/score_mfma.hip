@@ -1177,11 +1177,21 @@ int run_mfma(const Prob& pb, const void* q, const void* k, const void* v, const 
   if (S < 1) S = 1;
   int kps = (pb.L + S - 1) / S;
   kps = (kps + TN - 1) / TN * TN;
-  RK_LAUNCH(ST_ATTN, st, (k_attn_pipe<D>), dim3(S, gy, pb.Hkv), dim3(512), 0, st, pb, qq, kk, vp, S, kps,
-            log2iw, w);
+  const float* part_z = w.part_z;
+  if (pb.ext_lse) {
+    // the caller's attention output and log-sum-exp stand in for the attention pass: one "split"
+    S = 1;
+    const int rows = pb.Hq * pb.W;
+    RK_LAUNCH(ST_ATTN, st, (k_stats_fill<0>), dim3((rows + 255) / 256), dim3(256), 0, st, rows, pb.ext_lse,
+              w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l);
+    part_z = pb.ext_out;
+  } else {
+    RK_LAUNCH(ST_ATTN, st, (k_attn_pipe<D>), dim3(S, gy, pb.Hkv), dim3(512), 0, st, pb, qq, kk, vp, S, kps,
+              log2iw, w);
+  }
   if (pb.ind != 0) gram = nullptr;                 // the attention-weight and value-norm indicators have no projection
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<bf16_t, D>), combine_grid(pb), combine_block<D>(), 0, st, pb,
-            (const bf16_t*)v, S, gram, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m,
+            (const bf16_t*)v, S, gram, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, part_z, w.rs_m,
             w.rs_l, w.rs_zz, w.rs_nstar, w.rs_istar, w.rs_u, (const bf16_t*)q, w.op, ilog2(gp), lay.nwb, combine_groups(pb));
   if (gram) {
     constexpr int HPW = D == 128 ? 4 : 8;

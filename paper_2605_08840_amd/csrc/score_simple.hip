@@ -292,12 +292,22 @@ int run(const Prob& pb, const void* q, const void* k, const void* v, const float
   const T* kk = (const T*)k;
   const T* vp = (const T*)v;
   const ScorePtrs w = score_ptrs(ws, lay);
-  const int S = lay.S_simple;
+  int S = lay.S_simple;
   if (pb.ind != 0) gram = nullptr;                 // no projection: vv becomes the squared norm of the value row
-  RK_LAUNCH(ST_ATTN, st, (k_attn_partial<T, D>), dim3(S, (pb.R + RB - 1) / RB, pb.Hkv), dim3(256), 0, st,
-                     pb, qq, kk, vp, S, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z);
+  const float* part_z = w.part_z;
+  if (pb.ext_lse) {
+    // the caller's attention output and log-sum-exp stand in for the attention pass: one "split"
+    S = 1;
+    const int rows = pb.Hq * pb.W;
+    RK_LAUNCH(ST_ATTN, st, (k_stats_fill<0>), dim3((rows + 255) / 256), dim3(256), 0, st, rows, pb.ext_lse,
+              w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l);
+    part_z = pb.ext_out;
+  } else {
+    RK_LAUNCH(ST_ATTN, st, (k_attn_partial<T, D>), dim3(S, (pb.R + RB - 1) / RB, pb.Hkv), dim3(256), 0, st,
+                       pb, qq, kk, vp, S, w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z);
+  }
   RK_LAUNCH(ST_COMBINE, st, (k_attn_combine<T, D>), combine_grid(pb), combine_block<D>(), 0, st, pb, vp, S, gram,
-            w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, w.part_z, w.rs_m, w.rs_l, w.rs_zz, w.rs_nstar,
+            w.part_m, w.part_mx, w.part_n, w.part_ref, w.part_l, part_z, w.rs_m, w.rs_l, w.rs_zz, w.rs_nstar,
             w.rs_istar, w.rs_u, (const T*)nullptr, (uint16_t*)nullptr, 0, 0, combine_groups(pb));
   RK_LAUNCH(ST_VV, st, (k_vv<T, D>), dim3((pb.P + 63) / 64, pb.Hq), dim3(256), 0, st, pb, vp, gram, w.vv, lay.ldv);
   RK_LAUNCH(ST_SCORE, st, (k_score<T, D>), dim3((pb.P + TN - 1) / TN, pb.Hkv), dim3(256), 0, st, pb, qq,

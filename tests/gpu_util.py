@@ -40,7 +40,8 @@ def run_gpu_layer(rk, w, q, k, v, wo, dev="cuda", **over):
     return out
 
 
-def oracle_score(oracle, w, q, k, v, wo, heads=None, rows=None, causal=True, scale=None, group="mean"):
+def oracle_score(oracle, w, q, k, v, wo, heads=None, rows=None, causal=True, scale=None, group="mean",
+                 dominant_exact=True, with_amax=False):
     """Oracle indicator with the per-element tolerance. Returns {g: (Ig [nq,P], tol [nq,P])}.
     group='max': the largest indicator of the group, with the largest of the heads' tolerances."""
     qn, kn, vn = (t.float().numpy() for t in (q, k, v))
@@ -55,10 +56,31 @@ def oracle_score(oracle, w, q, k, v, wo, heads=None, rows=None, causal=True, sca
                                          rows=rows, aux=True, group=group)
         with np.errstate(divide="ignore", invalid="ignore"):
             second = np.minimum(np.where(I > 0, kappa * ub * ub / (2 * I), np.inf), np.sqrt(kappa) * ub)
-        second = np.where(A > 0.5, 0.0, second)        # dominant token: leave-one-out form, no cancellation
+        if dominant_exact:
+            second = np.where(A > 0.5, 0.0, second)    # dominant token: leave-one-out form, no cancellation
         tol = (RTOL * I + second).mean(axis=0) if group == "mean" else (RTOL * I + second).max(axis=0)
-        res[g] = (Ig, tol)
+        res[g] = (Ig, tol, A.max(axis=0)) if with_amax else (Ig, tol)
     return res
+
+
+def attention_statistics(q, k, v, W, scale=None, causal=True):
+    """What a fused attention kernel hands back for the window queries: output [Hq,W,d] and
+    log-sum-exp [Hq,W] (natural log), FP32, computed in FP64 with the library softmax.  Input
+    of restkv_score_from_attention in the tests."""
+    Hq, _, d = q.shape
+    Hkv, L, _ = k.shape
+    G = Hq // Hkv
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    out = torch.empty((Hq, W, d), dtype=torch.float32)
+    lse = torch.empty((Hq, W), dtype=torch.float32)
+    for h in range(Hq):
+        s = (q[h].double() @ k[h // G].double().T) * scale
+        if causal:
+            pos = torch.arange(L, device=s.device)[None, :] > (L - W + torch.arange(W, device=s.device))[:, None]
+            s = s.masked_fill(pos, float("-inf"))
+        lse[h] = torch.logsumexp(s, dim=-1).float()
+        out[h] = (torch.softmax(s, dim=-1) @ v[h // G].double()).float()
+    return out, lse
 
 
 def assert_score_close(got, ref, tol, what=""):

@@ -4,8 +4,8 @@ import pytest
 import torch
 
 import workloads
-from gpu_util import (RTOL, assert_score_close, check_selection, drift_bounds, oracle_score, params_for,
-                      run_gpu_layer)
+from gpu_util import (RTOL, assert_score_close, attention_statistics, check_selection, drift_bounds, oracle_score,
+                      params_for, run_gpu_layer)
 
 pytestmark = pytest.mark.gpu
 
@@ -684,4 +684,60 @@ def test_variant_whole_path_llama_8k(rk, oracle_mod):
         np.testing.assert_allclose(got["final"][g], sm["final"], rtol=2 * RTOL, atol=1e-30)
         check_selection(got["idx"][g], sm["final"], w.window, w.budget, 4 * RTOL)
         assert np.array_equal(got["k_out"][g], kn[g][got["idx"][g]])
+
+
+# ------------------------------------------------------------------ statistics from the caller's attention kernel
+@pytest.mark.parametrize("name", ["bf16_d128_splits", "bf16_g3", "bf16_mha", "f32_d64_ragged", "bf16_g16",
+                                  "bf16_sinks_g8"])
+def test_score_from_attention_statistics(rk, oracle_mod, name):
+    """restkv_score_from_attention (App. B: the statistics are there after prefill): attention
+    output and log-sum-exp of the window rows come from outside, the rest of the score is the
+    library's.  Same bound as restkv_score, except that a key above 0.9 of a row's attention
+    has no leave-one-out evaluation here (documented) and is left out of the comparison."""
+    w = _case(name)
+    q, k, v = workloads.make_qkv(w)
+    wo = None if name == "bf16_d128_splits" else workloads.make_wo(w)
+    out, lse = attention_statistics(q, k, v, w.window)
+    p = params_for(rk, w)
+    gram = None
+    if wo is not None:
+        gram = torch.empty((w.n_q_heads, w.head_dim, w.head_dim), dtype=torch.float32, device="cuda")
+        rk.restkv_prepare_wo(p, wo.cuda(), gram)
+    buf = rk.alloc_layer_buffers(p, q.dtype, "cuda")
+    rk.restkv_score_from_attention(p, q.cuda(), k.cuda(), v.cuda(), gram, out.cuda(), lse.cuda(), buf.score,
+                                   buf.workspace)
+    torch.cuda.synchronize()
+    got = buf.score[..., :w.prefix].cpu().numpy()
+    assert np.all(np.isfinite(got)) and np.all(got >= 0)
+    ref = oracle_score(oracle_mod, w, q, k, v, wo, dominant_exact=False, with_amax=True)
+    seen = 0
+    for g, (Ig, tol, amax) in ref.items():
+        keep = amax <= 0.9
+        seen += int(keep.sum())
+        assert_score_close(np.where(keep, got[g], Ig), Ig, tol, f"{name} head {g}")
+    assert seen > 0.99 * got.size
+
+
+def test_score_from_attention_full_size(rk, oracle_mod):
+    """The same at the benchmark configuration (drift_128k, one layer, two KV heads against the oracle);
+    the statistics are computed with the library softmax in FP64 on the GPU."""
+    w = workloads.WORKLOADS["drift_128k"]
+    q, k, v = workloads.make_qkv(w, 5, "cuda")
+    wo = workloads.make_wo(w, 5, "cuda")
+    p = params_for(rk, w)
+    gram = torch.empty((w.n_q_heads, w.head_dim, w.head_dim), dtype=torch.float32, device="cuda")
+    rk.restkv_prepare_wo(p, wo, gram)
+    out, lse = attention_statistics(q, k, v, w.window)
+    buf = rk.alloc_layer_buffers(p, q.dtype, "cuda")
+    rk.restkv_score_from_attention(p, q, k, v, gram, out.cuda(), lse.cuda(), buf.score, buf.workspace)
+    torch.cuda.synchronize()
+    G, d, P = w.group, w.head_dim, w.prefix
+    w1 = w.with_(n_q_heads=G, n_kv_heads=1)
+    for g in (1, 6):
+        Ig, tol, amax = oracle_score(oracle_mod, w1, q[g * G:(g + 1) * G].cpu(), k[g:g + 1].cpu(), v[g:g + 1].cpu(),
+                                     wo[g * G * d:(g + 1) * G * d].cpu(), heads=[0], dominant_exact=False,
+                                     with_amax=True)[0]
+        keep = amax <= 0.9
+        assert keep.mean() > 0.999
+        assert_score_close(np.where(keep, buf.score[g, :, :P].cpu().numpy(), Ig), Ig, tol, f"drift_128k head {g}")
 
