@@ -35,6 +35,7 @@ inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
 //   part_z    sum over the included keys of 2^(logit - ref) * v
 // A split keeps a key out when, on arrival, it is the largest so far and holds more than 1/9
 // of the mass seen so far (always true for a key that ends with more than 1/9 of the total).
+// part_ref never follows a kept-out key, only keys that are part of the sums.
 // The merge keeps out the excluded key that is the overall maximum (if any) and folds every
 // other excluded key back in.  With a key kept out ("champion", weight A* = 1/l):
 //   l = 1 + l_rest, z = (v* + z_rest)/l, u = z M_h, zz = u.z, and the champion's indicator
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
   __shared__ __attribute__((aligned(16))) float Mh_s[D * D];   // the head's Gram matrix (unused when gram == NULL)
   __shared__ float zq[CMB_RQ][D], xq[CMB_RQ][D];
   __shared__ float red[CMB_RQ][NWV][2];
-  __shared__ float s_m[CMB_RQ][1], s_mx[CMB_RQ][SMAX], s_l[CMB_RQ][SMAX];
+  __shared__ float s_m[CMB_RQ][2], s_mx[CMB_RQ][SMAX], s_l[CMB_RQ][SMAX];
   __shared__ int s_n[CMB_RQ][SMAX + 1];      // [SMAX]: the split that holds the champion, or -1
   __shared__ float s_w[CMB_RQ][SMAX];
   const int h = blockIdx.y, g = h / pb.G;
@@ -119,14 +120,22 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
     // split whose kept-out key is the overall maximum: the earliest one (= lowest key)
     const unsigned long long cand = __ballot(pn >= 0 && pmx == M0);
     const int ss = cand ? __builtin_ctzll(cand) : -1;
-    const bool empty = pm == -INFINITY;
-    // weight of the split's sums (relative to its reference); weight of its kept-out key if that
-    // key joins the rest (it does unless it is the overall maximum); 0 for an empty split
-    s_w[r][c] = empty ? 0.f : exp2f(pref - M0);
-    s_l[r][c] = empty ? 0.f : pl;                  // an empty split's sums may hold anything
-    s_mx[r][c] = (!empty && pn >= 0 && c != ss) ? exp2f(pmx - M0) : 0.f;
+    // a split adds to the merged sums if it saw a key and its own sums are not empty; its
+    // kept-out key joins them unless it is the overall maximum
+    const bool has = pm != -INFINITY && pl > 0.f;
+    const bool joins = pm != -INFINITY && pn >= 0 && c != ss;
+    // The merged sums are relative to R, the largest logit that is part of them (reference of a
+    // split, logit of a joining key), NOT to the overall maximum M0: a kept-out key may be any
+    // distance above the rest without the rest's sums underflowing.
+    float R = has ? pref : -INFINITY;
+    if (joins) R = fmaxf(R, pmx);
+#pragma unroll
+    for (int sh = 32; sh >= 1; sh >>= 1) R = fmaxf(R, __shfl_xor(R, sh, 64));
+    s_w[r][c] = has ? exp2f(pref - R) : 0.f;
+    s_l[r][c] = has ? pl : 0.f;                    // an empty split's sums may hold anything
+    s_mx[r][c] = joins ? exp2f(pmx - R) : 0.f;
     s_n[r][c] = pn;
-    if (c == 0) { s_m[r][0] = M0; s_n[r][SMAX] = ss; }
+    if (c == 0) { s_m[r][0] = M0; s_m[r][1] = R == -INFINITY ? 0.f : exp2f(R - M0); s_n[r][SMAX] = ss; }
   }
   __syncthreads();
   const float M = s_m[r][0];
@@ -155,15 +164,17 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
       lrest += wv[k];
     }
   }
+  // rest -> units of the overall maximum (0 when the rest is below FP32 range next to the kept-out key)
+  const float fr = s_m[r][1];
   float l, z, x;
   if (nstar >= 0) {
     const float vstar = to_float(vg[(int64_t)nstar * pb.kv_st + c]);
-    l = 1.f + lrest;
-    z = (vstar + zr) / l;
+    l = 1.f + lrest * fr;
+    z = (vstar + zr * fr) / l;
     x = lrest > 0.f ? zr / lrest - vstar : 0.f;   // z_without_champion - v_champion
   } else {
-    l = lrest;
-    z = zr / l;
+    l = lrest * fr;
+    z = zr / lrest;
     x = 0.f;
   }
   zq[r][c] = z;

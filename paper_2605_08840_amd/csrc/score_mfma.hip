@@ -36,7 +36,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int TN = 64;                 // keys per LDS tile
 constexpr float LOG2E = 1.4426950408889634f;
-constexpr float RESCALE_TH = 8.0f;     // log2 units a row maximum may run ahead of its reference
+constexpr float RESCALE_TH = 8.0f;  // log2 units a row maximum may run ahead of its reference
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
@@ -515,20 +515,24 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
       // A key is kept out of the sums only if, on arrival, it is the largest so far AND would
       // hold more than 1/9 of the mass seen so far; such keys are rare after the first tile, so
       // the expensive part of the bookkeeping (index search, folding the previous kept-out key
-      // back in) almost never runs.  The reference of the exponentials follows the maximum lazily.
+      // back in) almost never runs.  The reference of the exponentials follows, lazily, the
+      // largest logit that is PART of the sums: a kept-out key may be any distance above the
+      // others without the others' sums losing anything.
       const bool newmax = tm > mall;
-      const bool resc = (tm - mref) * c2 > RESCALE_TH;
       bool excl_here = false;
-      if (__ballot(newmax || resc) != 0ull) {
+      // (no key of the tile is further ahead of the reference than the tile maximum)
+      if (__ballot(newmax || (tm - mref) * c2 > RESCALE_TH) != 0ull) {
         bool dominant = false;
         if (newmax) {
           const float pstar = __builtin_amdgcn_exp2f((tm - mref) * c2);      // inf on the first tile
           float total = xhalf_sum(lsum);
           if (nx >= 0) total += __builtin_amdgcn_exp2f((mx - mref) * c2);
-          dominant = pstar * 8.0f > total;
+          // total = inf: the key kept out so far is the whole mass in FP32, and tm is above it
+          dominant = pstar * 8.0f > total || total == INFINITY;
         }
+        float tref = tm;                 // largest logit that joins the sums at this tile
+        int cand = INT_MAX;
         if (__ballot(dominant) != 0ull) {
-          int cand = INT_MAX;
           if (dominant) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
@@ -537,35 +541,66 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
                 if (sacc[mb][j] == tm) cand = min(cand, kb + 32 * mb + cidx(j, hf));
           }
           cand = xhalf_min(cand);
-          if (dominant) {
-            if (nx >= 0) {             // the key kept out so far joins the running sums
-              const float w = __builtin_amdgcn_exp2f((mx - mref) * c2);
-              if (hf == 0) lsum += w;
-              const uint16_t* vr = vg + (int64_t)nx * pb.kv_st;
+          // Where the new kept-out key is at most 64 binary orders above a logit that is part of
+          // the sums, the reference may follow it as it follows any maximum (tref = tm): the sums
+          // keep every bit that matters.  Further up the reference becomes the largest logit that
+          // really joins the sums.  The logit it is measured against: the reference so far; on
+          // the first tile, the second largest of the row's eight partial maxima (no larger than
+          // the largest logit that joins).
+          float base = mref;
+          if (t == 0) {
+            const float a1 = fmaxf(tq[0], tq[1]), a2 = fminf(tq[0], tq[1]);
+            const float b1 = fmaxf(tq[2], tq[3]), b2 = fminf(tq[2], tq[3]);
+            const float l1 = fmaxf(a1, b1), l2 = fmaxf(fminf(a1, b1), fmaxf(a2, b2));   // the lane's top two
+            const auto r1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(l1), __float_as_uint(l1), false, false);
+            base = fmaxf(fminf(__uint_as_float(r1[0]), __uint_as_float(r1[1])), xhalf_max(l2));
+          }
+          const bool far = dominant && !((tm - base) * c2 <= 64.f);
+          if (__ballot(far) != 0ull) {
+            float ti = -INFINITY;        // the tile without its new kept-out key
+            if (far) {
 #pragma unroll
-              for (int cb = 0; cb < CB; ++cb)
+              for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int jq = 0; jq < 4; ++jq) {
-                  const uint2 u = *(const uint2*)(vr + 32 * cb + 8 * jq + 4 * hf);
-                  oacc[cb][4 * jq + 0] += w * __uint_as_float(u.x << 16);
-                  oacc[cb][4 * jq + 1] += w * __uint_as_float(u.x & 0xFFFF0000u);
-                  oacc[cb][4 * jq + 2] += w * __uint_as_float(u.y << 16);
-                  oacc[cb][4 * jq + 3] += w * __uint_as_float(u.y & 0xFFFF0000u);
-                }
+                for (int j = 0; j < 16; ++j)
+                  ti = (kb + 32 * mb + cidx(j, hf)) == cand ? ti : fmaxf(ti, sacc[mb][j]);
             }
-            mx = tm;
-            nx = cand;
+            ti = xhalf_max(ti);
+            if (far) {
+              if (nx >= 0) ti = fmaxf(ti, mx);               // the key kept out so far joins too
+              // nothing joins (a tile with one visible key): any finite reference will do
+              tref = ti == -INFINITY ? (mref == -INFINITY ? tm : mref) : ti;
+            }
           }
           excl_here = true;
         }
-        if (resc) {
-          const float f = __builtin_amdgcn_exp2f((mref - tm) * c2);   // first tile: 2^-inf = 0
+        if ((tref - mref) * c2 > RESCALE_TH) {
+          const float f = __builtin_amdgcn_exp2f((mref - tref) * c2);   // first tile: 2^-inf = 0
           lsum *= f;
 #pragma unroll
           for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
             for (int j = 0; j < 16; ++j) oacc[cb][j] *= f;
-          mref = tm;
+          mref = tref;
+        }
+        if (dominant) {
+          if (nx >= 0) {               // the key kept out so far joins the running sums
+            const float w = __builtin_amdgcn_exp2f((mx - mref) * c2);   // at most 2^RESCALE_TH
+            if (hf == 0) lsum += w;
+            const uint16_t* vr = vg + (int64_t)nx * pb.kv_st;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+              for (int jq = 0; jq < 4; ++jq) {
+                const uint2 u = *(const uint2*)(vr + 32 * cb + 8 * jq + 4 * hf);
+                oacc[cb][4 * jq + 0] += w * __uint_as_float(u.x << 16);
+                oacc[cb][4 * jq + 1] += w * __uint_as_float(u.x & 0xFFFF0000u);
+                oacc[cb][4 * jq + 2] += w * __uint_as_float(u.y << 16);
+                oacc[cb][4 * jq + 3] += w * __uint_as_float(u.y & 0xFFFF0000u);
+              }
+          }
+          mx = tm;
+          nx = cand;
         }
         mall = fmaxf(mall, tm);
       }

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(Prob pb, const T* __restri
   }
 
   const float c2 = pb.scale * LOG2E;
-  float m = -INFINITY, l = 0.f;
+  float m = -INFINITY, ref = -INFINITY, l = 0.f;
   int nstar = -1;
   float acc[NC];
 #pragma unroll
@@ -114,23 +114,39 @@ __global__ __launch_bounds__(256) void k_attn_partial(Prob pb, const T* __restri
       if (vis && (sv[j] > tmax)) { tmax = sv[j]; tidx = n; }
     }
     argmax16(tmax, tidx);
-    if (tmax > m) {                         // the row has a new champion in this tile
-      const float w = exp2f(m - tmax);      // m = -inf gives 0
-      const bool had = nstar >= 0;
-      l = l * w + (had ? w : 0.f);
+    // The sums are relative to `ref`, the largest logit that is part of them; the champion stays
+    // out of them and may be any distance above the rest.
+    const bool newc = tmax > m;             // the row has a new champion in this tile
+    const float mold = m;
+    const int nold = nstar;
+    if (newc) { m = tmax; nstar = tidx; }
+    const bool joins = newc && nold >= 0;   // the previous champion joins the sums
+    float tinc = -INFINITY;                 // largest logit joining the sums at this tile
 #pragma unroll
-      for (int j = 0; j < NC; ++j) {
-        const float vo = had ? to_float(vg[(int64_t)nstar * pb.kv_st + ln + 16 * j]) : 0.f;
-        acc[j] = acc[j] * w + w * vo;
-      }
-      m = tmax;
-      nstar = tidx;
+    for (int j = 0; j < 2; ++j)
+      if (k0 + ln + 16 * j != nstar) tinc = fmaxf(tinc, sv[j]);
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) tinc = fmaxf(tinc, __shfl_xor(tinc, o, 16));
+    if (joins) tinc = fmaxf(tinc, mold);
+    if (tinc > ref) {
+      const float w = exp2f(ref - tinc);    // ref = -inf (empty sums) gives 0
+      l *= w;
+#pragma unroll
+      for (int j = 0; j < NC; ++j) acc[j] *= w;
+      ref = tinc;
+    }
+    if (joins) {
+      const float w = exp2f(mold - ref);
+      l += w;
+#pragma unroll
+      for (int j = 0; j < NC; ++j)
+        acc[j] = fmaf(w, to_float(vg[(int64_t)nold * pb.kv_st + ln + 16 * j]), acc[j]);
     }
     float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int kk = ln + 16 * j, n = k0 + kk;
-      const float pj = (n == nstar || sv[j] == -INFINITY) ? 0.f : exp2f(sv[j] - m);
+      const float pj = (n == nstar || sv[j] == -INFINITY) ? 0.f : exp2f(sv[j] - ref);
       Ps[rl][kk] = pj;
       psum += pj;
     }
@@ -145,7 +161,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(Prob pb, const T* __restri
   }
   if (row_ok) {
     const int64_t o = ((int64_t)g * pb.R + r) * S + s;
-    if (ln == 0) { part_m[o] = m; part_mx[o] = m; part_n[o] = nstar; part_ref[o] = m; part_l[o] = l; }
+    if (ln == 0) { part_m[o] = m; part_mx[o] = m; part_n[o] = nstar; part_ref[o] = ref; part_l[o] = l; }
 #pragma unroll
     for (int j = 0; j < NC; ++j) part_z[o * D + ln + 16 * j] = acc[j];
   }

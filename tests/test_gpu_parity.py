@@ -109,6 +109,36 @@ def test_score_degenerate_inputs(rk, oracle_mod, kind):
         assert_score_close(got["score"][g], Ig, tol, f"{kind} head {g}")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("spikes", [((450, 60.0),), ((450, 150.0),), ((5, 400.0),), ((100, 150.0), (450, 400.0))])
+def test_score_key_far_above_the_rest(rk, oracle_mod, dtype, spikes):
+    """One key whose logit lies 60 ... 400 nats above every other key's, for every window query
+    (and a second one far above the first): the sums over "all the other keys" must not be kept
+    relative to that key, or they underflow in FP32 and its leave-one-out indicator (Eq. ori) is
+    lost.  The other keys' own scores lie below the smallest normal FP32 number from a gap of about
+    87 nats on; the score array is FP32, so there any value up to that number passes."""
+    w = workloads.small_case(Hq=4, Hkv=2, d=128, L=700, W=16, B=64, dtype=dtype, D=128, seed=23)
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    d = w.head_dim
+    e = torch.zeros(d)
+    e[3] = 1.0
+    q = (q.float() + 8.0 * e).to(q.dtype)                 # every query shares a component along e
+    k = k.float().clone()
+    for n, gap in spikes:                                   # logit of key n: scale * lam * (8 + noise)
+        k[:, n, :] = (gap * d ** 0.5 / 8.0) * e
+    k = k.to(q.dtype)
+    got = run_gpu_layer(rk, w, q, k, v, wo)
+    assert np.all(np.isfinite(got["score"])) and np.all(got["score"] >= 0)
+    ref = oracle_score(oracle_mod, w, q, k, v, wo, with_amax=True)
+    top = max(spikes, key=lambda t: t[1])[0]
+    for g, (Ig, tol, amax) in ref.items():
+        assert amax[:, top].min() > 0.999999 and Ig[:, top].min() > 0
+        assert_score_close(got["score"][g], Ig, tol + 1.2e-38, f"spikes {spikes} head {g}")
+        # the spike's own score is an ordinary number and is held to the relative bar alone
+        assert np.all(np.abs(got["score"][g][:, top] - Ig[:, top]) <= RTOL * Ig[:, top])
+
+
 def test_gram_matches_float64_product(rk):
     w = _case("bf16_mha")
     wo = workloads.make_wo(w)
