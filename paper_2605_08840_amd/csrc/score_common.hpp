@@ -59,11 +59,15 @@ __global__ __launch_bounds__(256) void k_stats_fill(int rows, const float* __res
 }
 
 // Merge of the key splits and the per-row quantities of the score pass.
-// grid (ceil(W / CMB_RQ), Hq), CMB_RQ * D threads: thread = (row r of the group, column c).
-// The head's Gram matrix is staged in LDS once per workgroup; the per-split scalars of a row are
-// fetched by one thread each and shared through LDS.
+// grid (ceil(W / CMB_RQ), Hq), CMB_RQ * D threads.  For the merge a thread is (row r of the
+// group, column c); the per-split scalars of a row are fetched by one thread each and shared
+// through LDS.  For u = z M_h (and y = x M_h) a thread is (part p = r of the Gram matrix's rows,
+// column c): it holds its D / CMB_RQ Gram entries in registers (loaded first, their latency
+// hides behind the merge; every entry is needed by exactly one thread, so the matrix never
+// touches LDS) and works on all CMB_RQ rows at once, whose z and x it reads as LDS broadcasts;
+// the partial sums of the parts meet in LDS.
 template <typename T, int D>
-__global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* __restrict__ v, int S,
+__global__ __launch_bounds__(CMB_RQ * D, 4) void k_attn_combine(Prob pb, const T* __restrict__ v, int S,
                                                              const float* __restrict__ gram,
                                                              const float* __restrict__ part_m,
                                                              const float* __restrict__ part_mx,
@@ -78,8 +82,10 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
                                                              const T* __restrict__ q, uint16_t* __restrict__ op,
                                                              int log2gp, int nwb, int ngrp) {
   constexpr int NWV = D / 64, SMAX = 64;     // wavefronts per row; capacity of the split dimension
-  __shared__ __attribute__((aligned(16))) float Mh_s[D * D];   // the head's Gram matrix (unused when gram == NULL)
-  __shared__ float zq[CMB_RQ][D], xq[CMB_RQ][D];
+  constexpr int AP = D / CMB_RQ;             // Gram rows per thread
+  static_assert(CMB_RQ == 4, "z and x of the group's rows travel as one float4 each");
+  __shared__ __attribute__((aligned(16))) float zx[D][2 * CMB_RQ];     // [a][z of the rows | x of the rows]
+  __shared__ float up[CMB_RQ][2][CMB_RQ][D];                           // [part][u | y][row][c]
   __shared__ float red[CMB_RQ][NWV][2];
   __shared__ float s_m[CMB_RQ][2], s_mx[CMB_RQ][SMAX], s_l[CMB_RQ][SMAX];
   __shared__ int s_n[CMB_RQ][SMAX + 1];      // [SMAX]: the split that holds the champion, or -1
@@ -87,16 +93,13 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
   const int h = blockIdx.y, g = h / pb.G;
   const int r = threadIdx.x / D, c = threadIdx.x % D;
   const T* vg = v + (int64_t)g * pb.kv_sh;
-  // The Gram matrix travels through registers while the splits are merged (written to LDS just
-  // before the matrix-vector product): its latency hides behind the merge.
-  constexpr int GQ = D * D / 4 / (CMB_RQ * D);     // float4 per thread
-  float4 gq[GQ];
+  float mreg[AP];
   if (gram) {
-    const float4* Mh4 = (const float4*)(gram + (int64_t)h * D * D);
+    const float* Mh = gram + (int64_t)h * D * D + (int64_t)(r * AP) * D + c;
 #pragma unroll
-    for (int k = 0; k < GQ; ++k) gq[k] = Mh4[threadIdx.x + k * (CMB_RQ * D)];
+    for (int j = 0; j < AP; ++j) mreg[j] = Mh[j * D];
   }
-  // A workgroup walks ngrp groups of CMB_RQ rows with the one staged Gram matrix.
+  // A workgroup walks ngrp groups of CMB_RQ rows with the one set of Gram registers.
   for (int grp = 0; grp < ngrp; ++grp) {
   const int i = (blockIdx.x * ngrp + grp) * CMB_RQ + r;
   if ((blockIdx.x * ngrp + grp) * CMB_RQ >= pb.W) break;      // workgroup-uniform
@@ -113,6 +116,8 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
     pref = part_ref[o + c];
     pl = part_l[o + c];
   }
+  T qv = T();                    // needed at the very end: its latency hides behind everything else
+  if (op) qv = q[(int64_t)h * pb.q_sh + (int64_t)(live ? i : 0) * pb.q_st + c];
   if (c < 64) {
     float M0 = pm;
 #pragma unroll
@@ -177,26 +182,32 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
     z = zr / lrest;
     x = 0.f;
   }
-  zq[r][c] = z;
-  xq[r][c] = x;
-  if (gram && grp == 0) {
-#pragma unroll
-    for (int k = 0; k < GQ; ++k) ((float4*)Mh_s)[threadIdx.x + k * (CMB_RQ * D)] = gq[k];
-  }
-  __syncthreads();
   float u = z, y = x;
   if (pb.ind != 0) {
     // attention-weight and value-norm indicators: no output term (u = 0, zz = 0), no key is
     // evaluated by the leave-one-out form; the score pass then sees sqrt(vv) with vv = 1 or ||v||^2
     u = 0.f; y = 0.f;
   } else if (gram) {
-    u = 0.f; y = 0.f;
-#pragma unroll 8
-    for (int a = 0; a < D; ++a) {
-      const float mv = Mh_s[a * D + c];
-      u = fmaf(zq[r][a], mv, u);
-      y = fmaf(xq[r][a], mv, y);
+    zx[c][r] = z;
+    zx[c][CMB_RQ + r] = x;
+    __syncthreads();
+    float ua[CMB_RQ], ya[CMB_RQ];
+#pragma unroll
+    for (int k = 0; k < CMB_RQ; ++k) { ua[k] = 0.f; ya[k] = 0.f; }
+#pragma unroll
+    for (int j = 0; j < AP; ++j) {
+      const float4 z4 = *(const float4*)&zx[r * AP + j][0];
+      const float4 x4 = *(const float4*)&zx[r * AP + j][CMB_RQ];
+      ua[0] = fmaf(z4.x, mreg[j], ua[0]); ua[1] = fmaf(z4.y, mreg[j], ua[1]);
+      ua[2] = fmaf(z4.z, mreg[j], ua[2]); ua[3] = fmaf(z4.w, mreg[j], ua[3]);
+      ya[0] = fmaf(x4.x, mreg[j], ya[0]); ya[1] = fmaf(x4.y, mreg[j], ya[1]);
+      ya[2] = fmaf(x4.z, mreg[j], ya[2]); ya[3] = fmaf(x4.w, mreg[j], ya[3]);
     }
+#pragma unroll
+    for (int k = 0; k < CMB_RQ; ++k) { up[r][0][k][c] = ua[k]; up[r][1][k][c] = ya[k]; }
+    __syncthreads();
+    u = (up[0][0][r][c] + up[1][0][r][c]) + (up[2][0][r][c] + up[3][0][r][c]);
+    y = (up[0][1][r][c] + up[1][1][r][c]) + (up[2][1][r][c] + up[3][1][r][c]);
   }
   // zz = u.z and |x|_M^2 = y.x of the row: wavefront sums, then across the row's wavefronts
   float s0 = u * z, s1 = y * x;
@@ -224,7 +235,6 @@ __global__ __launch_bounds__(CMB_RQ * D) void k_attn_combine(Prob pb, const T* _
     hi &= 0xFFFF0000u;
     const uint32_t lb = __float_as_uint(u - __uint_as_float(hi));
     const uint32_t lo = (lb + 0x7FFFu + ((lb >> 16) & 1u)) >> 16;
-    const T qv = q[(int64_t)h * pb.q_sh + (int64_t)i * pb.q_st + c];
     uint16_t qb;
     __builtin_memcpy(&qb, &qv, 2);
     op[inner] = qb;
