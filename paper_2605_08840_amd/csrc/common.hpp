@@ -137,11 +137,30 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
   return r[0] + r[1];
 }
 
-// bits = 2 bits + (x > t): one compare whose outcome an add-with-carry shifts into a bit string
-// (t wave-uniform).  Sixteen calls leave element k of a lane at bit 15 - k.
-__device__ __forceinline__ void shift_in_gt(uint32_t& bits, float x, float t) {
-  asm("v_cmp_lt_f32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(bits) : "v"(x), "s"(t) : "vcc");
+// Bit strings of comparison outcomes: for each of two elements x0, x1 (in this order) and each of
+// two wave-uniform thresholds, bits = 2 bits + (x > t): one compare, whose outcome an
+// add-with-carry shifts in.  Sixteen elements leave element k of a lane at bit 15 - k.
+// gfx950 wants two other instructions between a vector instruction that writes a scalar register
+// (a compare's outcome) and a vector instruction that reads it: the four compares go first, each
+// into its own scalar pair, then the four adds.
+__device__ __forceinline__ void shift_in_gt_2x2(uint32_t& hb, uint32_t& lb, float x0, float x1, float thi,
+                                                float tlo) {
+  unsigned long long c0, c1, c2;
+  asm("v_cmp_lt_f32_e64 %2, %7, %5\n\t"
+      "v_cmp_lt_f32_e64 %3, %8, %5\n\t"
+      "v_cmp_lt_f32_e64 %4, %7, %6\n\t"
+      "v_cmp_lt_f32_e32 vcc, %8, %6\n\t"
+      "v_addc_co_u32_e64 %0, %2, %0, %0, %2\n\t"
+      "v_addc_co_u32_e64 %1, %3, %1, %1, %3\n\t"
+      "v_addc_co_u32_e64 %0, %4, %0, %0, %4\n\t"
+      "v_addc_co_u32_e32 %1, vcc, %1, %1, vcc"
+      : "+v"(hb), "+v"(lb), "=&s"(c0), "=&s"(c1), "=&s"(c2)
+      : "v"(x0), "v"(x1), "s"(thi), "s"(tlo)
+      : "vcc");
 }
+// The same distance between the vector instruction that made the thresholds wave-uniform
+// (a readfirstlane) and the first compare that reads them.
+__device__ __forceinline__ void settle_scalars(float& a, float& b) { asm volatile("s_nop 1" : "+s"(a), "+s"(b)); }
 
 // Budget of KV head g: its own entry of the optional per-head array, held inside (W, B], else B.
 __device__ __forceinline__ int head_budget(const Prob& pb, int g) {

@@ -110,14 +110,12 @@ __global__ __launch_bounds__(SEL_NT) void k_sel_scan(Prob pb, const float* __res
 #pragma unroll
     for (int e = 0; e < 4; ++e) x[e] = n0 + e < pb.P ? row[n0 + e] : -INFINITY;
   }
-  const float tlo = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.x)));
-  const float thi = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.y)));
+  float tlo = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.x)));
+  float thi = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.y)));
+  settle_scalars(tlo, thi);
   uint32_t hb = 0, lb = 0;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {                 // element e ends up at bit 3 - e
-    shift_in_gt(hb, x[e], thi);
-    shift_in_gt(lb, x[e], tlo);
-  }
+  for (int e = 0; e < 4; e += 2) shift_in_gt_2x2(hb, lb, x[e], x[e + 1], thi, tlo);   // element e ends up at bit 3 - e
   w.cmask[((int64_t)g * nchunks + ch) * 1024 + tid] = (uint8_t)(lb & ~hb);
   const uint32_t c = wave_sum((uint32_t)__popc(hb));
   if (lane == 0) red[wv] = c;

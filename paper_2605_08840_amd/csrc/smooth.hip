@@ -163,14 +163,12 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
     for (int k = 0; k < EW_NE; ++k) e[k] = fmaf(w, x[k], e[k]);
     if (!scan || !live) return;
     const float2 th = thr[g * pb.W + i];         // the threshold lies in (th.x, th.y]
-    const float tlo = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.x)));
-    const float thi = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.y)));
+    float tlo = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.x)));
+    float thi = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.y)));
+    settle_scalars(tlo, thi);
     uint32_t hb = 0, lb = 0;
 #pragma unroll
-    for (int k = 0; k < EW_NE; ++k) {
-      shift_in_gt(hb, x[k], thi);
-      shift_in_gt(lb, x[k], tlo);
-    }
+    for (int k = 0; k < EW_NE; k += 2) shift_in_gt_2x2(hb, lb, x[k], x[k + 1], thi, tlo);
     // entries above the bracket: element k = 4 j + q of this lane sits at bit 15 - k and at
     // position wbase + 256 j + 4 l + q, so with c = popcount
     //   sum of j = 3 c - [bits 4..7, 12..15] - 2 [bits 8..15],  sum of q = 3 c - [odd bits] - 2 [bits 2,3 mod 4]
