@@ -52,6 +52,7 @@ __device__ __forceinline__ uint32_t rank_in_ballot(unsigned long long ballot) {
 // Threshold of the k-th largest (1 <= k <= n): on return `tau` is its key, `n_gt`
 // the number of keys above it and `k_eq` how many keys equal to tau belong to the
 // top k (>= 1).  All threads of the block must call; all receive the result.
+// Any block of 64 .. SEL_NT threads whose size divides SEL_BINS.
 __device__ inline void block_kth_key(const float* __restrict__ row, int n, int k, SelectSmem& sm,
                                      uint32_t& tau, uint32_t& n_gt, uint32_t& k_eq) {
   uint32_t prefix = 0, mask = 0, krem = (uint32_t)k, above = 0;
@@ -61,22 +62,26 @@ __device__ inline void block_kth_key(const float* __restrict__ row, int n, int k
   for (int pass = 0; pass < 3; ++pass) {
     const int sh = shifts[pass];
     const uint32_t nb = 1u << nbits[pass];
-    for (int b = threadIdx.x; b < SEL_BINS; b += SEL_NT) sm.hist[b] = 0;
+    const int nt = (int)blockDim.x, bpt = SEL_BINS / nt;
+    for (int b = threadIdx.x; b < SEL_BINS; b += nt) sm.hist[b] = 0;
     __syncthreads();
-    for (int x = threadIdx.x; x < n; x += SEL_NT) {
+    for (int x = threadIdx.x; x < n; x += nt) {
       const uint32_t key = float_key(row[x]);
       if ((key & mask) == prefix) atomicAdd(&sm.hist[(key >> sh) & (nb - 1)], 1u);
     }
     __syncthreads();
-    // bins in descending order: thread t owns the reversed bins 2t, 2t+1
-    const int r0 = 2 * threadIdx.x, r1 = r0 + 1;
-    const uint32_t h0 = r0 < (int)nb ? sm.hist[nb - 1 - r0] : 0;
-    const uint32_t h1 = r1 < (int)nb ? sm.hist[nb - 1 - r1] : 0;
-    const uint32_t incl = block_incl_scan(h0 + h1, sm.wsum);
-    const uint32_t before = incl - (h0 + h1);
+    // bins in descending order: thread t owns the reversed bins bpt t .. bpt t + bpt - 1
+    const int r0 = bpt * (int)threadIdx.x;
+    uint32_t own = 0;
+    for (int j = 0; j < bpt; ++j) own += r0 + j < (int)nb ? sm.hist[nb - 1 - (r0 + j)] : 0u;
+    const uint32_t incl = block_incl_scan(own, sm.wsum);
+    uint32_t before = incl - own;
     if (before < krem && krem <= incl) {        // exactly one thread
-      if (krem <= before + h0) { sm.bin = nb - 1 - r0; sm.below = before; }
-      else                     { sm.bin = nb - 1 - r1; sm.below = before + h0; }
+      for (int j = 0; j < bpt; ++j) {
+        const uint32_t hj = r0 + j < (int)nb ? sm.hist[nb - 1 - (r0 + j)] : 0u;
+        if (krem <= before + hj) { sm.bin = nb - 1 - (r0 + j); sm.below = before; break; }
+        before += hj;
+      }
     }
     __syncthreads();
     prefix |= sm.bin << sh;
@@ -205,12 +210,14 @@ __device__ inline uint32_t block_kth(const uint32_t (&k)[NPT], uint32_t kk, Coun
 // ka-th and kb-th largest keys of the block (0 if fewer keys than that), bit by bit (with many
 // keys per thread the counting, not the barrier, is what a step costs).
 // With low_bit > 0 only the bits from it up are resolved (ta, tb are then lower bounds with the
-// unresolved bits zero).
+// unresolved bits zero).  Bits above `top_bit` are known (`prefix`: the leading bits that every
+// key shares).
 template <int NPT>
 __device__ inline void block_kth2(const uint32_t (&k)[NPT], uint32_t ka, uint32_t kb, CountSmem& cs,
-                                  int& it, uint32_t& ta, uint32_t& tb, int low_bit = 0) {
-  uint32_t a = 0, b = 0;
-  for (int bit = 31; bit >= low_bit; --bit) {
+                                  int& it, uint32_t& ta, uint32_t& tb, int low_bit = 0, int top_bit = 31,
+                                  uint32_t prefix = 0u) {
+  uint32_t a = prefix, b = prefix;
+  for (int bit = top_bit; bit >= low_bit; --bit) {
     const uint32_t pa = a | (1u << bit), pb = b | (1u << bit);
     uint32_t ca, cb;
     block_count_ge2<NPT>(k, pa, pb, cs, it, ca, cb);
@@ -226,6 +233,30 @@ __device__ __forceinline__ void common_prefix(uint32_t klo, uint32_t khi, int& t
   const uint32_t x = klo ^ khi;
   top_bit = x ? 31 - __builtin_clz(x) : -1;
   prefix = top_bit >= 31 ? 0u : (khi & ~((2u << max(top_bit, 0)) - 1u)) | (top_bit < 0 ? khi : 0u);
+}
+
+// Smallest and largest key of the block, empty slots (key 0) aside; kmin = 0xFFFFFFFF and kmax = 0
+// if there is no key.  One barrier, same buffers and turn-taking as the counting step.
+template <int NPT>
+__device__ inline void block_key_range(const uint32_t (&k)[NPT], CountSmem& cs, int& it, uint32_t& kmin,
+                                       uint32_t& kmax) {
+  uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    hi = max(hi, k[j]);
+    lo = k[j] ? min(lo, k[j]) : lo;
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    hi = max(hi, (uint32_t)__shfl_xor((int)hi, o, 64));
+    lo = min(lo, (uint32_t)__shfl_xor((int)lo, o, 64));
+  }
+  const int w = threadIdx.x >> 6, nw = (int)(blockDim.x >> 6), p = it & 1;
+  if ((threadIdx.x & 63) == 0) { cs.red[p][0][w] = hi; cs.red[p][1][w] = lo; }
+  __syncthreads();
+  kmin = 0xFFFFFFFFu; kmax = 0u;
+  for (int j = 0; j < nw; ++j) { kmax = max(kmax, cs.red[p][0][j]); kmin = min(kmin, cs.red[p][1][j]); }
+  ++it;
 }
 
 // Sample ranks that bracket the k-th largest of a population of n from a sample of ns
@@ -273,9 +304,15 @@ __device__ inline void block_bracket(const float* __restrict__ row, int n, int k
   int r_hi, r_lo;
   bracket_ranks(n, ns, k, r_hi, r_lo);
   // a bracket only has to hold the threshold: 16 resolved bits (sign, exponent, 7 mantissa
-  // bits) are plenty; the upper end is rounded up, the lower end down
+  // bits) are plenty; the upper end is rounded up, the lower end down.  The leading bits that
+  // the smallest and the largest sample share need no search.
+  uint32_t kmin, kmax, prefix;
+  int top_bit;
+  block_key_range<NPT>(keys, cs, it, kmin, kmax);
+  common_prefix(kmin, kmax, top_bit, prefix);
   uint32_t thi, tlo;
-  block_kth2<NPT>(keys, (uint32_t)max(r_hi, 1), (uint32_t)min(r_lo, ns), cs, it, thi, tlo, 16);
+  block_kth2<NPT>(keys, (uint32_t)max(r_hi, 1), (uint32_t)min(r_lo, ns), cs, it, thi, tlo, 16, top_bit,
+                  prefix & 0xFFFF0000u);
   khi = r_hi >= 1 ? (thi | 0xFFFFu) : 0xFFFFFFFFu;
   klo = r_lo <= ns ? tlo : 0u;
 }
@@ -363,8 +400,8 @@ __device__ __forceinline__ void for_each_mask_word(const uint32_t* __restrict__ 
 template <typename F>
 __device__ inline void block_visit_topk(const float* __restrict__ row, int n, uint32_t tau,
                                         uint32_t k_eq, SelectSmem& sm, F f) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  int seg = (n + SEL_NW - 1) / SEL_NW;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (int)(blockDim.x >> 6);
+  int seg = (n + nw - 1) / nw;
   seg = (seg + 63) / 64 * 64;
   const int beg = min(n, w * seg), end = min(n, beg + seg);
   uint32_t cgt = 0, ceq = 0;

@@ -14,12 +14,13 @@ namespace restkv {
 namespace {
 
 constexpr int CAND_CAP = 4096;      // candidates kept per (head, query) row
-constexpr int SMP_NS = 8192;        // samples per row for the bracket
+constexpr int SMP_NS = 8192;        // samples per row that the fused score pass may leave for the bracket
+constexpr int ROW_NS = 4096;        // samples per row that the bracket kernel fetches itself
 
 // Bracket of the top-min(B,P) threshold of one (head, query) row from a sample of the row.
 // thr[row] = {lo, hi}: the threshold lies in (lo, hi] unless the sample misled us (then the
 // finishing kernel falls back to the exact radix search).  Also clears the row's counters.
-// grid (W, Hkv), 256 threads, SMP_NS / 256 samples per thread in registers.
+// grid (W, Hkv), 256 threads, ROW_NS / 256 samples per thread in registers.
 __global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __restrict__ score,
                                                         float2* __restrict__ thr,
                                                         uint32_t* __restrict__ cnt_hi,
@@ -35,7 +36,7 @@ __global__ __launch_bounds__(256) void k_sample_bracket(Prob pb, const float* __
   }
   int it = 0;
   uint32_t klo, khi;
-  block_bracket<SMP_NS / 256, 16>(row, pb.P, k, cs, it, klo, khi);
+  block_bracket<ROW_NS / 256, 16>(row, pb.P, k, cs, it, klo, khi);
   if (threadIdx.x == 0)
     thr[r] = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
 }
@@ -226,7 +227,22 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
   }
 }
 
-constexpr unsigned long long ROW_PENDING = ~0ull;   // rowsum marker: the bracket missed this row
+// Exact search (radix select + ordered visit) of a row whose bracket missed or overflowed: the
+// sum of the positions of its top k, for thread 0.  Every thread of the block calls.
+__device__ inline unsigned long long row_exact_sum(const float* __restrict__ row, int n, int k, SelectSmem& sm) {
+  uint32_t tau, n_gt, k_eq;
+  block_kth_key(row, n, k, sm, tau, n_gt, k_eq);
+  unsigned long long acc = 0;
+  block_visit_topk(row, n, tau, k_eq, sm, [&](int x, uint32_t) { acc += (unsigned long long)x; });
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sm.isum[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  unsigned long long tot = 0;
+  for (int j = 0; j < (int)(blockDim.x >> 6); ++j) tot += sm.isum[j];
+  return tot;
+}
 
 // Exact threshold among the candidates of one row (keys ck, positions ci, NPT per thread, 256
 // threads; empty slots have key 0): `need` of them belong to the top-B, ties cut by position.
@@ -267,7 +283,7 @@ __device__ inline unsigned long long finish_candidates(const uint32_t (&ck)[NPT]
 // their values fetched from the raw score.  The threshold is found among them by bisection on
 // their keys; equal values are taken in position order (a second bisection on the position,
 // only when a tie straddles the cut).  A row whose bracket missed, or that has more than
-// CAND_CAP candidates, is marked pending and searched exactly by k_row_fallback.
+// CAND_CAP candidates, is searched exactly (radix select over the whole row) on the spot.
 // grid (W, Hkv), 256 threads.
 __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const float* __restrict__ score,
                                                     const uint32_t* __restrict__ cnt_hi,
@@ -280,6 +296,7 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const float* __rest
   __shared__ unsigned long long isum[4];
   __shared__ uint32_t wsum[SEL_NW];
   __shared__ int cpos[CAND_CAP];                 // positions of the row's candidates
+  __shared__ SelectSmem sm;                      // (exact search only)
   const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
   const int k = min(head_budget(pb, g), pb.P);
   if (k >= pb.P) {
@@ -301,7 +318,8 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const float* __rest
   const uint32_t nc = wsum[0];
   const bool ok = ch < (uint32_t)k && (uint32_t)k <= ch + nc && nc <= (uint32_t)CAND_CAP;
   if (!ok) {                                         // block-uniform
-    if (threadIdx.x == 0) rowsum[r] = ROW_PENDING;
+    const unsigned long long tot = row_exact_sum(score + (int64_t)r * pb.ld, pb.P, k, sm);
+    if (threadIdx.x == 0) rowsum[r] = tot;
     return;
   }
   uint32_t slot = incl - c;
@@ -340,6 +358,7 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const float* __rest
   };
   unsigned long long acc = nc <= 1024u  ? run(std::integral_constant<int, 4>{})
                            : nc <= 2048u ? run(std::integral_constant<int, 8>{})
+                           : nc <= 3072u ? run(std::integral_constant<int, 12>{})
                                          : run(std::integral_constant<int, NPT>{});
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 64);
@@ -351,7 +370,8 @@ __global__ __launch_bounds__(256) void k_row_finish(Prob pb, const float* __rest
 // The finishing step when the candidates of a row sit in per-chunk slices
 // (sval / sidx [row, nchunks, caps], fill counts scnt [row, nchunks]; nchunks <= 256).
 // grid (W, Hkv), 256 threads.
-__global__ __launch_bounds__(256) void k_row_finish_slices(Prob pb, const uint32_t* __restrict__ cnt_hi,
+__global__ __launch_bounds__(256) void k_row_finish_slices(Prob pb, const float* __restrict__ score,
+                                                           const uint32_t* __restrict__ cnt_hi,
                                                            const unsigned long long* __restrict__ sum_hi,
                                                            const uint32_t* __restrict__ scnt,
                                                            const float* __restrict__ sval,
@@ -363,6 +383,7 @@ __global__ __launch_bounds__(256) void k_row_finish_slices(Prob pb, const uint32
   __shared__ unsigned long long isum[4];
   __shared__ uint32_t pre[257];              // exclusive prefix of the slice fill counts
   __shared__ uint32_t over;
+  __shared__ SelectSmem sm;                  // (exact search only)
   const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
   const int k = min(head_budget(pb, g), pb.P);
   if (k >= pb.P) {
@@ -384,7 +405,8 @@ __global__ __launch_bounds__(256) void k_row_finish_slices(Prob pb, const uint32
   const uint32_t ch = cnt_hi[r], nc = pre[nchunks];
   const bool ok = !over && ch < (uint32_t)k && (uint32_t)k <= ch + nc && nc <= (uint32_t)CAND_CAP;
   if (!ok) {
-    if (threadIdx.x == 0) rowsum[r] = ROW_PENDING;
+    const unsigned long long tot = row_exact_sum(score + (int64_t)r * pb.ld, pb.P, k, sm);
+    if (threadIdx.x == 0) rowsum[r] = tot;
     return;
   }
   const uint32_t need = (uint32_t)k - ch;
@@ -417,31 +439,6 @@ __global__ __launch_bounds__(256) void k_row_finish_slices(Prob pb, const uint32
   if ((threadIdx.x & 63) == 0) isum[threadIdx.x >> 6] = acc;
   __syncthreads();
   if (threadIdx.x == 0) rowsum[r] = isum[0] + isum[1] + isum[2] + isum[3] + sum_hi[r];
-}
-
-// Exact search (radix select + ordered visit) of the rows k_row_finish marked pending.
-// grid (W, Hkv), SEL_NT threads; a workgroup whose row is done exits at once.
-__global__ __launch_bounds__(SEL_NT) void k_row_fallback(Prob pb, const float* __restrict__ score,
-                                                         unsigned long long* __restrict__ rowsum) {
-  __shared__ SelectSmem sm;
-  const int i = blockIdx.x, g = blockIdx.y, r = g * pb.W + i;
-  if (rowsum[r] != ROW_PENDING) return;
-  const float* row = score + (int64_t)r * pb.ld;
-  const int k = min(head_budget(pb, g), pb.P);
-  uint32_t tau, n_gt, k_eq;
-  block_kth_key(row, pb.P, k, sm, tau, n_gt, k_eq);
-  unsigned long long acc = 0;
-  block_visit_topk(row, pb.P, tau, k_eq, sm, [&](int x, uint32_t) { acc += (unsigned long long)x; });
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 64);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) sm.isum[threadIdx.x >> 6] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned long long tot = 0;
-    for (int j = 0; j < SEL_NW; ++j) tot += sm.isum[j];
-    rowsum[r] = tot;
-  }
 }
 
 // Window size and shift from the drift statistic (device function so that every block of
@@ -534,7 +531,6 @@ int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, in
   if (pb.adaptive) {
     RK_LAUNCH(ST_ROWTOPK, st, k_row_finish, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, score, cnt_hi, sum_hi,
               cmask, thr, rowsum);
-    RK_LAUNCH(ST_ROWTOPK, st, k_row_fallback, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
   }
   RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, e, rowsum, fin,
             aws_info, aws_d);
@@ -553,9 +549,8 @@ int launch_smooth_fused_tail(const Prob& pb, const float* score, const float* em
                              int32_t* aws_info, double* aws_d, char* ws, const SmoothWs& lay,
                              const FusedPtrs& fp, int nchunks, hipStream_t st) {
   unsigned long long* rowsum = (unsigned long long*)(ws + lay.rowsum);
-  RK_LAUNCH(ST_ROWTOPK, st, k_row_finish_slices, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, fp.cnt_hi,
+  RK_LAUNCH(ST_ROWTOPK, st, k_row_finish_slices, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, score, fp.cnt_hi,
             fp.sum_hi, fp.scnt, fp.sval, fp.sidx, nchunks, fp.caps, fp.thr, rowsum);
-  RK_LAUNCH(ST_ROWTOPK, st, k_row_fallback, dim3(pb.W, pb.Hkv), dim3(SEL_NT), 0, st, pb, score, rowsum);
   RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, ema, rowsum, fin,
             aws_info, aws_d);
   return hip_status();
