@@ -99,7 +99,7 @@ __device__ __forceinline__ float key_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
 }
 
-constexpr int SEL_NS = 4096;     // samples / candidate capacity of the bracketed search
+constexpr int SEL_NS = 4096;     // samples of the bracketed search
 
 // Block-wide counting on keys held in registers (NPT per thread; empty slots hold key 0, which
 // no pivot >= 1 counts).  One barrier per call; `it` alternates the two reduction buffers.
@@ -315,63 +315,6 @@ __device__ inline void block_bracket(const float* __restrict__ row, int n, int k
                   prefix & 0xFFFF0000u);
   khi = r_hi >= 1 ? (thi | 0xFFFFu) : 0xFFFFFFFFu;
   klo = r_lo <= ns ? tlo : 0u;
-}
-
-// Same contract as block_kth_key, but the threshold is first bracketed from a sample; one pass
-// over the row then counts the elements above the bracket and collects the few inside it in
-// LDS, among which the threshold is found by bisection.  Falls back to the radix search when
-// the bracket misses (heavy ties, adversarial order).  `buf` holds SEL_NS uint32; the block has
-// SEL_NT threads.
-__device__ inline void block_kth_key_fast(const float* __restrict__ row, int n, int k, SelectSmem& sm,
-                                          CountSmem& cs, uint32_t* buf, uint32_t& tau, uint32_t& n_gt,
-                                          uint32_t& k_eq) {
-  constexpr int NPT = SEL_NS / SEL_NT;
-  int it = 0;
-  uint32_t klo, khi;
-  block_bracket<NPT, 1>(row, n, k, cs, it, klo, khi);   // smoothed rows: single, spread samples
-  if (threadIdx.x == 0) { sm.take = 0; sm.below = 0; }
-  __syncthreads();
-  uint32_t cnt = 0;
-  for (int x0 = threadIdx.x; x0 < n; x0 += 8 * blockDim.x) {
-    uint32_t kk[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {            // eight loads in flight
-      const int x = x0 + u * blockDim.x;
-      kk[u] = x < n ? float_key(row[x]) : 0u;
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (kk[u] > khi) {
-        ++cnt;
-      } else if (kk[u] > klo) {
-        const uint32_t slot = atomicAdd(&sm.take, 1u);
-        if (slot < (uint32_t)SEL_NS) buf[slot] = kk[u];
-      }
-    }
-  }
-  if (cnt) atomicAdd(&sm.below, cnt);
-  __syncthreads();
-  const uint32_t nc = sm.take, above = sm.below;
-  const bool ok = above < (uint32_t)k && (uint32_t)k <= above + nc && nc <= (uint32_t)SEL_NS;
-  if (!ok) {                                  // block-uniform
-    __syncthreads();
-    block_kth_key(row, n, k, sm, tau, n_gt, k_eq);
-    return;
-  }
-  uint32_t ck[NPT];
-#pragma unroll
-  for (int j = 0; j < NPT; ++j) {
-    const uint32_t x = threadIdx.x + j * blockDim.x;
-    ck[j] = x < nc ? buf[x] : 0u;
-  }
-  const uint32_t need = (uint32_t)k - above;
-  const uint32_t t = block_kth<NPT>(ck, need, cs, it);
-  uint32_t cge, cgt;
-  block_count_ge2<NPT>(ck, t, t + 1u, cs, it, cge, cgt);     // t < 0xFFFFFFFF for any real float
-  tau = t;
-  n_gt = above + cgt;
-  k_eq = need - cgt;
-  __syncthreads();
 }
 
 // Calls f(word index, word) for every 32-bit word of a row of ndw mask words (ndw a multiple of

@@ -3,11 +3,11 @@
 //
 // The row of final scores of a head is cut into chunks that many workgroups scan in parallel:
 //   bracket : a sample of the row brackets the threshold of the top-(B-W)
-//   scan    : per chunk, count the entries above the bracket, collect those inside it
-//   finish  : exact threshold among the candidates (bisection on keys; ties by position)
-//   fallback: a head whose bracket missed is searched with the exact radix select
-//   count   : per chunk, number of selected entries
-//   emit    : per chunk, ordered write at the offset given by the counts of the earlier chunks
+//   scan    : per chunk, count the entries above the bracket; those inside it leave as bit masks
+//   finish  : per head, exact threshold among the candidates (bisection on keys; ties by
+//             position), or the exact radix search of the whole row if the bracket missed;
+//             number of selected entries before every chunk
+//   emit    : per chunk, ordered write at that offset
 #include <mutex>
 
 #include "rowselect.hpp"
