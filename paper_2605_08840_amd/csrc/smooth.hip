@@ -460,7 +460,10 @@ __device__ inline void aws_window(const Prob& pb, unsigned long long sf, unsigne
 }
 
 // final[g,n] = (1/W_s) sum_{j=gamma-half}^{gamma+half} ema[g,n+j], zero outside [0,P).
-// grid (ceil(P/256), Hkv), 256 threads.
+// grid (ceil(P / (256 BOX_PT)), Hkv), 256 threads; a thread owns BOX_PT positions 256 apart (the
+// loads of a window offset are independent and coalesced); every workgroup derives the head's
+// window from the index sums itself.
+constexpr int BOX_PT = 4;
 __global__ __launch_bounds__(256) void k_box(Prob pb, const float* __restrict__ ema,
                                              const unsigned long long* __restrict__ rowsum,
                                              float* __restrict__ fin, int32_t* __restrict__ aws_info,
@@ -468,6 +471,7 @@ __global__ __launch_bounds__(256) void k_box(Prob pb, const float* __restrict__ 
   const int g = blockIdx.y;
   __shared__ int sh_ws, sh_gamma;
   __shared__ unsigned long long sh_sum[2][4];
+  __shared__ float tile[2 * 256 * BOX_PT];           // span + reach of the window (when it fits)
   // the W index sums of the head: all loads in flight at once, wavefront sums, then thread 0
   {
     unsigned long long sf = 0, sr = 0;
@@ -494,19 +498,78 @@ __global__ __launch_bounds__(256) void k_box(Prob pb, const float* __restrict__ 
   }
   __syncthreads();
   const int w_s = sh_ws, gamma = sh_gamma;
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  if (n >= pb.P) return;
+  const int n0 = blockIdx.x * (256 * BOX_PT) + threadIdx.x;
   const float* e = ema + (int64_t)g * pb.ld;
   const int half = w_s / 2;
-  const int lo = max(0, n + gamma - half), hi = min(pb.P - 1, n + gamma + half);
-  float s = 0.f;
-  if (pb.pmax) {                                   // max pooling (ablation study): positions inside the prefix only
-    for (int m = lo; m <= hi; ++m) s = m == lo ? e[m] : fmaxf(s, e[m]);
-    fin[(int64_t)g * pb.ld + n] = s;
-    return;
+  float s[BOX_PT];
+#pragma unroll
+  for (int j = 0; j < BOX_PT; ++j) s[j] = 0.f;
+  // Window offsets in ascending order: a position's terms are added lowest index first; a term
+  // outside the prefix is zero padding (it adds nothing; max pooling skips it, and a window with
+  // no term inside the prefix gives 0).
+  const int last = gamma + half;
+  constexpr int SPAN = 256 * BOX_PT;
+  if (w_s - 1 <= SPAN) {
+    // the workgroup's span plus the window's reach goes through LDS: one coalesced read of the
+    // smoothed scores instead of W_s reads per position
+    const int t0 = blockIdx.x * SPAN + gamma - half;          // position of tile[0]
+    const int tn = SPAN + 2 * half;
+    const float pad = pb.pmax ? -INFINITY : 0.f;
+    for (int x = threadIdx.x; x < tn; x += 256) {
+      const int m = t0 + x;
+      tile[x] = (m >= 0 && m < pb.P) ? e[m] : pad;
+    }
+    __syncthreads();
+    if (pb.pmax) {
+#pragma unroll
+      for (int j = 0; j < BOX_PT; ++j) s[j] = -INFINITY;
+      for (int u = 0; u < w_s; ++u)
+#pragma unroll
+        for (int j = 0; j < BOX_PT; ++j) s[j] = fmaxf(s[j], tile[threadIdx.x + 256 * j + u]);
+#pragma unroll
+      for (int j = 0; j < BOX_PT; ++j) s[j] = s[j] == -INFINITY ? 0.f : s[j];
+    } else {
+      for (int u = 0; u < w_s; ++u)
+#pragma unroll
+        for (int j = 0; j < BOX_PT; ++j) s[j] += tile[threadIdx.x + 256 * j + u];
+    }
+  } else {
+    // a window wider than the span: straight from global memory, eight offsets at a time, every
+    // load of the batch unconditional (clamped index) and issued before the first is used
+    constexpr int OB = 8;
+    auto filter = [&](auto maxc) {
+      constexpr bool PMAX = decltype(maxc)::value;
+      bool any[BOX_PT];
+#pragma unroll
+      for (int j = 0; j < BOX_PT; ++j) any[j] = false;
+      for (int o0 = gamma - half; o0 <= last; o0 += OB) {
+        float x[OB][BOX_PT];
+#pragma unroll
+        for (int u = 0; u < OB; ++u)
+#pragma unroll
+          for (int j = 0; j < BOX_PT; ++j) x[u][j] = e[min(max(n0 + 256 * j + o0 + u, 0), pb.P - 1)];
+#pragma unroll
+        for (int u = 0; u < OB; ++u)
+#pragma unroll
+          for (int j = 0; j < BOX_PT; ++j) {
+            const int m = n0 + 256 * j + o0 + u;
+            const bool in = o0 + u <= last && m >= 0 && m < pb.P;
+            if constexpr (PMAX) {
+              s[j] = in ? (any[j] ? fmaxf(s[j], x[u][j]) : x[u][j]) : s[j];
+              any[j] = any[j] || in;
+            } else {
+              s[j] += in ? x[u][j] : 0.f;
+            }
+          }
+      }
+    };
+    if (pb.pmax) filter(std::true_type{}); else filter(std::false_type{});
   }
-  for (int m = lo; m <= hi; ++m) s += e[m];
-  fin[(int64_t)g * pb.ld + n] = s / (float)w_s;
+#pragma unroll
+  for (int j = 0; j < BOX_PT; ++j) {
+    const int n = n0 + 256 * j;
+    if (n < pb.P) fin[(int64_t)g * pb.ld + n] = pb.pmax ? s[j] : s[j] / (float)w_s;
+  }
 }
 
 }  // namespace
@@ -532,7 +595,7 @@ int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, in
     RK_LAUNCH(ST_ROWTOPK, st, k_row_finish, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, score, cnt_hi, sum_hi,
               cmask, thr, rowsum);
   }
-  RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, e, rowsum, fin,
+  RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 256 * BOX_PT - 1) / (256 * BOX_PT), pb.Hkv), dim3(256), 0, st, pb, e, rowsum, fin,
             aws_info, aws_d);
   return hip_status();
 }
@@ -551,7 +614,7 @@ int launch_smooth_fused_tail(const Prob& pb, const float* score, const float* em
   unsigned long long* rowsum = (unsigned long long*)(ws + lay.rowsum);
   RK_LAUNCH(ST_ROWTOPK, st, k_row_finish_slices, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, score, fp.cnt_hi,
             fp.sum_hi, fp.scnt, fp.sval, fp.sidx, nchunks, fp.caps, fp.thr, rowsum);
-  RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 255) / 256, pb.Hkv), dim3(256), 0, st, pb, ema, rowsum, fin,
+  RK_LAUNCH(ST_BOX, st, k_box, dim3((pb.P + 256 * BOX_PT - 1) / (256 * BOX_PT), pb.Hkv), dim3(256), 0, st, pb, ema, rowsum, fin,
             aws_info, aws_d);
   return hip_status();
 }

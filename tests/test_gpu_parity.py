@@ -221,6 +221,7 @@ def _smooth_select_inputs(seed, Hkv, W, P, kind):
     ("lognormal", 1, 900, 50, 5, 2000.0, 0.3),      # single query: no adaptive window
     ("drifting", 40, 20001, 700, 5, 100.0, 0.3),    # two row blocks (32 + 8), dense candidate runs, odd row length
     ("lognormal", 70, 6000, 400, 5, 500.0, 0.2),    # three row blocks (32 + 32 + 6)
+    ("drifting", 16, 20000, 512, 5, 8.0, 0.3),      # |dD| / beta in the hundreds: a window wider than a workgroup's span, a large shift
 ])
 def test_smooth_select_compact_stage_exact(rk, oracle_mod, kind, W, P, B, k, beta, alpha):
     """Same FP32 scores into both sides: index sums, W_s, gamma and the selection are exact."""
