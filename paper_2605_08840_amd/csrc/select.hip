@@ -2,8 +2,9 @@
 // window positions appended.
 //
 // The row of final scores of a head is cut into chunks that many workgroups scan in parallel:
-//   bracket : a sample of the row brackets the threshold of the top-(B-W)
-//   scan    : per chunk, count the entries above the bracket; those inside it leave as bit masks
+//   scan    : per chunk: a sample of the row brackets the threshold of the top-(B-W) (every
+//             workgroup of the head repeats this search); count the entries above the bracket;
+//             those inside it leave as bit masks
 //   finish  : per head, exact threshold among the candidates (bisection on keys; ties by
 //             position), or the exact radix search of the whole row if the bracket missed;
 //             number of selected entries before every chunk
@@ -39,15 +40,14 @@ int static_scratch(char** out) {
   return RESTKV_OK;
 }
 
-constexpr int SCH = 4096;            // positions per chunk = workgroup of the scan (4 per thread)
+constexpr int SCH = 4096;            // positions per chunk = workgroup of the scan (16 per thread)
 constexpr int SCAP = 4096;           // candidates the finishing step can take
 constexpr int LHIST = 8192;          // chunk counters kept in LDS by the finishing step
-constexpr uint32_t PENDING = 0xFFFFFFFFu;
 
 struct SelPtrs {
   float2* thr;            // [Hkv] bracket of the head's threshold
   uint32_t* above;        // [Hkv, nchunks] entries above the bracket
-  uint8_t* cmask;         // [Hkv, nchunks * 1024] entries inside the bracket: 4 bits per thread of the scan
+  uint16_t* cmask;        // [Hkv, nchunks * 256] entries inside the bracket: 16 bits per thread of the scan
   uint32_t* cut;          // [Hkv, 4] threshold key, position cut for ties
   uint32_t* offs;         // [Hkv, nchunks] selected entries in the chunks before
 };
@@ -59,28 +59,11 @@ SelPtrs sel_ptrs(const Prob& pb, char* ws, size_t* bytes) {
   SelPtrs w;
   w.thr = (float2*)take((size_t)pb.Hkv * 8);
   w.above = (uint32_t*)take((size_t)pb.Hkv * nch * 4);
-  w.cmask = (uint8_t*)take((size_t)pb.Hkv * nch * 1024);
+  w.cmask = (uint16_t*)take((size_t)pb.Hkv * nch * 512);
   w.cut = (uint32_t*)take((size_t)pb.Hkv * 16);
   w.offs = (uint32_t*)take((size_t)pb.Hkv * nch * 4);
   if (bytes) *bytes = off;
   return w;
-}
-
-// grid (Hkv), 256 threads: bracket of the head's top-(B-W) threshold from a sample
-__global__ __launch_bounds__(256) void k_sel_bracket(Prob pb, const float* __restrict__ fin, SelPtrs w) {
-  __shared__ CountSmem cs;
-  const int g = blockIdx.x;
-  const float* row = fin + (int64_t)g * pb.ld;
-  const int k = head_budget(pb, g) - pb.W;
-  if (k >= pb.P) {
-    if (threadIdx.x == 0) w.thr[g] = make_float2(INFINITY, INFINITY);
-    return;
-  }
-  int it = 0;
-  uint32_t klo, khi;
-  block_bracket<SEL_NS / 256, 1>(row, pb.P, k, cs, it, klo, khi);   // smoothed rows: single, spread samples
-  if (threadIdx.x == 0)
-    w.thr[g] = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
 }
 
 __device__ __forceinline__ bool sel_pred(float x, int n, uint32_t tau, uint32_t pos_cut) {
@@ -92,39 +75,53 @@ __device__ __forceinline__ bool sel_pred(float x, int n, uint32_t tau, uint32_t 
   return a >= b;
 }
 
-// Scan of one chunk of a head's final scores: thread t owns positions chunk * 4096 + 4 t .. + 3;
-// the entries above the bracket are counted (one count per chunk), the entries inside it leave
-// as a 4-bit mask per thread.  grid (chunks, Hkv), SEL_NT = 1024 threads.
-__global__ __launch_bounds__(SEL_NT) void k_sel_scan(Prob pb, const float* __restrict__ fin, SelPtrs w,
-                                                     int nchunks, int vec) {
-  __shared__ uint32_t red[SEL_NW];
+// Bracket and scan of one chunk of a head's final scores.  Every workgroup of a head first
+// brackets the head's top-(B-W) threshold from the same sample of the row (same arithmetic, same
+// result: thirty-two workgroups repeating a search that would otherwise leave all but eight
+// compute units idle behind a launch of its own), with the loads of its own chunk already in
+// flight.  Thread t then owns positions chunk * 4096 + 16 t .. + 15: the entries above the bracket
+// are counted (one count per chunk), the entries inside it leave as a 16-bit mask per thread
+// (element e at bit 15 - e).  grid (chunks, Hkv), 256 threads.
+__global__ __launch_bounds__(256) void k_sel_scan(Prob pb, const float* __restrict__ fin, SelPtrs w,
+                                                  int nchunks, int vec) {
+  __shared__ CountSmem cs;
+  __shared__ uint32_t red[4];
   const int g = blockIdx.y, ch = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const float* row = fin + (int64_t)g * pb.ld;
-  const float2 th = w.thr[g];
-  const int n0 = ch * SCH + 4 * tid;
-  float x[4];
-  if (vec && n0 + 3 < pb.P) {
-    const float4 v4 = *(const float4*)(row + n0);
-    x[0] = v4.x; x[1] = v4.y; x[2] = v4.z; x[3] = v4.w;
+  const int n0 = ch * SCH + 16 * tid;
+  float x[16];
+  if (vec && n0 + 15 < pb.P) {
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const float4 v4 = *(const float4*)(row + n0 + 4 * q4);
+      x[4 * q4] = v4.x; x[4 * q4 + 1] = v4.y; x[4 * q4 + 2] = v4.z; x[4 * q4 + 3] = v4.w;
+    }
   } else {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) x[e] = n0 + e < pb.P ? row[n0 + e] : -INFINITY;
+    for (int e = 0; e < 16; ++e) x[e] = row[min(n0 + e, pb.P - 1)];     // unconditional, masked below
+#pragma unroll
+    for (int e = 0; e < 16; ++e) x[e] = n0 + e < pb.P ? x[e] : -INFINITY;
   }
+  const int k = head_budget(pb, g) - pb.W;
+  float2 th = make_float2(INFINITY, INFINITY);          // everything is kept: nothing above, nothing inside
+  if (k < pb.P) {                                       // block-uniform
+    int it = 0;
+    uint32_t klo, khi;
+    block_bracket<SEL_NS / 256, 1>(row, pb.P, k, cs, it, klo, khi);   // smoothed rows: single, spread samples
+    th = make_float2(klo ? key_float(klo) : -INFINITY, khi != 0xFFFFFFFFu ? key_float(khi) : INFINITY);
+  }
+  if (ch == 0 && tid == 0) w.thr[g] = th;
   float tlo = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.x)));
   float thi = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, th.y)));
   settle_scalars(tlo, thi);
   uint32_t hb = 0, lb = 0;
 #pragma unroll
-  for (int e = 0; e < 4; e += 2) shift_in_gt_2x2(hb, lb, x[e], x[e + 1], thi, tlo);   // element e ends up at bit 3 - e
-  w.cmask[((int64_t)g * nchunks + ch) * 1024 + tid] = (uint8_t)(lb & ~hb);
+  for (int e = 0; e < 16; e += 2) shift_in_gt_2x2(hb, lb, x[e], x[e + 1], thi, tlo);
+  w.cmask[((int64_t)g * nchunks + ch) * 256 + tid] = (uint16_t)(lb & ~hb);
   const uint32_t c = wave_sum((uint32_t)__popc(hb));
   if (lane == 0) red[wv] = c;
   __syncthreads();
-  if (tid == 0) {
-    uint32_t tot = 0;
-    for (int j = 0; j < SEL_NW; ++j) tot += red[j];
-    w.above[g * nchunks + ch] = tot;
-  }
+  if (tid == 0) w.above[g * nchunks + ch] = red[0] + red[1] + red[2] + red[3];
 }
 
 // Exact threshold of a head and the chunks' output offsets.  One workgroup per head
@@ -161,8 +158,8 @@ __global__ __launch_bounds__(SEL_NT) void k_sel_finish(Prob pb, const float* __r
   if (lds_hist) for (int c = tid; c < nchunks; c += SEL_NT) lhist[c] = 0;
   else for (int c = tid; c < nchunks; c += SEL_NT) offs[c] = 0;      // (global counters: offs itself)
   // counts above the bracket and number of candidates
-  const int ndw = nchunks * 256;
-  const uint32_t* mrow = (const uint32_t*)(w.cmask + (int64_t)g * nchunks * 1024);
+  const int ndw = nchunks * 128;                 // two threads of the scan per 32-bit word
+  const uint32_t* mrow = (const uint32_t*)(w.cmask + (int64_t)g * nchunks * 256);
   uint32_t c_mine = 0, a_mine = 0;
   for_each_mask_word<SEL_NT>(mrow, ndw, [&](int, uint32_t m) { c_mine += (uint32_t)__popc(m); });
   for (int c = tid; c < nchunks; c += SEL_NT) a_mine += above[c];
@@ -184,7 +181,7 @@ __global__ __launch_bounds__(SEL_NT) void k_sel_finish(Prob pb, const float* __r
       while (m) {
         const int b = __builtin_ctz(m);
         m &= m - 1;
-        cpos[slot++] = 4 * (4 * x + (b >> 3)) + 3 - (b & 7);     // byte = thread of the scan, bit 3 - e = element e
+        cpos[slot++] = 16 * (2 * x + (b >> 4)) + 15 - (b & 15);  // half word = thread of the scan, bit 15 - e = element e
       }
     });
     __syncthreads();
@@ -334,8 +331,7 @@ int launch_select(const Prob& pb, const float* fin, int32_t* idx, char* ws, hipS
   const int nch = (pb.P + SCH - 1) / SCH;
   const SelPtrs w = sel_ptrs(pb, ws, nullptr);
   const int vec = ((pb.ld & 3) == 0 && ((uintptr_t)fin & 15u) == 0) ? 1 : 0;
-  RK_LAUNCH(ST_SELECT, st, k_sel_bracket, dim3(pb.Hkv), dim3(256), 0, st, pb, fin, w);
-  RK_LAUNCH(ST_SELECT, st, k_sel_scan, dim3(nch, pb.Hkv), dim3(SEL_NT), 0, st, pb, fin, w, nch, vec);
+  RK_LAUNCH(ST_SELECT, st, k_sel_scan, dim3(nch, pb.Hkv), dim3(256), 0, st, pb, fin, w, nch, vec);
   RK_LAUNCH(ST_SELECT, st, k_sel_finish, dim3(pb.Hkv), dim3(SEL_NT), 0, st, pb, fin, w, nch);
   RK_LAUNCH(ST_SELECT, st, k_sel_emit, dim3(nch, pb.Hkv), dim3(256), 0, st, pb, fin, w, nch, idx);
   return hip_status();
