@@ -171,6 +171,41 @@ def test_tiny_config_full_path(rk, oracle_mod):
             assert np.array_equal(got["v_out"][g], v.numpy()[g][got["idx"][g]])
 
 
+@pytest.mark.parametrize("Hq,Hkv,d,L,W,B,dtype", [
+    (4, 2, 64, 9, 8, 9, "f32"),          # one prefix token
+    (2, 1, 128, 20, 4, 10, "bf16"),      # prefix shorter than a tile and than a sample run
+    (8, 2, 128, 129, 64, 100, "bf16"),   # full window, prefix one past a tile
+    (4, 4, 64, 70, 7, 20, "bf16"),       # prefix one short of a tile, MHA
+    (4, 1, 128, 200, 1, 50, "bf16"),     # a single window query
+    (4, 2, 64, 64 + 4096, 64, 65, "bf16"),   # budget of one prefix token, prefix = one scan chunk exactly
+    (2, 2, 128, 3 + 4097, 3, 4100, "f32"),   # budget = everything, prefix one past a scan chunk
+])
+def test_edge_shapes_whole_path(rk, oracle_mod, Hq, Hkv, d, L, W, B, dtype):
+    """Shapes at the edges of the tiling (one prefix token, prefixes around a 64-key tile and a
+    4096-position chunk, one window query, budgets of one prefix token and of everything): raw
+    score against the oracle; every later stage exactly, on the GPU's own FP32 output of the stage
+    before (index sums, window, selection, gather)."""
+    w = workloads.small_case(Hq=Hq, Hkv=Hkv, d=d, L=L, W=W, B=B, dtype=dtype, D=2 * d, seed=31)
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    got = run_gpu_layer(rk, w, q, k, v, wo)
+    ref = oracle_score(oracle_mod, w, q, k, v, wo)
+    kf, vf = k.float().numpy(), v.float().numpy()
+    for g in range(Hkv):
+        Ig, tol = ref[g]
+        assert_score_close(got["score"][g], Ig, tol, f"edge shape head {g}")
+        sm = oracle_mod.smooth_head(got["score"][g], w.alpha, w.beta, w.base_window, True, w.budget)
+        np.testing.assert_allclose(got["ema"][g], sm["ema"], rtol=1e-5, atol=1e-30)
+        if W >= 2:
+            assert got["aws_d"][g, 0] == sm["d_front"] and got["aws_d"][g, 1] == sm["d_rear"]
+        assert tuple(got["aws_info"][g]) == (sm["w_s"], sm["gamma"])
+        want = oracle_mod.box(got["ema"][g].astype(np.float64), sm["w_s"], sm["gamma"])
+        np.testing.assert_allclose(got["final"][g], want, rtol=1e-5, atol=1e-30)
+        np.testing.assert_array_equal(got["idx"][g], oracle_mod.select(got["final"][g].astype(np.float64), W, B))
+        assert np.array_equal(got["k_out"][g], kf[g][got["idx"][g]])
+        assert np.array_equal(got["v_out"][g], vf[g][got["idx"][g]])
+
+
 def test_llama_8k_config_score_and_selection(rk, oracle_mod):
     """Benchmark configuration 2, "llama_8k": 32 q / 8 kv heads, d 128, L 8192, W 32, bf16, planted heavy keys."""
     w = workloads.WORKLOADS["llama_8k"]
