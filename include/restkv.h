@@ -230,10 +230,11 @@ int restkv_select_b(const restkv_params* p, const float* final_score, const int3
  * restkv_select (same kernels); the scratch is an array inside the library's device image, one
  * copy per GPU that lives until the process ends (restkv_select_static_capacity() bytes, 4 MiB).
  * Returns RESTKV_EWORKSPACE, with nothing enqueued, when the shape needs more than that: about
- * 1 KiB per 4096 prefix positions and KV head (120 KV heads fit at 128k tokens).  The call allocates nothing and frees nothing (the first call on a GPU looks up
- * the array's address once).  Every call on a GPU uses that GPU's
- * one array: calls that overlap in time on one GPU (different streams or host threads) race;
- * calls ordered on one stream are safe, and each call clears what it needs cleared itself.
+ * 0.5 KiB per 4096 prefix positions and KV head (240 KV heads fit at 128k tokens).  The call
+ * allocates nothing and frees nothing (the first call on a GPU looks up the array's address
+ * once).  Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU
+ * (different streams or host threads) race; calls ordered on one stream are safe, and each call
+ * clears what it needs cleared itself.
  */
 int restkv_select_static(const restkv_params* p, const float* final_score, int32_t* idx,
                          restkv_stream_t stream);
