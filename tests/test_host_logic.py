@@ -70,3 +70,42 @@ def test_check_selection_accepts_near_ties_only():
     fin2[P - 11] = fin2[P - 10] * (1 - 1e-5)     # a near-tie just below the threshold
     swap = np.concatenate([[P - 11], np.arange(P - 9, P), [P, P + 1]])
     assert check_selection(swap, fin2, W, B, 1e-3) == 2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N above 1 exits with a message instead of timing anything."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="2")
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py")], capture_output=True, text=True, timeout=120,
+                       env=env)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_product_and_oracle_do_not_know_each_other():
+    """No source of the package mentions the oracle, no source of the oracle mentions the package
+    (the two share no code; only tests, the smoke check and the benchmark's CPU leg use both)."""
+    import os
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+    def sources(top, exts):
+        for d, _, files in os.walk(os.path.join(root, top)):
+            if "_build" in d or "__pycache__" in d:
+                continue
+            for f in files:
+                if f.endswith(exts):
+                    yield os.path.join(d, f)
+
+    for path in sources("paper_2605_08840_amd", (".py", ".hip", ".hpp", ".h")):
+        text = open(path).read()
+        assert not re.search(r"\boracle\b", text), path
+    for path in list(sources("oracle", (".py", ".c", ".h"))):
+        text = open(path).read()
+        assert "paper_2605_08840_amd" not in text and "librestkv.so" not in text and "restkv.h" not in text, path
+    assert not re.search(r"\boracle\b", open(os.path.join(root, "include", "restkv.h")).read())
