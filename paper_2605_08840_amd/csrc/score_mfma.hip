@@ -193,9 +193,9 @@ __device__ __forceinline__ void wait_vm() {
 // from 2 rb on, so a wavefront takes the row blocks pr and D/32 - 1 - pr of one head: D/16 + 2
 // k-steps whatever pr.  The value tiles arrive through a 4-deep asynchronous LDS ring and are
 // the B operand shared by all wavefronts; the partial dots of a head's wavefronts meet in LDS.
-// The two 32-key halves of a tile each have a matrix quarter (20 MFMAs) and a vector quarter (row
-// dots) of about the same length; wavefronts 0..3 and 4..7 run them in complementary order (see
-// the loop), so the matrix cores stay fed.  The two wavefronts of a head are in the same group.
+// A tile has a matrix part (two 32-key halves of 20 MFMAs) and a vector part (the row dots);
+// wavefronts 0..3 and 4..7 run them in complementary order (see the loop), so the matrix cores
+// stay fed.  The two wavefronts of a head are in the same group.
 // grid (key chunks, ceil(G/HPW), Hkv), 512 threads; HPW = 4 heads per workgroup (8 for D = 64).
 template <int D>
 __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __restrict__ v,
@@ -306,43 +306,42 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
       if (hf == 0) part[(t - t0) & 1][hw][PR][32 * nb + rr] = acc;
     };
 
-    // Half-steps H_0, H_1, ... separated by workgroup barriers.  Wavefronts 0..3 run
-    //   H_2t: matrix(0,t) dot(0,t)      H_2t+1: matrix(1,t) dot(1,t),
-    // wavefronts 4..7 the complementary order
-    //   H_2t: dot(1,t-1) matrix(0,t)    H_2t+1: dot(0,t) matrix(1,t),
-    // so that on every SIMD one wavefront feeds the matrix cores while the other does the (about
-    // equally long) vector quarter.  A tile is read from H_2t to H_2t+2; the copy of tile t+2 is
-    // issued at the top of H_2t+1 (its slot held tile t-2); a wavefront waits for its share of tile
-    // t+1 before the barrier that ends H_2t+1, when only the copy of tile t+2 is younger.
+    // Steps H_t, one tile each, separated by workgroup barriers.  Wavefronts 0..3 run
+    //   H_t: matrix(0,t) matrix(1,t) dot(0,t) dot(1,t),
+    // wavefronts 4..7 the complementary order, one tile behind with their row dots,
+    //   H_t: dot(0,t-1) dot(1,t-1) matrix(0,t) matrix(1,t),
+    // so that on every SIMD one wavefront feeds the matrix cores while the other does its vector
+    // work.  Tile t is read in H_t only; the copy of tile t+2 is issued at the top of H_t (its
+    // slot held tile t-2); a wavefront waits for its share of tile t+1 before the barrier that
+    // ends H_t, when only the copy of tile t+2 is younger.  The partial dots of tile t meet in LDS
+    // one step after they were written (two buffers).
     const bool late = wv >= NW / 2;
     wait_vm<NG>();           // own share of tile t0 (compiler-issued loads above are older or waited for)
     wg_barrier();
     for (int t = t0; t < t1; ++t) {
-      // ---- H_2t ----
-      if (!late) {
-        if (t > t0) head_sum(t - 1);
-        mat(0, t);
-        dot(0, t);
-      } else {
-        if (t > t0) dot(1, t - 1);
-        mat(0, t);
-      }
-      wg_barrier();
-      // ---- H_2t+1 ----
       issue_tile(t + 2);     // into the slot of tile t-2
       if (!late) {
+        if (t > t0) head_sum(t - 1);
+        mat(0, t);
         mat(1, t);
+        dot(0, t);
         dot(1, t);
       } else {
-        if (t > t0) head_sum(t - 1);
-        dot(0, t);
+        if (t > t0 + 1) head_sum(t - 2);
+        if (t > t0) { dot(0, t - 1); dot(1, t - 1); }
+        mat(0, t);
         mat(1, t);
       }
       wait_vm<NG>();         // own share of tile t+1 (only the copy of tile t+2 is younger)
       wg_barrier();
     }
-    // ---- H_2n: the late wavefronts' last vector quarter ----
-    if (late) dot(1, t1 - 1); else head_sum(t1 - 1);
+    if (late) {
+      dot(0, t1 - 1);
+      dot(1, t1 - 1);
+      if (t1 - 2 >= t0) head_sum(t1 - 2);
+    } else {
+      head_sum(t1 - 1);
+    }
     wg_barrier();
     if (late) head_sum(t1 - 1);
     wait_vm<0>();            // no copy may land in LDS after the workgroup has gone
