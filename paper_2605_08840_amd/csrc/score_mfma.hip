@@ -359,16 +359,17 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
 // A.V sums (outputs: the per-split statistics described in score_common.hpp).
 // grid (S, row blocks, Hkv), 512 threads.
 //
-// K tiles travel through a 4-deep, V tiles through a 5-deep asynchronous LDS ring.  A step t has a
+// K tiles travel through a 3-deep, V tiles through a 4-deep asynchronous LDS ring.  A step t has a
 // matrix half (P.V of tile t-1, then Q.K of tile t: 48 MFMAs) and a vector half (softmax
-// bookkeeping of tile t), separated by workgroup barriers; wavefronts 4..7 run one half-step
-// behind wavefronts 0..3, so the two wavefronts of a SIMD alternate between the matrix cores and
-// the vector ALUs.  With barriers E_0, E_1, ...: the early half reads K tile t in (E_2t, E_2t+1)
-// and V tile t in (E_2t+2, E_2t+3), the late half one barrier later.  The copy of tile t+3 is
-// issued in the vector half of step t (after E_2t+1 / E_2t+2, where the wavefront has slack) into
-// the K slot of tile t-1 and the V slot of tile t-2, both last read before E_2t; every wavefront
-// waits for its share of tile t+1 (only tile t+2 is younger) before its mid-step barrier, which
-// precedes E_2t+2.
+// bookkeeping of tile t).  Every wavefront passes ONE workgroup barrier per step: wavefronts 0..3
+// after the vector half, wavefronts 4..7 between the halves, so that the two wavefronts of a SIMD
+// alternate between the matrix cores and the vector ALUs without meeting twice per tile.  With
+// B_t the barrier of step t: K tile t and V tile t-1 are read between B_t-1 and B_t+1 at the
+// latest by the matrix halves of step t (early wavefronts: before B_t, late ones: before their
+// B_t too); the copy of tile t+2 is issued at the top of step t, after B_t-1, into the K slot of
+// tile t-1 and the V slot of tile t-2, both last read by a matrix half that precedes B_t-1; every
+// wavefront waits for its share of tile t+1 (only tile t+2 is younger) before its B_t, the first
+// barrier after which tile t+1 is read.
 template <int D>
 __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __restrict__ q,
                                                    const uint16_t* __restrict__ k,
@@ -378,8 +379,8 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
   using RingK = TileRing<D, 0>;
   using RingV = TileRing<D, 1>;
   constexpr int NG = 2 * (RingK::NI / NW);          // copies per wavefront and tile
-  __shared__ __attribute__((aligned(1024))) uint16_t Ks[4][TN * D];
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs[5][TN * D];
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks[3][TN * D];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[4][TN * D];
 
   const int s = blockIdx.x, g = blockIdx.z;
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
@@ -393,13 +394,12 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
   const uint32_t pitch = (uint32_t)pb.kv_st * 2u;
   auto issue_tile = [&](int t) {
     const int kb = kbeg + min(t, ntiles - 1) * TN;   // past the end: harmless repeat into a free slot
-    RingK::template issue<NW>(kg, pitch, kb, pb.L, Ks[t & 3], wv, l);
-    RingV::template issue<NW>(vg, pitch, kb, pb.L, Vs[t % 5], wv, l);
+    RingK::template issue<NW>(kg, pitch, kb, pb.L, Ks[t % 3], wv, l);
+    RingV::template issue<NW>(vg, pitch, kb, pb.L, Vs[t & 3], wv, l);
   };
   if (ntiles > 0) {
     issue_tile(0);
     issue_tile(1);
-    issue_tile(2);
   }
 
   bf16x8 qf[KS];
@@ -455,17 +455,17 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
   };
 
   if (ntiles > 0) {
-    wait_vm<2 * NG>();       // own share of tile 0
-    wg_barrier();            // E_0
+    wait_vm<NG>();           // own share of tile 0
+    wg_barrier();            // B_-1
     const bool late = wv >= NW / 2;
-    if (late) wg_barrier();
 
     for (int t = 0; t < ntiles; ++t) {
       const int kb = kbeg + t * TN;
+      issue_tile(t + 2);     // into the K slot of tile t-1 and the V slot of tile t-2, both last read before B_t-1
       __builtin_amdgcn_s_setprio(2);
-      // ---- matrix half-step: P.V of the previous tile, logits S^T[key, row] = K Q^T of this one ----
-      if (t > 0) accumulate(Vs[(t - 1) % 5]);
-      const uint16_t* kt = Ks[t & 3];
+      // ---- matrix half: P.V of the previous tile, logits S^T[key, row] = K Q^T of this one ----
+      if (t > 0) accumulate(Vs[(t - 1) & 3]);
+      const uint16_t* kt = Ks[t % 3];
       f32x16 sacc[2];
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
@@ -485,11 +485,12 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
 #pragma unroll
           for (int mb = 0; mb < 2; ++mb) sacc[mb] = MFMA(a[ks][mb], qf[k0 + ks], sacc[mb]);
       }
-      wait_vm<NG>();         // own share of tile t+1 (only the copies of tile t+2 are younger)
-      wg_barrier();
       __builtin_amdgcn_s_setprio(0);
-      // ---- vector half-step: first the copies of tile t+3, into slots last read before E_2t ----
-      issue_tile(t + 3);
+      if (late) {            // B_t of the late wavefronts: between the halves
+        wait_vm<NG>();       // own share of tile t+1 (only the copies of tile t+2 are younger)
+        wg_barrier();
+      }
+      // ---- vector half ----
       const bool tile_mask = (kb + TN > kend) || (pb.causal && kb + TN - 1 > pb.P);
       if (tile_mask) {
 #pragma unroll
@@ -633,10 +634,12 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
           }
         lsum += (ls[0] + ls[1]) + (ls[2] + ls[3]);
       }
-      wg_barrier();
+      if (!late) {           // B_t of the early wavefronts: after both halves
+        wait_vm<NG>();
+        wg_barrier();
+      }
     }
-    accumulate(Vs[(ntiles - 1) % 5]);   // its slot is not a target of the copies still in flight
-    if (!late) wg_barrier();
+    accumulate(Vs[(ntiles - 1) & 3]);   // its slot is not a target of the copies still in flight
     wait_vm<0>();            // no copy may land in LDS after the workgroup has gone
   }
   const float ltot = xhalf_sum(lsum);
