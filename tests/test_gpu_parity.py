@@ -229,6 +229,51 @@ def test_llama_8k_config_score_and_selection(rk, oracle_mod):
         assert np.array_equal(got["v_out"][g], vf[g][got["idx"][g]])
 
 
+def test_layer_replayed_from_a_hip_graph(rk):
+    """The calls of a layer allocate nothing, synchronise nothing and clear their scratch with
+    kernels, so a caller may capture them: the captured layer (selection through the entry point
+    with the library's own scratch) is replayed three times, with eager work and synchronisations
+    in between, and every replay must reproduce the eager result bit for bit."""
+    w = workloads.WORKLOADS["llama_8k"]
+    q, k, v = workloads.make_qkv(w, 0, "cuda")
+    wo = workloads.make_wo(w, 0, "cuda")
+    p = params_for(rk, w)
+    gram = torch.empty((w.n_q_heads, w.head_dim, w.head_dim), dtype=torch.float32, device="cuda")
+    rk.restkv_prepare_wo(p, wo, gram)
+
+    def layer(buf):
+        rk.restkv_score(p, q, k, v, gram, buf.score, buf.workspace)
+        rk.restkv_smooth(p, buf.score, buf.ema, buf.final, buf.aws_info, buf.aws_d, buf.workspace)
+        rk.restkv_select_static(p, buf.final, buf.idx)
+        rk.restkv_compact(p, k, v, buf.idx, buf.k_out, buf.v_out)
+
+    eager, other, cap = (rk.alloc_layer_buffers(p, q.dtype, "cuda") for _ in range(3))
+    layer(eager)                                   # also the warm-up: every one-time lookup has happened
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            layer(cap)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (cap.score, cap.ema, cap.final, cap.k_out, cap.v_out):
+            t.zero_()
+        cap.idx.fill_(-7)
+        layer(other)                               # eager work of the program between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        P = w.seq_len - w.window
+        assert torch.equal(cap.score[..., :P], eager.score[..., :P]), rep
+        assert torch.equal(cap.final[..., :P], eager.final[..., :P]), rep
+        assert torch.equal(cap.aws_info, eager.aws_info) and torch.equal(cap.aws_d, eager.aws_d), rep
+        assert torch.equal(cap.idx, eager.idx), rep
+        assert torch.equal(cap.k_out, eager.k_out) and torch.equal(cap.v_out, eager.v_out), rep
+
+
 # ------------------------------------------------------------------ stage-isolated, bit-exact
 def _smooth_select_inputs(seed, Hkv, W, P, kind):
     r = np.random.default_rng(seed)
