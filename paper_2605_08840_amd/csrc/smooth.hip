@@ -119,12 +119,18 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
                                                   float* __restrict__ ema, const float2* __restrict__ thr,
                                                   uint32_t* __restrict__ cnt_hi,
                                                   unsigned long long* __restrict__ sum_hi,
-                                                  uint16_t* __restrict__ cmask) {
+                                                  uint16_t* __restrict__ cmask, int rs) {
+  // rs = 1, 2 or 4 wavefronts share a run of positions and split the rows of every block of 64
+  // among them (short prefixes: more wavefronts, more bytes in flight); their partial weighted
+  // sums meet in LDS at the end.  rs = 1: a wavefront works alone, no barrier anywhere.
+  __shared__ float esum[4][EW_NE][64];
   const int g = blockIdx.y, l = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // (a scalar for the compiler)
-  const int wg = blockIdx.x * 4 + wv;            // wavefront along the prefix
+  const int part = wv % rs, rpp = 64 / rs;       // this wavefront's share of a block of 64 rows
+  const int wg = blockIdx.x * (4 / rs) + wv / rs;   // run of positions along the prefix
   const int wbase = wg * EW_POS;
-  if (wbase >= pb.P) return;                     // no barrier anywhere below
+  const bool active = wbase < pb.P;
+  if (rs == 1 && !active) return;
   const int nwt = scan_waves(pb.P);
   const float* s = score + (int64_t)g * pb.W * pb.ld;
   const bool scan = pb.adaptive != 0;
@@ -196,7 +202,8 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
   };
 
   for (int blk = 0; blk * 64 < pb.W; ++blk) {
-    const int r0 = blk * 64, r1 = min(pb.W, r0 + 64);
+    const int r0 = blk * 64 + part * rpp, r1 = min(pb.W, r0 + rpp);
+    if (!active || r0 >= r1) continue;           // wave-uniform: nothing of this block is this wavefront's
     float xs[EPF][EW_NE];
 #pragma unroll
     for (int u = 0; u < EPF; ++u) load_row(min(r0 + u, r1 - 1), xs[u]);   // (past the end: the last row again)
@@ -212,6 +219,15 @@ __global__ __launch_bounds__(256) void k_ema_scan(Prob pb, const float* __restri
       }
     }
     end_block(blk);
+  }
+  if (rs > 1) {                                  // workgroup-uniform
+#pragma unroll
+    for (int k = 0; k < EW_NE; ++k) esum[wv][k][l] = e[k];
+    __syncthreads();
+    if (part != 0 || !active) return;
+    for (int o = 1; o < rs; ++o)
+#pragma unroll
+      for (int k = 0; k < EW_NE; ++k) e[k] += esum[wv + o][k][l];
   }
 #pragma unroll
   for (int j = 0; j < EW_NE / 4; ++j) {
@@ -586,11 +602,15 @@ int launch_smooth(const Prob& pb, const float* score, float* ema, float* fin, in
   if (pb.adaptive)
     RK_LAUNCH(ST_ROWTOPK, st, k_sample_bracket, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, score, thr,
               cnt_hi, sum_hi);
-  const dim3 ge((pb.P + 4 * EW_POS - 1) / (4 * EW_POS), pb.Hkv);
+  // short prefixes: 2 or 4 wavefronts per run of positions, until about a thousand wavefronts stream
+  const int64_t runs = (int64_t)scan_waves(pb.P) * pb.Hkv;
+  const int rs = runs >= 1024 ? 1 : (runs >= 512 ? 2 : 4);
+  const int ppw = 4 / rs;
+  const dim3 ge((scan_waves(pb.P) + ppw - 1) / ppw, pb.Hkv);
   if (vec)
-    RK_LAUNCH(ST_EMA, st, k_ema_scan<true>, ge, dim3(256), 0, st, pb, score, e, thr, cnt_hi, sum_hi, cmask);
+    RK_LAUNCH(ST_EMA, st, k_ema_scan<true>, ge, dim3(256), 0, st, pb, score, e, thr, cnt_hi, sum_hi, cmask, rs);
   else
-    RK_LAUNCH(ST_EMA, st, k_ema_scan<false>, ge, dim3(256), 0, st, pb, score, e, thr, cnt_hi, sum_hi, cmask);
+    RK_LAUNCH(ST_EMA, st, k_ema_scan<false>, ge, dim3(256), 0, st, pb, score, e, thr, cnt_hi, sum_hi, cmask, rs);
   if (pb.adaptive) {
     RK_LAUNCH(ST_ROWTOPK, st, k_row_finish, dim3(pb.W, pb.Hkv), dim3(256), 0, st, pb, score, cnt_hi, sum_hi,
               cmask, thr, rowsum);
