@@ -49,6 +49,45 @@ def stage_work(w, stage: str):
     return 0.0, 0.0
 
 
+def stage_read_write(w, stage: str):
+    """The algorithmic bytes of stage_work split into (read, written), or None for the stages
+    without a streaming share."""
+    Hq, Hkv, d, L, W, P, B = w.n_q_heads, w.n_kv_heads, w.head_dim, w.seq_len, w.window, w.prefix, w.budget
+    esz = 4 if w.dtype == "f32" else 2
+    if stage == "attn_partial":
+        return 2.0 * Hkv * L * d * esz + Hq * W * d * esz, 4.0 * Hq * W * d
+    if stage == "score":
+        return 2.0 * Hkv * P * d * esz + 4.0 * Hq * P, 4.0 * Hkv * W * P
+    if stage == "vv":
+        return 1.0 * Hkv * P * d * esz, 4.0 * Hq * P
+    if stage == "ema":
+        return 4.0 * Hkv * W * P, 4.0 * Hkv * P
+    return None
+
+
+def stream_reference(rk, read_bytes, write_bytes, reps=10):
+    """Microseconds a plain streaming kernel of the library (restkv_stream_reference: 16-byte
+    loads and stores, no arithmetic) takes for the same read / write byte mix, median
+    of `reps` launches alternating between two buffer pairs so that no launch finds its data in
+    the memory-side cache."""
+    import torch
+    rb, wb = int(read_bytes) // 16 * 16, int(write_bytes) // 16 * 16
+    pairs = [(torch.zeros(max(rb, 16), dtype=torch.uint8, device="cuda"),
+              torch.empty(max(wb, 16), dtype=torch.uint8, device="cuda")) for _ in range(2)]
+    ts = []
+    for i in range(reps + 3):
+        src, dst = pairs[i & 1]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rk.restkv_stream_reference(src, rb, dst, wb)
+        e1.record()
+        e1.synchronize()
+        if i >= 3:
+            ts.append(e0.elapsed_time(e1) * 1e3)
+    ts.sort()
+    return ts[len(ts) // 2]
+
+
 # kernel behind each timed stage whose HBM traffic was measured with rocprofv3 --pmc
 STAGE_KERNEL = {"attn_partial": "k_attn_pipe", "vv": "k_vv_pipe", "score": "k_score_pipe", "ema": "k_ema_scan",
                 "compact": "k_compact", "box": "k_box"}
@@ -125,6 +164,8 @@ def main():
     ap.add_argument("--fused", action="store_true", help="score and smoothing as the one fused call")
     ap.add_argument("--no-overlap", action="store_true", help="skip the extra two-stream measurement")
     ap.add_argument("--no-fold", action="store_true", help="skip the extra measurement with all layers as one call")
+    ap.add_argument("--no-stream-ref", action="store_true",
+                    help="skip timing a plain streaming kernel with the dominant kernel's byte mix")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with events in the timed region")
     args = ap.parse_args()
@@ -245,6 +286,13 @@ def main():
                 "achieved": s["achieved"] / div, "peak": s["peak"] / div,
                 "unit": unit, "frac": s["achieved"] / s["peak"], "traffic": measured_traffic(w.name, dom),
                 "avg_ms": s["ms"] / s["launches"]}
+        # the same byte mix through a plain streaming kernel on this part, measured now
+        rw = stage_read_write(w, dom)
+        if s["bound"] == "hbm" and rw and not args.no_stream_ref:
+            us = stream_reference(rk, *rw)
+            roof["stream_ref"] = {"read_bytes": rw[0], "write_bytes": rw[1], "us": us,
+                                  "GBps": (rw[0] + rw[1]) / (us * 1e-6) / 1e9,
+                                  "kernel_over_stream_ref": roof["avg_ms"] * 1e3 / us}
 
     # The same steps with the layers spread over two streams (no kernel is bracketed).
     overlap = None

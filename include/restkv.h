@@ -266,6 +266,19 @@ int restkv_timing_read(double* ms, int64_t* launches, int n_stages);
 const char* restkv_stage_name(int stage);   /* "gram", "attn_partial", ... */
 
 /*
+ * Measurement aid, no part of the eviction path: one plain streaming kernel (16-byte loads
+ * and stores, reads and writes interleaved step by step, no arithmetic beyond an XOR) that reads
+ * read_bytes from src and writes write_bytes to dst, so that a kernel's HBM rate can be set
+ * against what the part delivers for the same byte mix.
+ * src, dst: DEVICE pointers (16-byte aligned), caller-owned, must not overlap; read_bytes and
+ * write_bytes multiples of 16; either may be 0.  Result: 32-bit word i of dst = i XOR (all
+ * words the writing thread read in earlier steps), i.e. dst[i] = i for an all-zero source.
+ * Asynchronous on `stream`; RESTKV_EINVAL for null, misaligned or odd-sized arguments.
+ */
+int restkv_stream_reference(const void* src, size_t read_bytes, void* dst, size_t write_bytes,
+                            void* stream);
+
+/*
  * Debug aid: with on != 0 restkv_score runs bf16 inputs through the FP32 vector kernels
  * instead of the MFMA kernels (same stages, every product in FP32).  Process-wide.
  */

@@ -4,5 +4,5 @@ from .binding import (  # noqa: F401
     RESTKV_POOL_MAX, RESTKV_TEMPORAL_INV_EMA, RESTKV_TEMPORAL_MEAN, LayerBuffers, RestkvError, RestkvParams, alloc_layer_buffers,
     alloc_workspace, evict_layer, lib, make_params, restkv_compact, restkv_prepare_wo, restkv_score, restkv_score_from_attention,
     restkv_score_smooth, restkv_select, restkv_select_b, restkv_select_static, restkv_select_static_capacity, restkv_smooth, restkv_smooth_b, restkv_debug_force_fp32,
-    restkv_timing_enable, restkv_timing_read, restkv_version, restkv_workspace_bytes, strerror,
+    restkv_stream_reference, restkv_timing_enable, restkv_timing_read, restkv_version, restkv_workspace_bytes, strerror,
 )

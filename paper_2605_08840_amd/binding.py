@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.restkv_stage_name.argtypes = [ctypes.c_int]
         L.restkv_debug_force_fp32.argtypes = [ctypes.c_int]
         L.restkv_debug_force_fp32.restype = ctypes.c_int
+        L.restkv_stream_reference.argtypes = [vp, sz, vp, sz, vp]
+        L.restkv_stream_reference.restype = ctypes.c_int
         for f in ("restkv_timing_enable", "restkv_timing_read", "restkv_prepare_wo", "restkv_score", "restkv_smooth", "restkv_select",
                   "restkv_compact", "restkv_version", "restkv_score_smooth", "restkv_smooth_b", "restkv_select_b"):
             getattr(L, f).restype = ctypes.c_int
@@ -226,6 +228,13 @@ def restkv_timing_read():
 
 def restkv_debug_force_fp32(on: bool):
     _chk(lib().restkv_debug_force_fp32(int(bool(on))), "restkv_debug_force_fp32")
+
+
+def restkv_stream_reference(src: Optional[torch.Tensor], read_bytes: int, dst: Optional[torch.Tensor],
+                            write_bytes: int, stream=None):
+    """Plain streaming kernel with a given read / write byte mix (a measurement aid)."""
+    _chk(lib().restkv_stream_reference(_ptr(src), int(read_bytes), _ptr(dst), int(write_bytes), _stream(stream)),
+         "restkv_stream_reference")
 
 
 def restkv_version() -> int:

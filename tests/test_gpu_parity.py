@@ -419,6 +419,39 @@ def test_compact_f32_and_out_of_range_index(rk):
             assert torch.equal(ko[g, j].cpu(), want) and torch.equal(vo[g, j].cpu(), -want)
 
 
+def test_stream_reference_kernel(rk):
+    """restkv_stream_reference (the plain streaming kernel bench.py times beside the dominant
+    kernel): with an all-zero source word i of the destination is i; with a source that holds one
+    set bit every word of the thread that read it, and all later ones of that thread, flip it;
+    bad arguments are refused."""
+    for rb, wb in ((0, 4096), (16 * 1000, 16 * 777), (16 * 100003, 16 * 300001), (48, 0), (1 << 22, 1 << 21),
+                   (16 * 9000001, 16 * 5)):
+        src = torch.zeros(max(rb, 16), dtype=torch.uint8, device="cuda")
+        dst = torch.full((wb // 4 + 1,), -1, dtype=torch.int32, device="cuda")
+        rk.restkv_stream_reference(src, rb, dst, wb)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:wb // 4], torch.arange(wb // 4, dtype=torch.int32, device="cuda")), (rb, wb)
+        assert int(dst[wb // 4]) == -1
+    # every destination word is i or i ^ bit, and some word does carry the bit the source holds
+    # (large enough for several steps per workgroup: a store carries what EARLIER steps read)
+    rb, wb = 16 * (3 * 4096 * 2048 + 12345), 16 * 1000003
+    src = torch.zeros(rb // 4, dtype=torch.int32, device="cuda")
+    src[0] = 1 << 20
+    dst = torch.zeros(wb // 4, dtype=torch.int32, device="cuda")
+    rk.restkv_stream_reference(src, rb, dst, wb)
+    torch.cuda.synchronize()
+    x = dst ^ torch.arange(wb // 4, dtype=torch.int32, device="cuda")
+    assert set(x.unique().tolist()) == {0, 1 << 20}
+    with pytest.raises(rk.RestkvError):
+        rk.restkv_stream_reference(src, 24, dst, 16)          # not a multiple of 16
+    with pytest.raises(rk.RestkvError):
+        rk.restkv_stream_reference(None, 32, dst, 16)
+    with pytest.raises(rk.RestkvError):
+        rk.restkv_stream_reference(src.view(torch.uint8)[4:], 32, dst, 16)   # misaligned source
+    with pytest.raises(rk.RestkvError):
+        rk.restkv_stream_reference(src, 32, dst, 24)          # not a multiple of 16
+
+
 def test_strided_token_major_cache(rk, oracle_mod):
     """K/V stored [L, Hkv, d] (token-major) and queries [W, Hq, d] through the stride fields."""
     w = workloads.small_case(Hq=4, Hkv=2, d=64, L=400, W=8, B=50, dtype="bf16", D=64, seed=21)
