@@ -130,6 +130,19 @@ __device__ __forceinline__ void dma_1k(const void* base, uint32_t voff, void* ld
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(ub), "s"(dst)
                : "memory", "m0");
 }
+// The same with the LDS byte address given as a number (wave-uniform, like base): nothing of the
+// copy's addressing is left to the vector ALU but the lane's own offset.
+__device__ __forceinline__ void dma_1k_to(const void* base, uint32_t voff, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_dst)
+               : "memory", "m0");
+}
+// LDS byte address of a __shared__ object
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// The wavefront's index inside its workgroup as a scalar: what is derived from it (ring slots,
+// row blocks, the early / late split) then lives in scalar registers and branches.
+__device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 // KIND 0: tile read as MFMA operand columns (16 rows x one 16-byte chunk per instruction):
 //         chunk c of row r sits at chunk position c ^ key, key = (r >> log2(16/CH)) & (CH-1).
 // KIND 1: tile read through the transposing 8-byte LDS read (4 rows x 4 consecutive chunks per
@@ -167,6 +180,25 @@ struct TileRing {
       const uint32_t voff = (uint32_t)row_of(r) * pitch + (uint32_t)(swz(r, cs) * 16);
       dma_1k(base, voff, lds_tile + blk * 512);
     }
+  }
+  // The fast path for tiles that lie wholly inside the matrix (no row clamp): the lane's byte
+  // offsets inside a tile are computed once per kernel (plan), a copy then takes the tile's
+  // wave-uniform address (tile_base = base + first row * pitch) and LDS address and no vector
+  // arithmetic at all.
+  template <int NW>
+  __device__ static __forceinline__ void plan(uint32_t pitch, int wv, int lane, uint32_t (&off)[NI / NW]) {
+#pragma unroll
+    for (int j = 0; j < NI / NW; ++j) {
+      const int blk = wv * (NI / NW) + j;
+      const int r = blk * RPI + lane / CH, cs = lane % CH;
+      off[j] = (uint32_t)r * pitch + (uint32_t)(swz(r, cs) * 16);
+    }
+  }
+  template <int NW>
+  __device__ static __forceinline__ void issue_whole(const void* tile_base, const uint32_t (&off)[NI / NW],
+                                                     uint32_t lds_tile, int wv) {
+#pragma unroll
+    for (int j = 0; j < NI / NW; ++j) dma_1k_to(tile_base, off[j], lds_tile + (uint32_t)(wv * (NI / NW) + j) * 1024u);
   }
 };
 // Workgroup barrier without the full fence of __syncthreads (which would also wait for the
@@ -208,6 +240,7 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
   __shared__ float part[2][HPW][WPH][TN];
   const int g = blockIdx.z;
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
+  const int wvs = wave_index();                     // the same as a scalar, for the copies' addresses
   const int hw = wv / WPH, pr = wv % WPH;           // head inside the workgroup, row block pair
   const int hloc = blockIdx.y * HPW + hw;
   const int h = g * pb.G + (hloc < pb.G ? hloc : 0);
@@ -218,7 +251,16 @@ __global__ __launch_bounds__(512) void k_vv_pipe(Prob pb, const uint16_t* __rest
   const int t0 = blockIdx.x * tiles_per_wg;
   const int t1 = min(NT, t0 + tiles_per_wg);
   if (t0 >= t1) return;
-  auto issue_tile = [&](int t) { Ring::template issue<NW>(vg, pitch, min(t, t1 - 1) * TN, pb.L, Vs[t & 3], wv, l); };
+  uint32_t voff[NG];
+  Ring::template plan<NW>(pitch, wvs, l, voff);
+  const uint32_t vs_base = lds_addr(&Vs[0][0]);
+  auto issue_tile = [&](int t) {
+    const int kb = min(t, t1 - 1) * TN;
+    if (kb + TN <= pb.L)
+      Ring::template issue_whole<NW>((const char*)vg + (uint64_t)kb * pitch, voff, vs_base + (uint32_t)(t & 3) * (TN * D * 2), wvs);
+    else
+      Ring::template issue<NW>(vg, pitch, kb, pb.L, Vs[t & 3], wv, l);
+  };
   issue_tile(t0);
   issue_tile(t0 + 1);
 
@@ -383,7 +425,7 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[4][TN * D];
 
   const int s = blockIdx.x, g = blockIdx.z;
-  const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
+  const int l = threadIdx.x & 63, wv = wave_index(), rr = l & 31, hf = l >> 5;
   const RowInfo ri = row_info(pb, g, blockIdx.y * NW + wv, l, log2iw);
   const uint16_t* kg = k + (int64_t)g * pb.kv_sh;
   const uint16_t* vg = v + (int64_t)g * pb.kv_sh;
@@ -392,10 +434,20 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
   const int kend = min(pb.L, kbeg + kps);
   const int ntiles = kend > kbeg ? (kend - kbeg + TN - 1) / TN : 0;
   const uint32_t pitch = (uint32_t)pb.kv_st * 2u;
+  uint32_t koff[NG / 2], voff[NG / 2];
+  RingK::template plan<NW>(pitch, wv, l, koff);
+  RingV::template plan<NW>(pitch, wv, l, voff);
+  const uint32_t ks_base = lds_addr(&Ks[0][0]), vs_base = lds_addr(&Vs[0][0]);
   auto issue_tile = [&](int t) {
     const int kb = kbeg + min(t, ntiles - 1) * TN;   // past the end: harmless repeat into a free slot
-    RingK::template issue<NW>(kg, pitch, kb, pb.L, Ks[t % 3], wv, l);
-    RingV::template issue<NW>(vg, pitch, kb, pb.L, Vs[t & 3], wv, l);
+    if (kb + TN <= pb.L) {
+      const uint64_t tb = (uint64_t)kb * pitch;
+      RingK::template issue_whole<NW>((const char*)kg + tb, koff, ks_base + (uint32_t)(t % 3) * (TN * D * 2), wv);
+      RingV::template issue_whole<NW>((const char*)vg + tb, voff, vs_base + (uint32_t)(t & 3) * (TN * D * 2), wv);
+    } else {
+      RingK::template issue<NW>(kg, pitch, kb, pb.L, Ks[t % 3], wv, l);
+      RingV::template issue<NW>(vg, pitch, kb, pb.L, Vs[t & 3], wv, l);
+    }
   };
   if (ntiles > 0) {
     issue_tile(0);
@@ -742,6 +794,7 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
 
   const int g = blockIdx.z;
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6, rr = l & 31, hf = l >> 5;
+  const int wvs = wave_index();                     // the same as a scalar, for the copies' addresses
   const int wb = blockIdx.y * NW + wv;              // block of IW window positions
   const uint16_t* kg = k + (int64_t)g * pb.kv_sh;
   const uint16_t* vg = v + (int64_t)g * pb.kv_sh;
@@ -755,10 +808,14 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
   auto key_of = [&](int j) { return min((int)((double)(j >> 4) * fa.step) & ~3, pb.P - 16) + (j & 15); };
 
   // vv copy of this wavefront: block wv % NVB (duplicates write identical bytes)
-  const int vb = wv % NVB;
+  const int vb = wvs % NVB;
   const float* vv_g = o.vv + (int64_t)g * pb.G * ldv;                    // vv rows of this group
   const uint32_t vv_row = (uint32_t)min(4 * vb + (l >> 4), pb.G - 1) * (uint32_t)ldv;
   const uint32_t pitch = (uint32_t)pb.kv_st * 2u;
+  uint32_t kvoff[(NG - 1) / 2];
+  Ring::template plan<NW>(pitch, wvs, l, kvoff);
+  const uint32_t vvoff = (vv_row + 4u * (uint32_t)(l & 15)) * 4u;
+  const uint32_t ks_base = lds_addr(&Ks[0][0]), vs_base = lds_addr(&Vs[0][0]), vv_base = lds_addr(&vvs[0][0][0]);
   auto issue_tile = [&](int t) {
     const int tt = min(t, t1 - 1);                  // past the end: harmless repeat into a free slot
     const int kb = tt * TN;
@@ -766,6 +823,12 @@ __global__ __launch_bounds__(512) void k_score_pipe(Prob pb, const uint16_t* __r
       Ring::template issue_rows<NW>(kg, pitch, [&](int r) { return key_of(kb + r); }, Ks[t % 3], wv, l);
       Ring::template issue_rows<NW>(vg, pitch, [&](int r) { return key_of(kb + r); }, Vs[t % 3], wv, l);
       dma_1k(vv_g, (vv_row + (uint32_t)key_of(kb + 4 * (l & 15))) * 4u, &vvs[t & 3][4 * vb][0]);
+    } else if (kb + TN <= pb.L && kb + TN <= ldv) {   // whole tile, no clamp anywhere
+      const uint64_t tb = (uint64_t)kb * pitch;
+      const uint32_t slot = (uint32_t)(t % 3) * (TN * D * 2);
+      Ring::template issue_whole<NW>((const char*)kg + tb, kvoff, ks_base + slot, wvs);
+      Ring::template issue_whole<NW>((const char*)vg + tb, kvoff, vs_base + slot, wvs);
+      dma_1k_to(vv_g + kb, vvoff, vv_base + (uint32_t)((t & 3) * GV + 4 * vb) * (TN * 4));
     } else {
       Ring::template issue<NW>(kg, pitch, kb, pb.L, Ks[t % 3], wv, l);
       Ring::template issue<NW>(vg, pitch, kb, pb.L, Vs[t % 3], wv, l);
