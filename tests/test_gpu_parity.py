@@ -179,6 +179,9 @@ def test_tiny_config_full_path(rk, oracle_mod):
     (4, 1, 128, 200, 1, 50, "bf16"),     # a single window query
     (4, 2, 64, 64 + 4096, 64, 65, "bf16"),   # budget of one prefix token, prefix = one scan chunk exactly
     (2, 2, 128, 3 + 4097, 3, 4100, "f32"),   # budget = everything, prefix one past a scan chunk
+    (4, 2, 128, 900, 100, 200, "bf16"),      # window above 64: two row blocks per KV head, two 64-row blocks in the scan
+    (6, 1, 64, 1500, 200, 400, "bf16"),      # G = 6 padded to 8 and a long window: seven row blocks
+    (2, 1, 64, 1300, 300, 500, "f32"),       # long window through the FP32 kernels
 ])
 def test_edge_shapes_whole_path(rk, oracle_mod, Hq, Hkv, d, L, W, B, dtype):
     """Shapes at the edges of the tiling (one prefix token, prefixes around a 64-key tile and a
