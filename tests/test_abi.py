@@ -78,6 +78,13 @@ def test_error_codes_without_launch(rk):
     assert L.restkv_select(ctypes.byref(good(rk, budget=1025)), one, one, None, 0, None) == -1
     bad_ld = good(rk, ld_score=100)
     assert L.restkv_smooth(ctypes.byref(bad_ld), one, None, one, None, None, one, 1 << 20, None) == -1
+    # the streaming reference: null, odd sizes, misaligned pointers; nothing to move is not an error
+    assert L.restkv_stream_reference(None, 32, one, 16, None) == -1
+    assert L.restkv_stream_reference(one, 32, None, 16, None) == -1
+    assert L.restkv_stream_reference(one, 24, one, 16, None) == -1
+    assert L.restkv_stream_reference(one, 32, one, 20, None) == -1
+    assert L.restkv_stream_reference(ctypes.c_void_p(264), 32, one, 16, None) == -1
+    assert L.restkv_stream_reference(None, 0, None, 0, None) == 0
     for code in (0, -1, -2, -3, -4, -99):
         assert len(rk.strerror(code)) > 0
 
