@@ -35,7 +35,9 @@ inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
 //   part_z    sum over the included keys of 2^(logit - ref) * v
 // A split keeps a key out when, on arrival, it is the largest so far and holds more than 1/9
 // of the mass seen so far (always true for a key that ends with more than 1/9 of the total).
-// part_ref never follows a kept-out key, only keys that are part of the sums.
+// part_ref never follows a kept-out key, only keys that are part of the sums (on the matrix-core
+// path: exactly the logit of a key that was heavy among the others when it arrived, so that its
+// bf16 weight is exact).
 // The merge keeps out the excluded key that is the overall maximum (if any) and folds every
 // other excluded key back in.  With a key kept out ("champion", weight A* = 1/l):
 //   l = 1 + l_rest, z = (v* + z_rest)/l, u = z M_h, zz = u.z, and the champion's indicator

@@ -567,22 +567,28 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
       // A key is kept out of the sums only if, on arrival, it is the largest so far AND would
       // hold more than 1/9 of the mass seen so far; such keys are rare after the first tile, so
       // the expensive part of the bookkeeping (index search, folding the previous kept-out key
-      // back in) almost never runs.  The reference of the exponentials follows, lazily, the
-      // largest logit that is PART of the sums: a kept-out key may be any distance above the
-      // others without the others' sums losing anything.
+      // back in) almost never runs.  The weights that enter the P.V product are rounded to bf16;
+      // that costs nothing where a key holds a small share of the sums, and would cost up to
+      // 2^-9 of a heavy key's share.  So the reference of the exponentials is always a logit that
+      // is PART of the sums (never the kept-out key's, which may be any distance above), it is
+      // moved exactly onto the largest joining logit of a tile whenever that key is heavy among
+      // the others (its weight is then exactly 1, which bf16 holds), and lazily otherwise.
       const bool newmax = tm > mall;
-      bool excl_here = false;
-      // (no key of the tile is further ahead of the reference than the tile maximum)
-      if (__ballot(newmax || (tm - mref) * c2 > RESCALE_TH) != 0ull) {
+      const float pl = __builtin_amdgcn_exp2f((tm - mref) * c2);   // tile maximum in the current frame (inf on the first tile)
+      mall = fmaxf(mall, tm);
+      // Nothing to do unless the reference has to move or the tile maximum may be heavy: lsum is
+      // this lane's share of the row's sum, so the comparison is a necessary condition for both
+      // "kept out" and "heavy", which are settled below.
+      if (__ballot((tm - mref) * c2 > RESCALE_TH || pl * 8.0f > lsum) != 0ull) {
+        const float oth = xhalf_sum(lsum);
         bool dominant = false;
         if (newmax) {
-          const float pstar = __builtin_amdgcn_exp2f((tm - mref) * c2);      // inf on the first tile
-          float total = xhalf_sum(lsum);
+          float total = oth;
           if (nx >= 0) total += __builtin_amdgcn_exp2f((mx - mref) * c2);
           // total = inf: the key kept out so far is the whole mass in FP32, and tm is above it
-          dominant = pstar * 8.0f > total || total == INFINITY;
+          dominant = pl * 8.0f > total || total == INFINITY;
         }
-        float tref = tm;                 // largest logit that joins the sums at this tile
+        float tinc = tm;                 // largest logit of the tile that joins the sums
         int cand = INT_MAX;
         if (__ballot(dominant) != 0ull) {
           if (dominant) {
@@ -593,40 +599,34 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
                 if (sacc[mb][j] == tm) cand = min(cand, kb + 32 * mb + cidx(j, hf));
           }
           cand = xhalf_min(cand);
-          // Where the new kept-out key is at most 64 binary orders above a logit that is part of
-          // the sums, the reference may follow it as it follows any maximum (tref = tm): the sums
-          // keep every bit that matters.  Further up the reference becomes the largest logit that
-          // really joins the sums.  The logit it is measured against: the reference so far; on
-          // the first tile, the second largest of the row's eight partial maxima (no larger than
-          // the largest logit that joins).
-          float base = mref;
-          if (t == 0) {
-            const float a1 = fmaxf(tq[0], tq[1]), a2 = fminf(tq[0], tq[1]);
-            const float b1 = fmaxf(tq[2], tq[3]), b2 = fminf(tq[2], tq[3]);
-            const float l1 = fmaxf(a1, b1), l2 = fmaxf(fminf(a1, b1), fmaxf(a2, b2));   // the lane's top two
-            const auto r1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(l1), __float_as_uint(l1), false, false);
-            base = fmaxf(fminf(__uint_as_float(r1[0]), __uint_as_float(r1[1])), xhalf_max(l2));
-          }
-          const bool far = dominant && !((tm - base) * c2 <= 64.f);
-          if (__ballot(far) != 0ull) {
-            float ti = -INFINITY;        // the tile without its new kept-out key
-            if (far) {
+          // the new kept-out key leaves the tile: its weight below is exp2(-inf) = 0
+          const int cz = dominant ? cand : -1;
 #pragma unroll
-              for (int mb = 0; mb < 2; ++mb)
+          for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j)
-                  ti = (kb + 32 * mb + cidx(j, hf)) == cand ? ti : fmaxf(ti, sacc[mb][j]);
-            }
-            ti = xhalf_max(ti);
-            if (far) {
-              if (nx >= 0) ti = fmaxf(ti, mx);               // the key kept out so far joins too
-              // nothing joins (a tile with one visible key): any finite reference will do
-              tref = ti == -INFINITY ? (mref == -INFINITY ? tm : mref) : ti;
-            }
+            for (int j = 0; j < 16; ++j)
+              sacc[mb][j] = (kb + 32 * mb + cidx(j, hf)) == cz ? -INFINITY : sacc[mb][j];
+          float u[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            u[c] = fmaxf(fmaxf(sacc[0][c], sacc[0][4 + c]), sacc[0][8 + c]);
+            u[c] = fmaxf(fmaxf(u[c], sacc[0][12 + c]), sacc[1][c]);
+            u[c] = fmaxf(fmaxf(u[c], sacc[1][4 + c]), sacc[1][8 + c]);
+            u[c] = fmaxf(u[c], sacc[1][12 + c]);
           }
-          excl_here = true;
+          tinc = xhalf_max(fmaxf(fmaxf(u[0], u[1]), fmaxf(u[2], u[3])));
         }
-        if ((tref - mref) * c2 > RESCALE_TH) {
+        // Where nothing of the tile joins (one visible key, and it is kept out) the reference
+        // stays; a row without any reference yet takes the kept-out key's logit (any finite
+        // value will do: its sums are empty).
+        float tref = mref;
+        if (tinc == -INFINITY) {
+          if (mref == -INFINITY) tref = tm;
+        } else {
+          const float pinc = tinc == tm ? pl : __builtin_amdgcn_exp2f((tinc - mref) * c2);   // inf without a reference
+          if (pinc * 8.0f > oth || (tinc - mref) * c2 > RESCALE_TH) tref = tinc;
+        }
+        if (tref != mref) {
           const float f = __builtin_amdgcn_exp2f((mref - tref) * c2);   // first tile: 2^-inf = 0
           lsum *= f;
 #pragma unroll
@@ -636,8 +636,8 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
           mref = tref;
         }
         if (dominant) {
-          if (nx >= 0) {               // the key kept out so far joins the running sums
-            const float w = __builtin_amdgcn_exp2f((mx - mref) * c2);   // at most 2^RESCALE_TH
+          if (nx >= 0) {               // the key kept out so far joins the running sums, in FP32
+            const float w = __builtin_amdgcn_exp2f((mx - mref) * c2);
             if (hf == 0) lsum += w;
             const uint16_t* vr = vg + (int64_t)nx * pb.kv_st;
 #pragma unroll
@@ -654,21 +654,10 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
           mx = tm;
           nx = cand;
         }
-        mall = fmaxf(mall, tm);
       }
       // ---- weights relative to the reference ----
       const float nm = -mref * c2;
-      if (excl_here) {                 // wave-uniform: this tile holds a key that is being kept out
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][j], c2, nm));
-            if ((kb + 32 * mb + cidx(j, hf)) == nx) p = 0.f;
-            lsum += p;
-            pv[mb][j >> 3][j & 7] = (__bf16)p;
-          }
-      } else {
+      {
         float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)

@@ -189,14 +189,19 @@ def test_edge_shapes_whole_path(rk, oracle_mod, Hq, Hkv, d, L, W, B, dtype):
     score against the oracle; every later stage exactly, on the GPU's own FP32 output of the stage
     before (index sums, window, selection, gather)."""
     w = workloads.small_case(Hq=Hq, Hkv=Hkv, d=d, L=L, W=W, B=B, dtype=dtype, D=2 * d, seed=31)
+    _score_against_oracle_then_every_stage_exactly(rk, oracle_mod, w, "edge shape")
+
+
+def _score_against_oracle_then_every_stage_exactly(rk, oracle_mod, w, what):
     q, k, v = workloads.make_qkv(w)
     wo = workloads.make_wo(w)
     got = run_gpu_layer(rk, w, q, k, v, wo)
     ref = oracle_score(oracle_mod, w, q, k, v, wo)
     kf, vf = k.float().numpy(), v.float().numpy()
-    for g in range(Hkv):
+    W, B = w.window, w.budget
+    for g in range(w.n_kv_heads):
         Ig, tol = ref[g]
-        assert_score_close(got["score"][g], Ig, tol, f"edge shape head {g}")
+        assert_score_close(got["score"][g], Ig, tol, f"{what} head {g}")
         sm = oracle_mod.smooth_head(got["score"][g], w.alpha, w.beta, w.base_window, True, w.budget)
         np.testing.assert_allclose(got["ema"][g], sm["ema"], rtol=1e-5, atol=1e-30)
         if W >= 2:
@@ -207,6 +212,27 @@ def test_edge_shapes_whole_path(rk, oracle_mod, Hq, Hkv, d, L, W, B, dtype):
         np.testing.assert_array_equal(got["idx"][g], oracle_mod.select(got["final"][g].astype(np.float64), W, B))
         assert np.array_equal(got["k_out"][g], kf[g][got["idx"][g]])
         assert np.array_equal(got["v_out"][g], vf[g][got["idx"][g]])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_shapes_whole_path(rk, oracle_mod, seed):
+    """Shapes, group sizes, windows, budgets, precisions, input structures and smoothing parameters
+    drawn from a seeded generator (ragged everywhere: nothing is a multiple of a tile on purpose):
+    the same checks as the edge shapes."""
+    r = np.random.default_rng(1000 + seed)
+    G = int(r.choice([1, 2, 3, 4, 5, 8, 12]))
+    Hkv = int(r.integers(1, 4)) if G <= 4 else 1
+    d = int(r.choice([64, 128]))
+    W = int(r.choice([1, 2, 5, 13, 32, 47, 64, 90]))
+    if G * W > 1024:
+        W = 1024 // G
+    L = W + int(r.integers(1, 2600))
+    B = W + int(r.integers(1, L - W + 1))
+    w = workloads.small_case(Hq=G * Hkv, Hkv=Hkv, d=d, L=L, W=W, B=B, dtype=str(r.choice(["bf16", "bf16", "f32"])),
+                             D=int(r.choice([d // 2, d, 3 * d])), alpha=float(r.choice([0.05, 0.3, 0.8, 1.0])),
+                             k=int(r.choice([1, 3, 5, 21])), beta=float(r.choice([8.0, 50.0, 2000.0])),
+                             structure=str(r.choice(["plain", "sinks", "drift", "lowrank"])), seed=2000 + seed)
+    _score_against_oracle_then_every_stage_exactly(rk, oracle_mod, w, f"random shape {seed} {w}")
 
 
 def test_llama_8k_config_score_and_selection(rk, oracle_mod):
