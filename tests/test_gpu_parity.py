@@ -214,7 +214,7 @@ def _score_against_oracle_then_every_stage_exactly(rk, oracle_mod, w, what):
         assert np.array_equal(got["v_out"][g], vf[g][got["idx"][g]])
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", list(range(24)) + [184])     # 184: scores at the edge of FP32's normal range
 def test_seeded_random_shapes_whole_path(rk, oracle_mod, seed):
     """Shapes, group sizes, windows, budgets, precisions, input structures and smoothing parameters
     drawn from a seeded generator (ragged everywhere: nothing is a multiple of a tile on purpose):
