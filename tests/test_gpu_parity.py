@@ -863,6 +863,51 @@ def test_variant_whole_path_llama_8k(rk, oracle_mod):
         assert np.array_equal(got["k_out"][g], kn[g][got["idx"][g]])
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_seeded_random_variants_whole_path(rk, oracle_mod, seed):
+    """Random combinations of the variant switches (indicator, group reduction, temporal and
+    spatial smoothing type, adaptive window) on random ragged shapes: raw score against the oracle,
+    every later stage exactly on the GPU's own output of the stage before."""
+    r = np.random.default_rng(9000 + seed)
+    G = int(r.choice([1, 2, 3, 4, 8, 16]))
+    Hkv = int(r.integers(1, 3)) if G <= 4 else 1
+    d = int(r.choice([64, 128]))
+    W = int(r.choice([1, 4, 13, 32, 64]))
+    L = W + int(r.integers(1, 5000))
+    B = W + int(r.integers(1, L - W + 1))
+    ind = str(r.choice(["reconstruction", "attention", "value_norm"]))
+    grp = str(r.choice(["mean", "max"]))
+    tmode = str(r.choice(["ema", "mean", "inv_ema"]))
+    pool = str(r.choice(["avg", "max"]))
+    adaptive = bool(r.integers(0, 2)) and pool == "avg"
+    w = workloads.small_case(Hq=G * Hkv, Hkv=Hkv, d=d, L=L, W=W, B=B, dtype=str(r.choice(["bf16", "bf16", "f32"])),
+                             D=int(r.choice([d, 2 * d])), alpha=float(r.choice([0.05, 0.3, 1.0])),
+                             k=int(r.choice([1, 3, 5, 21])), beta=float(r.choice([8.0, 300.0, 2000.0])),
+                             structure=str(r.choice(["plain", "sinks", "drift", "lowrank"])), seed=9500 + seed)
+    var = {"reconstruction": 0, "attention": rk.RESTKV_IND_ATTENTION, "value_norm": rk.RESTKV_IND_VALUE_NORM}[ind]
+    var |= rk.RESTKV_GROUP_MAX if grp == "max" else 0
+    var |= {"ema": 0, "mean": rk.RESTKV_TEMPORAL_MEAN, "inv_ema": rk.RESTKV_TEMPORAL_INV_EMA}[tmode]
+    var |= rk.RESTKV_POOL_MAX if pool == "max" else 0
+    tag = f"variant case {seed}: {ind}, group {grp}, {tmode}, pool {pool}, adaptive {adaptive}, {w}"
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w) if ind == "reconstruction" else None
+    got = run_gpu_layer(rk, w, q, k, v, wo, variant=var, adaptive=adaptive)
+    qn, kn, vn = (t.float().numpy() for t in (q, k, v))
+    ref = oracle_score(oracle_mod, w, q, k, v, wo, group=grp) if ind == "reconstruction" else None
+    for g in range(Hkv):
+        if ref is not None:
+            assert_score_close(got["score"][g], ref[g][0], ref[g][1], tag)
+        else:
+            Ig = oracle_mod.score_head(qn[g * G:(g + 1) * G], kn[g], vn[g], None, W, 1 / np.sqrt(d), indicator=ind, group=grp)
+            np.testing.assert_allclose(got["score"][g], Ig, rtol=RTOL, atol=1e-30, err_msg=tag)
+        sm = oracle_mod.smooth_head(got["score"][g], w.alpha, w.beta, w.base_window, adaptive, w.budget, tmode, pool)
+        np.testing.assert_allclose(got["ema"][g], sm["ema"], rtol=1e-5, atol=1e-30, err_msg=tag)
+        assert tuple(got["aws_info"][g]) == (sm["w_s"], sm["gamma"]), tag
+        np.testing.assert_allclose(got["final"][g], sm["final"], rtol=2e-5, atol=1e-30, err_msg=tag)
+        np.testing.assert_array_equal(got["idx"][g], oracle_mod.select(got["final"][g].astype(np.float64), W, B), err_msg=tag)
+        assert np.array_equal(got["k_out"][g], kn[g][got["idx"][g]]), tag
+
+
 # ------------------------------------------------------------------ statistics from the caller's attention kernel
 @pytest.mark.parametrize("name", ["bf16_d128_splits", "bf16_g3", "bf16_mha", "f32_d64_ragged", "bf16_g16",
                                   "bf16_sinks_g8"])
