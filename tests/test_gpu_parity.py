@@ -940,6 +940,28 @@ def test_score_from_attention_statistics(rk, oracle_mod, name):
     assert seen > 0.99 * got.size
 
 
+def test_score_from_attention_one_key_holds_everything(rk):
+    """The statistics-in entry keeps no key out: with a key that holds all of every row's attention
+    (A = 1 in FP32) its own score has no meaning (documented), but every score stays finite and
+    non-negative, and the other keys' scores are 0 or tiny."""
+    w = _case("bf16_mha")
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    k = k.clone()
+    k[:, 37] = (q[:, -1].float() * 40.0).to(k.dtype)          # one key aligned with the queries' direction
+    k[:, 37] += (q.float().mean(dim=1) * 40.0).to(k.dtype)
+    out, lse = attention_statistics(q, k, v, w.window)
+    p = params_for(rk, w)
+    gram = torch.empty((w.n_q_heads, w.head_dim, w.head_dim), dtype=torch.float32, device="cuda")
+    rk.restkv_prepare_wo(p, wo.cuda(), gram)
+    buf = rk.alloc_layer_buffers(p, q.dtype, "cuda")
+    rk.restkv_score_from_attention(p, q.cuda(), k.cuda(), v.cuda(), gram, out.cuda(), lse.cuda(), buf.score,
+                                   buf.workspace)
+    torch.cuda.synchronize()
+    got = buf.score[..., :w.prefix].cpu().numpy()
+    assert np.all(np.isfinite(got)) and np.all(got >= 0)
+
+
 def test_score_from_attention_full_size(rk, oracle_mod):
     """The same at the benchmark configuration (drift_128k, one layer, two KV heads against the oracle);
     the statistics are computed with the library softmax in FP64 on the GPU."""
