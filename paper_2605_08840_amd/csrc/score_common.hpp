@@ -33,8 +33,8 @@ inline ScorePtrs score_ptrs(char* ws, const ScoreWs& lay) {
 //   part_ref  reference the sums are relative to
 //   part_l    sum over the included keys of 2^(logit - ref)
 //   part_z    sum over the included keys of 2^(logit - ref) * v
-// A split keeps a key out when, on arrival, it is the largest so far and holds more than 1/9
-// of the mass seen so far (always true for a key that ends with more than 1/9 of the total).
+// A split keeps a key out when, on arrival, it is the largest so far and holds more than half
+// of the mass seen so far (always true for a key that ends with more than half of the total).
 // part_ref never follows a kept-out key, only keys that are part of the sums (on the matrix-core
 // path: exactly the logit of a key that was heavy among the others when it arrived, so that its
 // bf16 weight is exact).

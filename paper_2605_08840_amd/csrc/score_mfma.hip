@@ -564,10 +564,10 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
       }
       float tm = xhalf_max(fmaxf(fmaxf(tq[0], tq[1]), fmaxf(tq[2], tq[3])));
 
-      // A key is kept out of the sums only if, on arrival, it is the largest so far AND would
-      // hold more than 1/9 of the mass seen so far; such keys are rare after the first tile, so
-      // the expensive part of the bookkeeping (index search, folding the previous kept-out key
-      // back in) almost never runs.  The weights that enter the P.V product are rounded to bf16;
+      // A key is kept out of the sums only if, on arrival, it is the largest so far AND holds
+      // more than half of the mass seen so far (what a key that ends with A > 1/2 always does);
+      // such keys are rare after the first tile, so the expensive part of the bookkeeping (index
+      // search, folding the previous kept-out key back in) almost never runs.  The weights that enter the P.V product are rounded to bf16;
       // that costs nothing where a key holds a small share of the sums, and would cost up to
       // 2^-9 of a heavy key's share.  So the reference of the exponentials is always a logit that
       // is PART of the sums (never the kept-out key's, which may be any distance above), it is
@@ -586,7 +586,7 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
           float total = oth;
           if (nx >= 0) total += __builtin_amdgcn_exp2f((mx - mref) * c2);
           // total = inf: the key kept out so far is the whole mass in FP32, and tm is above it
-          dominant = pl * 8.0f > total || total == INFINITY;
+          dominant = pl > total || total == INFINITY;
         }
         float tinc = tm;                 // largest logit of the tile that joins the sums
         int cand = INT_MAX;
