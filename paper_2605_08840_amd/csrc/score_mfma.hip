@@ -626,6 +626,9 @@ __global__ __launch_bounds__(512) void k_attn_pipe(Prob pb, const uint16_t* __re
           const float pinc = tinc == tm ? pl : __builtin_amdgcn_exp2f((tinc - mref) * c2);   // inf without a reference
           if (pinc * 8.0f > oth || (tinc - mref) * c2 > RESCALE_TH) tref = tinc;
         }
+        // The key kept out so far joins the sums too (in FP32, below): the reference may not
+        // stay far under it, however far it lies above the rest.
+        if (dominant && nx >= 0 && (mx - tref) * c2 > RESCALE_TH) tref = mx;
         if (tref != mref) {
           const float f = __builtin_amdgcn_exp2f((mref - tref) * c2);   // first tile: 2^-inf = 0
           lsum *= f;

@@ -139,6 +139,33 @@ def test_score_key_far_above_the_rest(rk, oracle_mod, dtype, spikes):
         assert np.all(np.abs(got["score"][g][:, top] - Ig[:, top]) <= RTOL * Ig[:, top])
 
 
+@pytest.mark.parametrize("spikes", [((10, 150.0), (100, 400.0)), ((100, 400.0), (10, 150.0)), ((5, 60.0), (70, 130.0), (140, 300.0))])
+def test_score_stacked_spikes_inside_one_key_split(rk, oracle_mod, spikes):
+    """Keys far above the rest that follow one another inside ONE key split of the attention pass
+    (8 KV heads and 4500 keys: 32 splits of three tiles): each is kept out when it arrives, and
+    the one it supersedes joins the sums although it lies tens to hundreds of nats above every
+    other key in them."""
+    w = workloads.small_case(Hq=8, Hkv=8, d=128, L=4500, W=16, B=64, dtype="bf16", D=128, seed=29)
+    q, k, v = workloads.make_qkv(w)
+    wo = workloads.make_wo(w)
+    d = w.head_dim
+    e = torch.zeros(d)
+    e[3] = 1.0
+    q = (q.float() + 8.0 * e).to(q.dtype)
+    k = k.float().clone()
+    for n, gap in spikes:
+        k[:, n, :] = (gap * d ** 0.5 / 8.0) * e
+    k = k.to(q.dtype)
+    got = run_gpu_layer(rk, w, q, k, v, wo)
+    assert np.all(np.isfinite(got["score"])) and np.all(got["score"] >= 0)
+    ref = oracle_score(oracle_mod, w, q, k, v, wo, with_amax=True)
+    top = max(spikes, key=lambda t: t[1])[0]
+    for g, (Ig, tol, amax) in ref.items():
+        assert amax[:, top].min() > 0.999999 and Ig[:, top].min() > 0
+        assert_score_close(got["score"][g], Ig, tol, f"spikes {spikes} head {g}")
+        assert np.all(np.abs(got["score"][g][:, top] - Ig[:, top]) <= RTOL * Ig[:, top])
+
+
 def test_gram_matches_float64_product(rk):
     w = _case("bf16_mha")
     wo = workloads.make_wo(w)
