@@ -36,6 +36,13 @@ class Workload:
     structure: str        # "plain" | "sinks" | "lowrank" | "drift"
     seed: int
 
+    def __post_init__(self):
+        # The library's parameter block carries alpha and beta as FP32.  The workload holds exactly
+        # those values, so that every consumer sees the same numbers (1 - alpha differs by 1.3e-5
+        # between 0.999 and its nearest FP32 neighbour).
+        for name in ("alpha", "beta"):
+            object.__setattr__(self, name, float(torch.tensor(getattr(self, name), dtype=torch.float32).item()))
+
     @property
     def group(self) -> int:
         return self.n_q_heads // self.n_kv_heads
