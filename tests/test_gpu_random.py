@@ -148,3 +148,62 @@ def test_random_smoothing_and_selection_stage(rk, oracle_mod, seed):
         np.testing.assert_allclose(fin[g], want, rtol=2e-5, atol=1e-30, err_msg=tag)
         np.testing.assert_array_equal(idx[g, :Bg], oracle_mod.select(fin[g].astype(np.float64), W, Bg), err_msg=tag)
         assert np.all(idx[g, Bg:] == -1), tag
+
+
+GUARD = 4096          # bytes of sentinel on either side of every output buffer
+
+
+def _carved_buffers(rk, p, dtype):
+    """The layer's output buffers and workspace as views into ONE byte pool, each between two
+    guard zones filled with a sentinel; returns (LayerBuffers, pool, list of guard slices)."""
+    Hkv, W, B, d = p.n_kv_heads, p.window, p.budget, p.head_dim
+    ld = p.ld_score if p.ld_score else p.seq_len - p.window
+    esz = 2 if dtype == torch.bfloat16 else 4
+    specs = [("score", torch.float32, (Hkv, W, ld)), ("ema", torch.float32, (Hkv, ld)), ("final", torch.float32, (Hkv, ld)),
+             ("aws_info", torch.int32, (Hkv, 2)), ("aws_d", torch.float64, (Hkv, 2)), ("idx", torch.int32, (Hkv, B)),
+             ("k_out", dtype, (Hkv, B, d)), ("v_out", dtype, (Hkv, B, d)),
+             ("workspace", torch.uint8, (max(int(rk.restkv_workspace_bytes(p)), 256),))]
+    sizes = {torch.float32: 4, torch.int32: 4, torch.float64: 8, torch.uint8: 1, dtype: esz}
+    off, place = GUARD, []
+    for name, dt, shape in specs:
+        nbytes = int(np.prod(shape)) * sizes[dt]
+        place.append((name, dt, shape, off, nbytes))
+        off = (off + nbytes + GUARD + 255) // 256 * 256
+    pool = torch.full((off + GUARD,), 0xA5, dtype=torch.uint8, device="cuda")
+    views, guards, prev_end = {}, [], 0
+    for name, dt, shape, o, nbytes in place:
+        views[name] = pool[o:o + nbytes].view(dt).view(shape)
+        guards.append((prev_end, o))
+        prev_end = o + nbytes
+    guards.append((prev_end, pool.numel()))
+    return rk.LayerBuffers(**views), pool, guards
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_write_nothing_outside_their_buffers(rk, seed):
+    """Every output buffer and the workspace sit between guard zones in one pool: after the whole
+    path (every third case through the fused call, with a long enough prefix) no guard byte has
+    changed."""
+    r = np.random.default_rng(80000 + seed)
+    fused = seed % 3 == 0
+    G = int(r.choice([4, 8])) if fused else int(r.choice([1, 2, 3, 4, 8, 16]))
+    Hkv = int(r.integers(1, 4)) if G <= 4 else 1
+    d = int(r.choice([64, 128]))
+    W = int(r.choice([1, 5, 16, 32, 64])) if not fused else int(r.choice([8, 32]))
+    L = W + (int(r.integers(32768, 50000)) if fused else int(r.integers(1, 9000)))
+    B = W + int(r.integers(1, min(L - W, 3000) + 1))
+    dtype = "bf16" if fused else str(r.choice(["bf16", "f32"]))
+    w = workloads.small_case(Hq=G * Hkv, Hkv=Hkv, d=d, L=L, W=W, B=B, dtype=dtype, D=d, beta=float(r.choice([8.0, 2000.0])),
+                             k=int(r.choice([1, 5, 21])), structure=str(r.choice(["plain", "sinks", "drift", "lowrank"])),
+                             seed=81000 + seed)
+    q, k, v = workloads.make_qkv(w, 0, "cuda")
+    wo = workloads.make_wo(w, 0, "cuda")
+    p = params_for(rk, w)
+    gram = torch.empty((w.n_q_heads, d, d), dtype=torch.float32, device="cuda")
+    rk.restkv_prepare_wo(p, wo, gram)
+    buf, pool, guards = _carved_buffers(rk, p, q.dtype)
+    rk.evict_layer(p, q, k, v, gram, buf, fused=fused)
+    torch.cuda.synchronize()
+    for a, b in guards:
+        assert bool((pool[a:b] == 0xA5).all()), f"guard bytes [{a}, {b}) changed: {w} fused={fused}"
+    assert int(buf.idx.min()) >= 0 and int(buf.idx.max()) < L
